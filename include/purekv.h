@@ -1,0 +1,183 @@
+/*
+ * purekv.h -- C ABI of the PureKV hot path for AMD MI355X (gfx950).
+ *
+ * The library implements, on one GPU, the data-parallel part of PureKV:
+ *   - ST-SpAttn prefill attention over F frames x P patches of video tokens followed by
+ *     T text tokens (paper Sec. 3.2), and dense causal attention for the low layers (Eq. 1);
+ *   - the recent-window column-sum importance C^low (Eq. 2);
+ *   - the V-norm weighting S = C * ||V|| (Eq. 3 for the low layer, Eq. 4 for the high layers that
+ *     reuse C^low with their own V) and the per-KV-head selection "recent w + top h" (Sec. 3.1);
+ *   - the gather of the kept K/V rows into a compact cache;
+ *   - single-token decode attention against that compact cache.
+ *
+ * Conventions
+ *   - Token order: video tokens frame-major (index i < F*P: frame i / P, patch i % P), then text.
+ *     N = F*P + T.  P = patch_h * patch_w; "the corresponding token of the previous frame" is i - P.
+ *   - Tensors are packed, row-major, innermost dimension head_dim contiguous:
+ *       Q [Hq, N, d], K and V [Hkv, N, d], O [Hq, N, d]: bf16.   Query head hq reads KV head hq / (Hq/Hkv).
+ *   - Every data pointer is a DEVICE pointer owned by the caller (16-byte aligned), unless the
+ *     argument is documented as a host pointer.  `stream` is a hipStream_t passed as void* (NULL = default
+ *     stream).  Calls enqueue work on `stream` and return; they do not synchronise and, except for plan
+ *     creation/destruction, do not allocate.  The caller keeps buffers alive until the stream has run.
+ *   - Return value: PUREKV_OK (0) or a negative purekv_status.  All argument validation happens on the
+ *     host before any GPU call, so EINVAL / EUNSUPPORTED / EWORKSPACE never leave work half enqueued.
+ *   - Workspaces: purekv_workspace_bytes() gives the size an operation needs; pass a device buffer of at
+ *     least that size (may be NULL when the size is 0).  Contents need no initialisation.
+ */
+#ifndef PUREKV_H_
+#define PUREKV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define PUREKV_API __attribute__((visibility("default")))
+#else
+#define PUREKV_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PUREKV_OK = 0,
+  PUREKV_EINVAL = -1,        /* null pointer, non-positive size, inconsistent arguments          */
+  PUREKV_EUNSUPPORTED = -2,  /* head_dim not in {64, 128}, unknown pattern bits                   */
+  PUREKV_EWORKSPACE = -3,    /* workspace smaller than purekv_workspace_bytes() says              */
+  PUREKV_EHIP = -4,          /* a HIP runtime call failed (no device, launch failure, ...)        */
+  PUREKV_ENOMEM = -5         /* host allocation failed                                            */
+} purekv_status;
+
+/* Sparsity pattern bits (Sec. 3.2).  0 = dense causal attention (Eq. 1). */
+#define PUREKV_PATTERN_DENSE 0u
+#define PUREKV_PATTERN_SPATIAL 1u  /* keys of the first frame and of the query's own frame         */
+#define PUREKV_PATTERN_TEMPORAL 2u /* keys of the first frame, the same patch one frame back, self */
+#define PUREKV_PATTERN_ST 3u       /* union of both paths                                          */
+
+typedef struct {
+  int32_t n_frames, patch_h, patch_w, n_text; /* F >= 1, patch_h, patch_w >= 1, T >= 0            */
+  int32_t n_q_heads, n_kv_heads, head_dim;    /* Hq % Hkv == 0; head_dim 64 or 128                */
+  uint32_t pattern;                           /* PUREKV_PATTERN_*                                 */
+  float softmax_scale;                        /* 0 => 1/sqrt(head_dim) (Eq. 1)                    */
+} purekv_shape_t;
+
+typedef struct purekv_plan purekv_plan_t;
+
+typedef enum {
+  PUREKV_OP_PREFILL = 0,
+  PUREKV_OP_IMPORTANCE = 1,
+  PUREKV_OP_TOPK = 2,
+  PUREKV_OP_COMPACT = 3,
+  PUREKV_OP_DECODE = 4
+} purekv_op;
+
+/*
+ * Plan: the static block structure of the mask for one shape (Sec. 3.2: the pattern depends only on
+ * F, P, T).  For every tile of PUREKV_BQ query rows it lists the tiles of PUREKV_BK keys that hold at
+ * least one allowed (query, key) pair of the "block part" of the mask -- causal keys of the first
+ * frame, of the query's own frame (spatial bit), and everything for text queries or the dense pattern --
+ * flags tiles in which every pair is allowed, and cuts long lists into balanced work items.  The
+ * single previous-frame key and the self key of the temporal path are not tiles: the kernel adds them
+ * per query row.
+ *
+ * purekv_plan_create builds the lists on the host and uploads them to the current device (a few KB to
+ * MB, owned by the plan; `stream` orders the upload).  purekv_plan_create_host only builds the host
+ * lists (no GPU needed; such a plan can be inspected but not launched: compute calls return EINVAL).
+ * `*out` is written only on success.  Destroy with purekv_plan_destroy (NULL is accepted).
+ */
+#define PUREKV_BQ 128
+#define PUREKV_BK 64
+PUREKV_API int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* stream);
+PUREKV_API int purekv_plan_create_host(const purekv_shape_t* shape, purekv_plan_t** out);
+PUREKV_API int purekv_plan_destroy(purekv_plan_t* plan);
+
+/* Plan inspection (host memory).  counts[0..5] = N, number of query tiles, number of work items,
+ * number of (query tile, key tile) references, number of those flagged full, number of query tiles
+ * whose list is split over several work items. */
+PUREKV_API int purekv_plan_counts(const purekv_plan_t* plan, int64_t counts[6]);
+/* Copies the key-tile list of query tile `qt` into tiles[0..cap): entry = key_tile_index * 2 + full.
+ * Returns the list length (may exceed cap; then only cap entries are written) or a negative status. */
+PUREKV_API int purekv_plan_qtile_list(const purekv_plan_t* plan, int32_t qt, int32_t* tiles, int32_t cap);
+/* Copies work item `it` as {query tile, first list position, tile count, split index, number of
+ * splits, partial-result slot or -1}.  Returns PUREKV_OK or a negative status. */
+PUREKV_API int purekv_plan_item(const purekv_plan_t* plan, int32_t it, int32_t item[6]);
+
+/* Device workspace bytes needed by `op` for this plan.  `n_layers`, `w` and `cap` are read by the ops
+ * that take them (TOPK: n_layers, w; DECODE: cap); pass 0 otherwise. */
+PUREKV_API size_t purekv_workspace_bytes(const purekv_plan_t* plan, int op, int32_t n_layers, int32_t w, int32_t cap);
+
+/*
+ * Prefill attention under the plan's pattern (Sec. 3.2; Eq. 1 when the pattern is dense):
+ *   out[hq, i, :] = sum_j A[i, j] v[kv, j, :],  A = softmax over the allowed keys of q_i . k_j * scale.
+ * The attention matrix is never stored.  bf16 inputs, bf16 MFMA products, fp32 accumulation and softmax.
+ *   q [Hq, N, d], k, v [Hkv, N, d], out [Hq, N, d]: bf16 device.
+ *   lse: optional fp32 device [Hq, N]: natural-log sum of exponentials of every row's scaled logits
+ *        (needed by purekv_lowlayer_importance); NULL to skip.
+ */
+PUREKV_API int purekv_st_spattn_prefill(const purekv_plan_t* plan, const void* q, const void* k, const void* v,
+                             void* out, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Recent-window column sums (Eq. 2), summed over the query heads of each KV group:
+ *   c_out[kv, j] = sum_{hq in group kv} sum_{i = N-w}^{N-1} exp(q_i . k_j * scale - lse[hq, i]),  0 <= j < N-w,
+ * over the pairs (i, j) the plan's pattern allows.  `lse` is the one written by the prefill call of the
+ * same layer with the same plan.  fp32 throughout after the bf16 products; summation order is fixed, so
+ * results are reproducible bit for bit.
+ *   q [Hq, N, d], k [Hkv, N, d] bf16; lse [Hq, N] fp32; c_out [Hkv, N-w] fp32.   1 <= w <= N.
+ */
+PUREKV_API int purekv_lowlayer_importance(const purekv_plan_t* plan, const void* q, const void* k, const float* lse,
+                               int32_t w, float* c_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * V-norm weighting and selection (Eq. 3 / Eq. 4 and the selection rule of Sec. 3.1), for `n_layers`
+ * layers that share one C:
+ *   s[l, kv, j] = c[kv, j] * ||v[l, kv, j, :]||_2   (fp32; s = c when v is NULL, then n_layers must be 1),
+ *   idx_out[l, kv, 0..h)   = the h indices j < N-w with the largest s, ties to the lower index, ascending,
+ *   idx_out[l, kv, h..h+w) = N-w .. N-1.
+ *   c [Hkv, N-w] fp32; v: bf16, layer l at v + l * v_layer_stride elements, each [Hkv, N, d];
+ *   idx_out [n_layers, Hkv, h+w] int32; s_out optional [n_layers, Hkv, N-w] fp32 (NULL to skip).
+ *   1 <= w <= N, 0 <= h <= N-w.  Scores must not be NaN; -0.0 ranks equal to +0.0.
+ */
+PUREKV_API int purekv_topk_select(const purekv_plan_t* plan, const float* c, const void* v, int64_t v_layer_stride,
+                       int32_t n_layers, int32_t w, int32_t h, int32_t* idx_out, float* s_out,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Compaction: kc[l, kv, r, :] = k[l, kv, idx[l, kv, r], :] for r < n_keep, same for v (bit copy).
+ *   k, v: bf16, layer l at + l * kv_layer_stride elements, each [Hkv, N, d];
+ *   idx [n_layers, Hkv, n_keep] int32 with values in [0, N) (not checked on the device beyond clamping);
+ *   kc, vc [n_layers, Hkv, cap, d] bf16, cap >= n_keep; rows r >= n_keep are left untouched.
+ */
+PUREKV_API int purekv_kv_compact(const purekv_plan_t* plan, const void* k, const void* v, int64_t kv_layer_stride,
+                      int32_t n_layers, const int32_t* idx, int32_t n_keep, void* kc, void* vc,
+                      int32_t cap, void* stream);
+
+/* Appends one token's k_new, v_new [Hkv, d] as row n_cached of kc, vc [Hkv, cap, d] (n_cached < cap). */
+PUREKV_API int purekv_kv_append(const purekv_plan_t* plan, const void* k_new, const void* v_new, void* kc, void* vc,
+                     int32_t n_cached, int32_t cap, void* stream);
+
+/*
+ * Decode attention of one new token against the compact cache (the decode stage the paper times in its
+ * inference-speed table):  out[hq, :] = softmax(q_new[hq] . kc[kv, 0..n_cached)^T * scale) vc[kv, 0..n_cached).
+ *   q_new, out [Hq, d] bf16; kc, vc [Hkv, cap, d] bf16; 1 <= n_cached <= cap.
+ */
+PUREKV_API int purekv_decode_attn(const purekv_plan_t* plan, const void* q_new, const void* kc, const void* vc,
+                       int32_t n_cached, int32_t cap, void* out, void* ws, size_t ws_bytes, void* stream);
+
+/* h = max(0, floor(ratio * n) - w): the keep budget counts the recent window (20 % budget = 5.0x). */
+PUREKV_API int32_t purekv_budget(int32_t n, int32_t w, double ratio);
+
+/* Work counts for reporting: flops of one prefill call counted on the key tiles the kernel visits
+ * (4 * BQ * BK * d per tile reference and query head) and on the allowed pairs of the mask only. */
+PUREKV_API double purekv_plan_kept_tile_flops(const purekv_plan_t* plan);
+PUREKV_API double purekv_plan_mask_flops(const purekv_plan_t* plan);
+
+/* Static description of a status code; for PUREKV_EHIP the text of the last HIP error seen by this
+ * thread is appended. */
+PUREKV_API const char* purekv_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PUREKV_H_ */

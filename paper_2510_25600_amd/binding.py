@@ -1,0 +1,280 @@
+"""ctypes binding of libpurekv.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (see include/purekv.h).  PyTorch is used
+for device memory and the current stream; no step of the method runs in Python or in PyTorch ops.
+There is no CPU fallback: if the library is missing, import fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, byref, c_char_p, c_double, c_float, c_int, c_int32, c_int64, c_size_t, c_uint32, c_void_p
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpurekv.so")
+
+PATTERN_DENSE, PATTERN_SPATIAL, PATTERN_TEMPORAL, PATTERN_ST = 0, 1, 2, 3
+OP_PREFILL, OP_IMPORTANCE, OP_TOPK, OP_COMPACT, OP_DECODE = 0, 1, 2, 3, 4
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5
+BQ, BK = 128, 64
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [
+        ("n_frames", c_int32), ("patch_h", c_int32), ("patch_w", c_int32), ("n_text", c_int32),
+        ("n_q_heads", c_int32), ("n_kv_heads", c_int32), ("head_dim", c_int32),
+        ("pattern", c_uint32), ("softmax_scale", c_float),
+    ]
+
+
+class PureKVError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {purekv_strerror(status)} (status {status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2510_25600_amd.build` "
+            "(there is no fallback implementation)")
+    lib = ctypes.CDLL(LIB_PATH)
+    P = c_void_p
+    sig = {
+        "purekv_plan_create": (c_int, [POINTER(Shape), POINTER(P), P]),
+        "purekv_plan_create_host": (c_int, [POINTER(Shape), POINTER(P)]),
+        "purekv_plan_destroy": (c_int, [P]),
+        "purekv_plan_counts": (c_int, [P, POINTER(c_int64)]),
+        "purekv_plan_qtile_list": (c_int, [P, c_int32, POINTER(c_int32), c_int32]),
+        "purekv_plan_item": (c_int, [P, c_int32, POINTER(c_int32)]),
+        "purekv_workspace_bytes": (c_size_t, [P, c_int, c_int32, c_int32, c_int32]),
+        "purekv_st_spattn_prefill": (c_int, [P, P, P, P, P, P, P, c_size_t, P]),
+        "purekv_lowlayer_importance": (c_int, [P, P, P, P, c_int32, P, P, c_size_t, P]),
+        "purekv_topk_select": (c_int, [P, P, P, c_int64, c_int32, c_int32, c_int32, P, P, P, c_size_t, P]),
+        "purekv_kv_compact": (c_int, [P, P, P, c_int64, c_int32, P, c_int32, P, P, c_int32, P]),
+        "purekv_kv_append": (c_int, [P, P, P, P, P, c_int32, c_int32, P]),
+        "purekv_decode_attn": (c_int, [P, P, P, P, c_int32, c_int32, P, P, c_size_t, P]),
+        "purekv_budget": (c_int32, [c_int32, c_int32, c_double]),
+        "purekv_plan_kept_tile_flops": (c_double, [P]),
+        "purekv_plan_mask_flops": (c_double, [P]),
+        "purekv_strerror": (c_char_p, [c_int]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
+_lib = _load()
+EXPORTS = (
+    "purekv_plan_create", "purekv_plan_create_host", "purekv_plan_destroy", "purekv_plan_counts",
+    "purekv_plan_qtile_list", "purekv_plan_item", "purekv_workspace_bytes", "purekv_st_spattn_prefill",
+    "purekv_lowlayer_importance", "purekv_topk_select", "purekv_kv_compact", "purekv_kv_append",
+    "purekv_decode_attn", "purekv_budget", "purekv_plan_kept_tile_flops", "purekv_plan_mask_flops",
+    "purekv_strerror",
+)
+
+
+def raw() -> ctypes.CDLL:
+    """The ctypes handle, for tests that call the C ABI with hand-made (possibly invalid) arguments."""
+    return _lib
+
+
+def purekv_strerror(status: int) -> str:
+    return _lib.purekv_strerror(status).decode()
+
+
+def purekv_budget(n: int, w: int, ratio: float) -> int:
+    return int(_lib.purekv_budget(n, w, ratio))
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise PureKVError(status, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _dev_bf16(t: torch.Tensor, name: str) -> torch.Tensor:
+    if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous bf16 device tensor")
+    return t
+
+
+class Plan:
+    """Owns a purekv_plan_t.  `host_only` plans can be inspected without a GPU but not launched."""
+
+    def __init__(self, n_frames: int, patch_h: int, patch_w: int, n_text: int, n_q_heads: int, n_kv_heads: int,
+                 head_dim: int, pattern: int = PATTERN_ST, softmax_scale: float = 0.0, host_only: bool = False):
+        self.shape = Shape(n_frames, patch_h, patch_w, n_text, n_q_heads, n_kv_heads, head_dim, pattern,
+                           softmax_scale)
+        self._h = c_void_p()
+        if host_only:
+            _check(_lib.purekv_plan_create_host(byref(self.shape), byref(self._h)), "purekv_plan_create_host")
+        else:
+            _check(_lib.purekv_plan_create(byref(self.shape), byref(self._h), _stream()), "purekv_plan_create")
+        self.N = n_frames * patch_h * patch_w + n_text
+        self.Hq, self.Hkv, self.d = n_q_heads, n_kv_heads, head_dim
+        self._ws = {}
+
+    @classmethod
+    def for_workload(cls, wl, pattern: int = PATTERN_ST, host_only: bool = False) -> "Plan":
+        return cls(wl.n_frames, wl.patch_h, wl.patch_w, wl.n_text, wl.n_q_heads, wl.n_kv_heads, wl.head_dim,
+                   pattern, 0.0, host_only)
+
+    @property
+    def handle(self) -> c_void_p:
+        return self._h
+
+    def close(self) -> None:
+        if self._h:
+            _lib.purekv_plan_destroy(self._h)
+            self._h = c_void_p()
+        self._ws = {}
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- inspection -------------------------------------------------------------------------------
+    def counts(self) -> dict:
+        c = (c_int64 * 6)()
+        _check(_lib.purekv_plan_counts(self._h, c), "purekv_plan_counts")
+        return dict(N=c[0], n_qtiles=c[1], n_items=c[2], n_tile_refs=c[3], n_full=c[4], n_split_qtiles=c[5])
+
+    def qtile_list(self, qt: int) -> list:
+        n = _lib.purekv_plan_qtile_list(self._h, qt, None, 0)
+        if n < 0:
+            raise PureKVError(n, "purekv_plan_qtile_list")
+        buf = (c_int32 * max(n, 1))()
+        _lib.purekv_plan_qtile_list(self._h, qt, buf, n)
+        return [(buf[i] >> 1, buf[i] & 1) for i in range(n)]
+
+    def item(self, it: int) -> Tuple[int, ...]:
+        buf = (c_int32 * 6)()
+        _check(_lib.purekv_plan_item(self._h, it, buf), "purekv_plan_item")
+        return tuple(buf)
+
+    def kept_tile_flops(self) -> float:
+        return float(_lib.purekv_plan_kept_tile_flops(self._h))
+
+    def mask_flops(self) -> float:
+        return float(_lib.purekv_plan_mask_flops(self._h))
+
+    def workspace_bytes(self, op: int, n_layers: int = 0, w: int = 0, cap: int = 0) -> int:
+        return int(_lib.purekv_workspace_bytes(self._h, op, n_layers, w, cap))
+
+    def _workspace(self, op: int, nbytes: int, device) -> Optional[torch.Tensor]:
+        """Device scratch owned by the Python wrapper (torch memory), reused across calls."""
+        if nbytes == 0:
+            return None
+        t = self._ws.get(op)
+        if t is None or t.numel() < nbytes or t.device != device:
+            t = torch.empty(nbytes, dtype=torch.uint8, device=device)
+            self._ws[op] = t
+        return t
+
+
+def purekv_st_spattn_prefill(plan: Plan, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                             out: Optional[torch.Tensor] = None, want_lse: bool = False,
+                             lse: Optional[torch.Tensor] = None):
+    _dev_bf16(q, "q"), _dev_bf16(k, "k"), _dev_bf16(v, "v")
+    assert q.shape == (plan.Hq, plan.N, plan.d) and k.shape == (plan.Hkv, plan.N, plan.d) and v.shape == k.shape
+    if out is None:
+        out = torch.empty_like(q)
+    if want_lse and lse is None:
+        lse = torch.empty((plan.Hq, plan.N), dtype=torch.float32, device=q.device)
+    nb = plan.workspace_bytes(OP_PREFILL)
+    ws = plan._workspace(OP_PREFILL, nb, q.device)
+    _check(_lib.purekv_st_spattn_prefill(plan.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                         _ptr(lse), _ptr(ws), nb, _stream()), "purekv_st_spattn_prefill")
+    return (out, lse) if (want_lse or lse is not None) else out
+
+
+def purekv_lowlayer_importance(plan: Plan, q: torch.Tensor, k: torch.Tensor, lse: torch.Tensor, w: int,
+                               c_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev_bf16(q, "q"), _dev_bf16(k, "k")
+    assert lse.dtype == torch.float32 and lse.is_contiguous() and lse.shape == (plan.Hq, plan.N)
+    if c_out is None:
+        c_out = torch.empty((plan.Hkv, max(plan.N - w, 0)), dtype=torch.float32, device=q.device)
+    _check(_lib.purekv_lowlayer_importance(plan.handle, q.data_ptr(), k.data_ptr(), lse.data_ptr(), w,
+                                           c_out.data_ptr(), None, 0, _stream()), "purekv_lowlayer_importance")
+    return c_out
+
+
+def purekv_topk_select(plan: Plan, c: torch.Tensor, v: Optional[torch.Tensor], w: int, h: int,
+                       want_scores: bool = False, idx_out: Optional[torch.Tensor] = None):
+    """v: None, [Hkv, N, d] or [L, Hkv, N, d] (layers share c).  Returns idx [L, Hkv, h+w] (L squeezed when v has no
+    layer axis) and, if asked, the scores."""
+    assert c.dtype == torch.float32 and c.is_contiguous() and c.is_cuda
+    layered = v is not None and v.dim() == 4
+    n_layers = v.shape[0] if layered else 1
+    stride = v.stride(0) if layered else 0
+    if v is not None:
+        _dev_bf16(v, "v")
+    if idx_out is None:
+        idx_out = torch.empty((n_layers, plan.Hkv, h + w), dtype=torch.int32, device=c.device)
+    s_out = torch.empty((n_layers, plan.Hkv, plan.N - w), dtype=torch.float32, device=c.device) if want_scores else None
+    nb = plan.workspace_bytes(OP_TOPK, n_layers, w) if (v is not None and s_out is None) else 0
+    ws = plan._workspace(OP_TOPK, nb, c.device)
+    _check(_lib.purekv_topk_select(plan.handle, c.data_ptr(), _ptr(v), stride, n_layers, w, h, idx_out.data_ptr(),
+                                   _ptr(s_out), _ptr(ws), nb, _stream()), "purekv_topk_select")
+    if not layered:
+        idx_out = idx_out[0]
+        s_out = None if s_out is None else s_out[0]
+    return (idx_out, s_out) if want_scores else idx_out
+
+
+def purekv_kv_compact(plan: Plan, k: torch.Tensor, v: torch.Tensor, idx: torch.Tensor, cap: Optional[int] = None,
+                      kc: Optional[torch.Tensor] = None, vc: Optional[torch.Tensor] = None):
+    """k, v: [Hkv, N, d] or [L, Hkv, N, d]; idx: [Hkv, n_keep] or [L, Hkv, n_keep] int32."""
+    _dev_bf16(k, "k"), _dev_bf16(v, "v")
+    assert idx.dtype == torch.int32 and idx.is_contiguous() and idx.is_cuda
+    layered = k.dim() == 4
+    n_layers = k.shape[0] if layered else 1
+    stride = k.stride(0) if layered else 0
+    assert (not layered) or v.stride(0) == stride
+    n_keep = idx.shape[-1]
+    cap = n_keep if cap is None else cap
+    shape = (n_layers, plan.Hkv, cap, plan.d) if layered else (plan.Hkv, cap, plan.d)
+    if kc is None:
+        kc = torch.empty(shape, dtype=torch.bfloat16, device=k.device)
+    if vc is None:
+        vc = torch.empty(shape, dtype=torch.bfloat16, device=k.device)
+    _check(_lib.purekv_kv_compact(plan.handle, k.data_ptr(), v.data_ptr(), stride, n_layers, idx.data_ptr(), n_keep,
+                                  kc.data_ptr(), vc.data_ptr(), cap, _stream()), "purekv_kv_compact")
+    return kc, vc
+
+
+def purekv_kv_append(plan: Plan, k_new: torch.Tensor, v_new: torch.Tensor, kc: torch.Tensor, vc: torch.Tensor,
+                     n_cached: int) -> int:
+    _dev_bf16(k_new, "k_new"), _dev_bf16(v_new, "v_new"), _dev_bf16(kc, "kc"), _dev_bf16(vc, "vc")
+    cap = kc.shape[-2]
+    _check(_lib.purekv_kv_append(plan.handle, k_new.data_ptr(), v_new.data_ptr(), kc.data_ptr(), vc.data_ptr(),
+                                 n_cached, cap, _stream()), "purekv_kv_append")
+    return n_cached + 1
+
+
+def purekv_decode_attn(plan: Plan, q_new: torch.Tensor, kc: torch.Tensor, vc: torch.Tensor, n_cached: int,
+                       out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev_bf16(q_new, "q_new"), _dev_bf16(kc, "kc"), _dev_bf16(vc, "vc")
+    cap = kc.shape[-2]
+    if out is None:
+        out = torch.empty_like(q_new)
+    nb = plan.workspace_bytes(OP_DECODE, cap=cap)
+    ws = plan._workspace(OP_DECODE, nb, q_new.device)
+    _check(_lib.purekv_decode_attn(plan.handle, q_new.data_ptr(), kc.data_ptr(), vc.data_ptr(), n_cached, cap,
+                                   out.data_ptr(), _ptr(ws), nb, _stream()), "purekv_decode_attn")
+    return out

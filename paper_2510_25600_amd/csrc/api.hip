@@ -1,0 +1,245 @@
+// C-ABI entry points: argument validation (host only, before any GPU call), plan life cycle, dispatch.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "common.h"
+
+namespace purekv {
+
+static thread_local char g_hip_msg[256] = "";
+
+int note_hip_error(hipError_t e) {
+  std::snprintf(g_hip_msg, sizeof(g_hip_msg), "HIP error %d: %s", (int)e, hipGetErrorString(e));
+  return PUREKV_EHIP;
+}
+
+static int check_shape(const purekv_shape_t* s) {
+  if (s == nullptr) return PUREKV_EINVAL;
+  if (s->n_frames < 1 || s->patch_h < 1 || s->patch_w < 1 || s->n_text < 0) return PUREKV_EINVAL;
+  if (s->n_q_heads < 1 || s->n_kv_heads < 1 || s->n_q_heads % s->n_kv_heads != 0) return PUREKV_EINVAL;
+  if (!(s->softmax_scale >= 0.f) || std::isinf(s->softmax_scale)) return PUREKV_EINVAL;
+  const int64_t p = (int64_t)s->patch_h * s->patch_w, n = p * s->n_frames + s->n_text;
+  if (p > (1 << 24) || n > (int64_t)1 << 26) return PUREKV_EINVAL;  // indices are 32-bit on the device
+  if (s->head_dim != 64 && s->head_dim != 128) return PUREKV_EUNSUPPORTED;
+  if (s->pattern > PUREKV_PATTERN_ST) return PUREKV_EUNSUPPORTED;
+  return PUREKV_OK;
+}
+
+static int make_plan(const purekv_shape_t* s, purekv_plan_t** out, int n_cu) {
+  if (out == nullptr) return PUREKV_EINVAL;
+  const int rc = check_shape(s);
+  if (rc != PUREKV_OK) return rc;
+  purekv_plan* p = new (std::nothrow) purekv_plan();
+  if (p == nullptr) return PUREKV_ENOMEM;
+  Geometry& g = p->g;
+  g.F = s->n_frames;
+  g.P = s->patch_h * s->patch_w;
+  g.T = s->n_text;
+  g.Nv = g.F * g.P;
+  g.N = g.Nv + g.T;
+  g.Hq = s->n_q_heads;
+  g.Hkv = s->n_kv_heads;
+  g.G = g.Hq / g.Hkv;
+  g.d = s->head_dim;
+  g.pattern = s->pattern;
+  g.scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / std::sqrt((float)s->head_dim);
+  try {
+    build_plan(*p, n_cu);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return PUREKV_ENOMEM;
+  }
+  *out = p;
+  return PUREKV_OK;
+}
+
+static bool launchable(const purekv_plan_t* p) { return p != nullptr && p->d_items != nullptr; }
+
+}  // namespace purekv
+
+using namespace purekv;
+
+extern "C" {
+
+int purekv_plan_create_host(const purekv_shape_t* shape, purekv_plan_t** out) { return make_plan(shape, out, 256); }
+
+int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* stream) {
+  if (out == nullptr) return PUREKV_EINVAL;
+  int rc = check_shape(shape);
+  if (rc != PUREKV_OK) return rc;
+  int dev = 0, n_cu = 256;
+  PUREKV_HIP_TRY(hipGetDevice(&dev));
+  PUREKV_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+  purekv_plan_t* p = nullptr;
+  rc = make_plan(shape, &p, n_cu > 0 ? n_cu : 256);
+  if (rc != PUREKV_OK) return rc;
+  p->device = dev;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const size_t tb = p->tiles.size() * sizeof(int32_t), ib = p->items.size() * sizeof(WorkItem),
+               mb = p->merges.size() * sizeof(MergeItem);
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_tiles), tb ? tb : 4);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_items), ib ? ib : 4);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_merges), mb ? mb : 4);
+  if (e == hipSuccess && tb) e = hipMemcpyAsync(p->d_tiles, p->tiles.data(), tb, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess && ib) e = hipMemcpyAsync(p->d_items, p->items.data(), ib, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess && mb) e = hipMemcpyAsync(p->d_merges, p->merges.data(), mb, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);  // host vectors may be reallocated later; finish the copy now
+  if (e != hipSuccess) {
+    purekv_plan_destroy(p);
+    return note_hip_error(e);
+  }
+  *out = p;
+  return PUREKV_OK;
+}
+
+int purekv_plan_destroy(purekv_plan_t* p) {
+  if (p == nullptr) return PUREKV_OK;
+  if (p->d_tiles) (void)hipFree(p->d_tiles);
+  if (p->d_items) (void)hipFree(p->d_items);
+  if (p->d_merges) (void)hipFree(p->d_merges);
+  delete p;
+  return PUREKV_OK;
+}
+
+int purekv_plan_counts(const purekv_plan_t* p, int64_t counts[6]) {
+  if (p == nullptr || counts == nullptr) return PUREKV_EINVAL;
+  counts[0] = p->g.N;
+  counts[1] = p->n_qtiles;
+  counts[2] = (int64_t)p->items.size();
+  counts[3] = (int64_t)p->tiles.size();
+  counts[4] = p->n_full;
+  counts[5] = (int64_t)p->merges.size();
+  return PUREKV_OK;
+}
+
+int purekv_plan_qtile_list(const purekv_plan_t* p, int32_t qt, int32_t* tiles, int32_t cap) {
+  if (p == nullptr || qt < 0 || qt >= p->n_qtiles || cap < 0 || (cap > 0 && tiles == nullptr)) return PUREKV_EINVAL;
+  const int32_t b = p->qtile_begin[qt], len = p->qtile_begin[qt + 1] - b;
+  for (int32_t i = 0; i < len && i < cap; ++i) tiles[i] = p->tiles[b + i];
+  return len;
+}
+
+int purekv_plan_item(const purekv_plan_t* p, int32_t it, int32_t item[6]) {
+  if (p == nullptr || item == nullptr || it < 0 || it >= (int32_t)p->items.size()) return PUREKV_EINVAL;
+  const WorkItem& w = p->items[it];
+  item[0] = w.qtile;
+  item[1] = w.list_begin;
+  item[2] = w.n_tiles;
+  item[3] = w.split;
+  item[4] = w.n_splits;
+  item[5] = w.slot;
+  return PUREKV_OK;
+}
+
+double purekv_plan_kept_tile_flops(const purekv_plan_t* p) {
+  if (p == nullptr) return 0.0;
+  return 4.0 * PUREKV_BQ * PUREKV_BK * p->g.d * (double)p->tiles.size() * p->g.Hq;
+}
+
+double purekv_plan_mask_flops(const purekv_plan_t* p) {
+  if (p == nullptr) return 0.0;
+  return 4.0 * p->g.d * p->mask_pairs * p->g.Hq;
+}
+
+size_t purekv_workspace_bytes(const purekv_plan_t* p, int op, int32_t n_layers, int32_t w, int32_t cap) {
+  if (p == nullptr) return 0;
+  switch (op) {
+    case PUREKV_OP_PREFILL:
+      return prefill_ws_bytes(*p);
+    case PUREKV_OP_TOPK:
+      return (n_layers >= 1 && w >= 1 && w <= p->g.N) ? topk_ws_bytes(*p, n_layers, w) : 0;
+    case PUREKV_OP_DECODE:
+      return cap >= 1 ? decode_ws_bytes(*p, cap) : 0;
+    default:
+      return 0;
+  }
+}
+
+int purekv_st_spattn_prefill(const purekv_plan_t* p, const void* q, const void* k, const void* v, void* out,
+                             float* lse, void* ws, size_t ws_bytes, void* stream) {
+  if (!launchable(p) || q == nullptr || k == nullptr || v == nullptr || out == nullptr) return PUREKV_EINVAL;
+  const size_t need = prefill_ws_bytes(*p);
+  if (need > 0 && (ws == nullptr || ws_bytes < need)) return PUREKV_EWORKSPACE;
+  return launch_prefill(*p, q, k, v, out, lse, ws, static_cast<hipStream_t>(stream));
+}
+
+int purekv_lowlayer_importance(const purekv_plan_t* p, const void* q, const void* k, const float* lse, int32_t w,
+                               float* c_out, void* ws, size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  if (!launchable(p) || q == nullptr || k == nullptr || lse == nullptr) return PUREKV_EINVAL;
+  if (w < 1 || w > p->g.N) return PUREKV_EINVAL;
+  if (c_out == nullptr && w < p->g.N) return PUREKV_EINVAL;
+  return launch_importance(*p, q, k, lse, w, c_out, static_cast<hipStream_t>(stream));
+}
+
+int purekv_topk_select(const purekv_plan_t* p, const float* c, const void* v, int64_t v_layer_stride,
+                       int32_t n_layers, int32_t w, int32_t h, int32_t* idx_out, float* s_out, void* ws,
+                       size_t ws_bytes, void* stream) {
+  if (!launchable(p) || idx_out == nullptr || n_layers < 1) return PUREKV_EINVAL;
+  if (w < 1 || w > p->g.N || h < 0 || h > p->g.N - w) return PUREKV_EINVAL;
+  if (c == nullptr && w < p->g.N) return PUREKV_EINVAL;
+  if (v == nullptr && n_layers != 1) return PUREKV_EINVAL;
+  if (v != nullptr && n_layers > 1 && v_layer_stride < (int64_t)p->g.Hkv * p->g.N * p->g.d) return PUREKV_EINVAL;
+  if (v != nullptr && s_out == nullptr) {
+    const size_t need = topk_ws_bytes(*p, n_layers, w);
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return PUREKV_EWORKSPACE;
+  }
+  return launch_topk(*p, c, v, v_layer_stride, n_layers, w, h, idx_out, s_out, ws, static_cast<hipStream_t>(stream));
+}
+
+int purekv_kv_compact(const purekv_plan_t* p, const void* k, const void* v, int64_t kv_layer_stride, int32_t n_layers,
+                      const int32_t* idx, int32_t n_keep, void* kc, void* vc, int32_t cap, void* stream) {
+  if (!launchable(p) || k == nullptr || v == nullptr || kc == nullptr || vc == nullptr || n_layers < 1)
+    return PUREKV_EINVAL;
+  if (n_keep < 0 || n_keep > cap || cap < 1 || n_keep > p->g.N) return PUREKV_EINVAL;
+  if (idx == nullptr && n_keep > 0) return PUREKV_EINVAL;
+  if (n_layers > 1 && kv_layer_stride < (int64_t)p->g.Hkv * p->g.N * p->g.d) return PUREKV_EINVAL;
+  return launch_compact(*p, k, v, kv_layer_stride, n_layers, idx, n_keep, kc, vc, cap, static_cast<hipStream_t>(stream));
+}
+
+int purekv_kv_append(const purekv_plan_t* p, const void* k_new, const void* v_new, void* kc, void* vc,
+                     int32_t n_cached, int32_t cap, void* stream) {
+  if (!launchable(p) || k_new == nullptr || v_new == nullptr || kc == nullptr || vc == nullptr) return PUREKV_EINVAL;
+  if (n_cached < 0 || n_cached >= cap) return PUREKV_EINVAL;
+  return launch_append(*p, k_new, v_new, kc, vc, n_cached, cap, static_cast<hipStream_t>(stream));
+}
+
+int purekv_decode_attn(const purekv_plan_t* p, const void* q_new, const void* kc, const void* vc, int32_t n_cached,
+                       int32_t cap, void* out, void* ws, size_t ws_bytes, void* stream) {
+  if (!launchable(p) || q_new == nullptr || kc == nullptr || vc == nullptr || out == nullptr) return PUREKV_EINVAL;
+  if (n_cached < 1 || n_cached > cap) return PUREKV_EINVAL;
+  if (ws == nullptr || ws_bytes < decode_ws_bytes(*p, cap)) return PUREKV_EWORKSPACE;
+  return launch_decode(*p, q_new, kc, vc, n_cached, cap, out, ws, static_cast<hipStream_t>(stream));
+}
+
+int32_t purekv_budget(int32_t n, int32_t w, double ratio) {
+  const double kept = std::floor(ratio * (double)n);
+  const int64_t h = (int64_t)kept - w;
+  return h > 0 ? (int32_t)h : 0;
+}
+
+const char* purekv_strerror(int status) {
+  static thread_local char buf[320];
+  switch (status) {
+    case PUREKV_OK:
+      return "ok";
+    case PUREKV_EINVAL:
+      return "invalid argument (null pointer, size out of range, inconsistent shape, or a host-only plan)";
+    case PUREKV_EUNSUPPORTED:
+      return "unsupported shape (head_dim must be 64 or 128; pattern must be 0..3)";
+    case PUREKV_EWORKSPACE:
+      return "workspace missing or smaller than purekv_workspace_bytes()";
+    case PUREKV_ENOMEM:
+      return "host allocation failed";
+    case PUREKV_EHIP:
+      std::snprintf(buf, sizeof(buf), "HIP runtime failure: %s", g_hip_msg[0] ? g_hip_msg : "(no detail recorded)");
+      return buf;
+    default:
+      return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,62 @@
+// Internal helpers shared by the HIP translation units (device-side types, error plumbing).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "plan.h"
+
+namespace purekv {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (inputs are finite here).
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return f32_to_bf16(lo) | (f32_to_bf16(hi) << 16);
+}
+
+// Value held by the lane 32 positions away (the other half of the wavefront).
+__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
+
+// Records a failed HIP call for purekv_strerror and maps it to PUREKV_EHIP.
+int note_hip_error(hipError_t e);
+
+#define PUREKV_HIP_TRY(expr)                                \
+  do {                                                      \
+    hipError_t e__ = (expr);                                \
+    if (e__ != hipSuccess) return purekv::note_hip_error(e__); \
+  } while (0)
+
+// Kernel launchers (one per translation unit); all arguments validated by the caller.
+int launch_prefill(const purekv_plan& p, const void* q, const void* k, const void* v, void* out, float* lse,
+                   void* ws, hipStream_t st);
+int launch_importance(const purekv_plan& p, const void* q, const void* k, const float* lse, int32_t w,
+                      float* c_out, hipStream_t st);
+int launch_topk(const purekv_plan& p, const float* c, const void* v, int64_t v_layer_stride, int32_t n_layers,
+                int32_t w, int32_t h, int32_t* idx_out, float* s_out, void* ws, hipStream_t st);
+int launch_compact(const purekv_plan& p, const void* k, const void* v, int64_t kv_layer_stride, int32_t n_layers,
+                   const int32_t* idx, int32_t n_keep, void* kc, void* vc, int32_t cap, hipStream_t st);
+int launch_append(const purekv_plan& p, const void* k_new, const void* v_new, void* kc, void* vc, int32_t n_cached,
+                  int32_t cap, hipStream_t st);
+int launch_decode(const purekv_plan& p, const void* q_new, const void* kc, const void* vc, int32_t n_cached,
+                  int32_t cap, void* out, void* ws, hipStream_t st);
+
+size_t prefill_ws_bytes(const purekv_plan& p);
+size_t topk_ws_bytes(const purekv_plan& p, int32_t n_layers, int32_t w);
+size_t decode_ws_bytes(const purekv_plan& p, int32_t cap);
+
+}  // namespace purekv

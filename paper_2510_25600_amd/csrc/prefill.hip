@@ -1,0 +1,351 @@
+// ST-SpAttn / dense causal prefill attention for gfx950 (Sec. 3.2; Eq. 1 for the dense pattern).
+//
+// One workgroup (4 wavefronts) owns a tile of 128 query rows of one query head and walks a slice of
+// that tile's key-tile list (64 keys per tile).  Each wavefront owns 32 query rows.  Scores are formed
+// transposed, S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so that a lane holds 16 keys of ONE query:
+// the softmax row maximum and row sum are in-lane reductions plus one exchange between the two halves
+// of the wavefront, and the probabilities leave the accumulator already in the register layout that
+// the second product O^T = V^T P^T takes as its B operand.  K tiles sit in LDS row-major, V tiles
+// transposed (the contraction index of the second product is the key), both XOR-swizzled in 16-byte
+// units so the 128-bit operand reads are conflict-free.  The attention matrix never exists.
+//
+// The temporal path's single previous-frame key (and the self key when the spatial path is off) is not
+// worth a tile: it enters as one extra online-softmax step per row, computed with vector ALU dot products.
+#include "common.h"
+
+namespace purekv {
+namespace {
+
+constexpr int BQ = PUREKV_BQ;
+constexpr int BK = PUREKV_BK;
+
+struct PrefillArgs {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  uint16_t* out;
+  float* lse;
+  float* ws_o;    // [n_slots, Hq, BQ, D] normalised partial outputs
+  float* ws_lse;  // [n_slots, Hq, BQ]    log2-domain log-sum-exp of the partial
+  const int32_t* tiles;
+  const WorkItem* items;
+  const MergeItem* merges;
+  int32_t N, Nv, P, Hq, G;
+  uint32_t pattern;
+  float scale_log2;  // softmax scale * log2(e)
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
+  constexpr int KSTEPS = D / 16;        // MFMA k-steps of the score product
+  constexpr int DBLK = D / 32;          // 32-row blocks of O^T
+  constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
+  constexpr int KCH = BK * CPR / 256;   // K chunks staged per thread
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[BK * D];
+  __shared__ __attribute__((aligned(16))) uint16_t Vt[D * BK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 31, h = lane >> 5;
+  const int item_id = blockIdx.x / a.Hq, hq = blockIdx.x % a.Hq, kvh = hq / a.G;
+  const WorkItem it = a.items[item_id];
+  const int row = it.qtile * BQ + wave * 32 + n;
+  const int rowc = min(row, a.N - 1);
+
+  // Block part of the mask for this lane's row: key j allowed iff j <= rowc and (j <= a_i or j >= lo_i).
+  const bool sparse_row = a.pattern != 0u && rowc < a.Nv;
+  const int frame = sparse_row ? rowc / a.P : 0;
+  const int a_i = sparse_row ? min(rowc, a.P - 1) : rowc;
+  const int lo_i = sparse_row ? ((a.pattern & 1u) ? frame * a.P : rowc + 1) : 0;
+
+  const uint16_t* kbase = a.k + (size_t)kvh * a.N * D;
+  const uint16_t* vbase = a.v + (size_t)kvh * a.N * D;
+
+  bf16x8 qf[KSTEPS];
+  {
+    const uint16_t* qrow = a.q + ((size_t)hq * a.N + rowc) * D;
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s + 8 * h);
+  }
+
+  float m = -INFINITY, l = 0.f;
+  floatx16 oacc[DBLK];
+#pragma unroll
+  for (int b = 0; b < DBLK; ++b)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
+
+  // ---- side keys of the temporal path (first slice of the row's list only) ----
+  if (it.split == 0 && (a.pattern & 2u)) {
+    const bool has_prev = sparse_row && frame >= 2;
+    const bool has_self = sparse_row && !(a.pattern & 1u) && frame >= 1;
+    const int js[2] = {has_prev ? rowc - a.P : rowc, rowc};
+    const bool valid[2] = {has_prev, has_self};
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      if (!__any(valid[t])) continue;
+      const uint16_t* kr = kbase + (size_t)js[t] * D;
+      float part = 0.f;
+#pragma unroll
+      for (int s = 0; s < KSTEPS; ++s) {
+        const u32x4 kk = *reinterpret_cast<const u32x4*>(kr + 16 * s + 8 * h);
+        const u32x4 qq = __builtin_bit_cast(u32x4, qf[s]);
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          part += bf16_lo(qq[w]) * bf16_lo(kk[w]) + bf16_hi(qq[w]) * bf16_hi(kk[w]);
+      }
+      float sdot = (part + other_half(part)) * a.scale_log2;
+      if (!valid[t]) sdot = -INFINITY;
+      const float m_new = fmaxf(m, sdot);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+      const float p = __builtin_amdgcn_exp2f(sdot - m_use);
+      l = l * alpha + (h == 0 ? p : 0.f);
+      m = m_new;
+      const uint16_t* vr = vbase + (size_t)js[t] * D;
+#pragma unroll
+      for (int b = 0; b < DBLK; ++b)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const u32x2 vv = *reinterpret_cast<const u32x2*>(vr + 32 * b + 8 * g4 + 4 * h);
+          oacc[b][4 * g4 + 0] = oacc[b][4 * g4 + 0] * alpha + p * bf16_lo(vv[0]);
+          oacc[b][4 * g4 + 1] = oacc[b][4 * g4 + 1] * alpha + p * bf16_hi(vv[0]);
+          oacc[b][4 * g4 + 2] = oacc[b][4 * g4 + 2] * alpha + p * bf16_lo(vv[1]);
+          oacc[b][4 * g4 + 3] = oacc[b][4 * g4 + 3] * alpha + p * bf16_hi(vv[1]);
+        }
+    }
+  }
+
+  // ---- staging maps ----
+  // V: a thread owns 4 consecutive keys (quad vg) x 8 consecutive d (chunk vc); 4 neighbouring lanes read 64
+  // contiguous bytes of one row.
+  const int vcl = tid & 3, vg = (tid >> 2) & 15, vc = (tid >> 6) * 4 + vcl;
+  const bool v_active = vc < CPR;
+  u32x4 kreg[KCH], vreg[4];
+
+  auto load_tile = [&](int k0) {
+#pragma unroll
+    for (int r = 0; r < KCH; ++r) {
+      const int id = tid + 256 * r, rk = id / CPR, cc = id % CPR;
+      const int j = min(k0 + rk, a.N - 1);
+      kreg[r] = *reinterpret_cast<const u32x4*>(kbase + (size_t)j * D + cc * 8);
+    }
+    if (v_active) {
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int j = min(k0 + 4 * vg + jj, a.N - 1);
+        vreg[jj] = *reinterpret_cast<const u32x4*>(vbase + (size_t)j * D + vc * 8);
+      }
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int r = 0; r < KCH; ++r) {
+      const int id = tid + 256 * r, rk = id / CPR, cc = id % CPR;
+      *reinterpret_cast<u32x4*>(Ks + rk * D + ((cc ^ (rk & 7)) * 8)) = kreg[r];
+    }
+    if (v_active) {
+      // quad vg holds keys 16*grp + 8*aa + 4*hh + 0..3; the MFMA k-order wants, per 16 keys,
+      // [hh=0: aa=0, aa=1 | hh=1: aa=0, aa=1], i.e. 16-byte unit 2*grp + hh, 8-byte half aa.
+      const int unit = 2 * (vg >> 2) + (vg & 1), half = (vg >> 1) & 1;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int dd = 8 * vc + e;
+        const uint32_t x0 = vreg[0][e >> 1], x1 = vreg[1][e >> 1], x2 = vreg[2][e >> 1], x3 = vreg[3][e >> 1];
+        u32x2 w;
+        if (e & 1) {
+          w[0] = (x0 >> 16) | (x1 & 0xffff0000u);
+          w[1] = (x2 >> 16) | (x3 & 0xffff0000u);
+        } else {
+          w[0] = (x0 & 0xffffu) | (x1 << 16);
+          w[1] = (x2 & 0xffffu) | (x3 << 16);
+        }
+        *reinterpret_cast<u32x2*>(Vt + dd * BK + ((unit ^ (dd & 7)) * 8) + half * 4) = w;
+      }
+    }
+  };
+
+  if (it.n_tiles > 0) load_tile((a.tiles[it.list_begin] >> 1) * BK);
+
+  for (int t = 0; t < it.n_tiles; ++t) {
+    const int entry = a.tiles[it.list_begin + t];
+    const int k0 = (entry >> 1) * BK;
+    const bool full = entry & 1;
+    __syncthreads();  // every wave has finished reading the previous tile
+    store_tile();
+    __syncthreads();
+    if (t + 1 < it.n_tiles) load_tile((a.tiles[it.list_begin + t + 1] >> 1) * BK);  // in flight during the math
+
+    // S^T = K Q^T: two 32-key blocks x 32 queries
+    floatx16 sacc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const int rk = 32 * kb + n;
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + rk * D + (((2 * s + h) ^ (n & 7)) * 8));
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[kb], 0, 0, 0);
+      }
+
+    // scale, mask, running maximum
+    float mt = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float x = sacc[kb][i] * a.scale_log2;
+        if (!full) {
+          const int j = k0 + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
+          const bool ok = (j <= rowc) && (j <= a_i || j >= lo_i);
+          x = ok ? x : -INFINITY;
+        }
+        sacc[kb][i] = x;
+        mt = fmaxf(mt, x);
+      }
+    mt = fmaxf(mt, other_half(mt));
+    const float m_new = fmaxf(m, mt);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+    m = m_new;
+
+    // probabilities -> bf16 B-operand fragments; pf[ks] covers keys 16*ks .. 16*ks+15 of the tile
+    float psum = 0.f;
+    bf16x8 pf[4];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        u32x4 pk;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const float p0 = __builtin_amdgcn_exp2f(sacc[kb][8 * half + 2 * w] - m_use);
+          const float p1 = __builtin_amdgcn_exp2f(sacc[kb][8 * half + 2 * w + 1] - m_use);
+          psum += p0 + p1;
+          pk[w] = pack_bf16(p0, p1);
+        }
+        pf[2 * kb + half] = __builtin_bit_cast(bf16x8, pk);
+      }
+    l = l * alpha + psum;
+
+    // O^T = alpha * O^T + V^T P^T
+#pragma unroll
+    for (int b = 0; b < DBLK; ++b) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int dr = 32 * b + n;
+        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(Vt + dr * BK + (((2 * ks + h) ^ (n & 7)) * 8));
+        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks], oacc[b], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- epilogue ----
+  const float l_tot = l + other_half(l);
+  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  const float lse2 = m + __builtin_amdgcn_logf(l_tot);  // log2 domain; -inf when the slice saw no key
+  if (it.n_splits == 1) {
+    if (row < a.N) {
+      uint16_t* orow = a.out + ((size_t)hq * a.N + row) * D;
+#pragma unroll
+      for (int b = 0; b < DBLK; ++b)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          u32x2 w;
+          w[0] = pack_bf16(oacc[b][4 * g4 + 0] * inv, oacc[b][4 * g4 + 1] * inv);
+          w[1] = pack_bf16(oacc[b][4 * g4 + 2] * inv, oacc[b][4 * g4 + 3] * inv);
+          *reinterpret_cast<u32x2*>(orow + 32 * b + 8 * g4 + 4 * h) = w;
+        }
+      if (a.lse != nullptr && h == 0) a.lse[(size_t)hq * a.N + row] = lse2 * kLn2;
+    }
+  } else {
+    const size_t prow = ((size_t)it.slot * a.Hq + hq) * BQ + wave * 32 + n;
+    float* orow = a.ws_o + prow * D;
+#pragma unroll
+    for (int b = 0; b < DBLK; ++b)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        floatx4 w;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) w[r] = oacc[b][4 * g4 + r] * inv;
+        *reinterpret_cast<floatx4*>(orow + 32 * b + 8 * g4 + 4 * h) = w;
+      }
+    if (h == 0) a.ws_lse[prow] = lse2;
+  }
+}
+
+// Combines the partial results of a query tile whose key list was cut into slices.
+template <int D>
+__global__ __launch_bounds__(256) void merge_kernel(const PrefillArgs a) {
+  const int mid = blockIdx.x / a.Hq, hq = blockIdx.x % a.Hq;
+  const MergeItem mi = a.merges[mid];
+  constexpr int C4 = D / 4;
+  for (int task = threadIdx.x; task < BQ * C4; task += 256) {
+    const int r = task / C4, c4 = task % C4;
+    const int row = mi.qtile * BQ + r;
+    if (row >= a.N) continue;
+    float mx = -INFINITY;
+    for (int s = 0; s < mi.n_splits; ++s)
+      mx = fmaxf(mx, a.ws_lse[((size_t)(mi.slot0 + s) * a.Hq + hq) * BQ + r]);
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    float wsum = 0.f;
+    for (int s = 0; s < mi.n_splits; ++s) {
+      const size_t prow = ((size_t)(mi.slot0 + s) * a.Hq + hq) * BQ + r;
+      const float w = __builtin_amdgcn_exp2f(a.ws_lse[prow] - mx);
+      const floatx4 o = *reinterpret_cast<const floatx4*>(a.ws_o + prow * D + 4 * c4);
+      acc += o * w;
+      wsum += w;
+    }
+    const float inv = 1.f / wsum;
+    u32x2 w2;
+    w2[0] = pack_bf16(acc[0] * inv, acc[1] * inv);
+    w2[1] = pack_bf16(acc[2] * inv, acc[3] * inv);
+    *reinterpret_cast<u32x2*>(a.out + ((size_t)hq * a.N + row) * D + 4 * c4) = w2;
+    if (a.lse != nullptr && c4 == 0) a.lse[(size_t)hq * a.N + row] = (mx + __builtin_amdgcn_logf(wsum)) * kLn2;
+  }
+}
+
+}  // namespace
+
+size_t prefill_ws_bytes(const purekv_plan& p) {
+  return (size_t)p.n_slots * p.g.Hq * BQ * (p.g.d + 1) * sizeof(float);
+}
+
+int launch_prefill(const purekv_plan& p, const void* q, const void* k, const void* v, void* out, float* lse,
+                   void* ws, hipStream_t st) {
+  PrefillArgs a;
+  a.q = static_cast<const uint16_t*>(q);
+  a.k = static_cast<const uint16_t*>(k);
+  a.v = static_cast<const uint16_t*>(v);
+  a.out = static_cast<uint16_t*>(out);
+  a.lse = lse;
+  a.ws_o = static_cast<float*>(ws);
+  a.ws_lse = a.ws_o ? a.ws_o + (size_t)p.n_slots * p.g.Hq * BQ * p.g.d : nullptr;
+  a.tiles = p.d_tiles;
+  a.items = p.d_items;
+  a.merges = p.d_merges;
+  a.N = p.g.N;
+  a.Nv = p.g.Nv;
+  a.P = p.g.P;
+  a.Hq = p.g.Hq;
+  a.G = p.g.G;
+  a.pattern = p.g.pattern;
+  a.scale_log2 = p.g.scale * kLog2e;
+  const dim3 grid((unsigned)(p.items.size() * p.g.Hq)), block(256);
+  const dim3 mgrid((unsigned)(p.merges.size() * p.g.Hq));
+  if (p.g.d == 128) {
+    hipLaunchKernelGGL(prefill_kernel<128>, grid, block, 0, st, a);
+    if (!p.merges.empty()) hipLaunchKernelGGL(merge_kernel<128>, mgrid, block, 0, st, a);
+  } else {
+    hipLaunchKernelGGL(prefill_kernel<64>, grid, block, 0, st, a);
+    if (!p.merges.empty()) hipLaunchKernelGGL(merge_kernel<64>, mgrid, block, 0, st, a);
+  }
+  PUREKV_HIP_TRY(hipGetLastError());
+  return PUREKV_OK;
+}
+
+}  // namespace purekv

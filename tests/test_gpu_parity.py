@@ -1,0 +1,258 @@
+"""GPU parity: every C-ABI compute call against the CPU oracle on the same seeded bf16 bits.
+
+Tolerances (written here, derived in the design notes): attention max-abs 2e-2 / mean-abs 2e-3;
+column sums relative 1e-3; kept-index sets exact outside a 1e-5 band around the h-th score;
+compacted K/V bit-exact given the indices.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_25600_amd as pk
+from oracle import purekv_oracle as orc
+from workloads import WORKLOADS, generate, small_variant
+
+from gpu_util import (IMPORTANCE_REL, SCORE_BAND, bits_of, check_attention, check_kept_sets, f64_of, to_dev)
+
+pytestmark = pytest.mark.gpu
+
+F64 = orc.bf16_bits_to_f64
+
+SMALL = {
+    "tiny_4f": WORKLOADS["tiny_4f"],
+    # ragged everywhere: P = 35 (no tile alignment), N = 124 < one query tile, d = 64
+    "ragged_3f": small_variant("ragged_3f"),
+    # query tiles straddle frame boundaries (P = 576 = 4.5 tiles), GQA 4:1, d = 128, one ragged tail tile
+    "straddle_3f": small_variant("straddle_3f", n_frames=3, patch_h=24, patch_w=24, n_text=70, n_q_heads=4,
+                                 n_kv_heads=1, head_dim=128),
+    # no text at all, single KV head per query head
+    "notext_5f": small_variant("notext_5f", n_frames=5, patch_h=8, patch_w=8, n_text=0, n_q_heads=2, n_kv_heads=2,
+                               head_dim=128),
+    # long text tail so that the text rows' key lists are split across work items and merged
+    "longtext_2f": small_variant("longtext_2f", n_frames=2, patch_h=16, patch_w=16, n_text=2100, n_q_heads=2,
+                                 n_kv_heads=1, head_dim=128),
+}
+
+
+def _plan(wl, pattern):
+    return pk.Plan.for_workload(wl, pattern)
+
+
+@pytest.mark.parametrize("pattern", [0, 1, 2, 3])
+@pytest.mark.parametrize("name", list(SMALL))
+def test_prefill_matches_oracle(name, pattern):
+    wl = SMALL[name]
+    inp = generate(wl, seed=11)
+    print(f"[case] prefill {name} pattern={pattern} N={wl.n_tokens}", flush=True)
+    plan = _plan(wl, pattern)
+    out, lse = pk.purekv_st_spattn_prefill(plan, to_dev(inp.q), to_dev(inp.k), to_dev(inp.v), want_lse=True)
+    torch.cuda.synchronize()
+    ref, ref_lse = orc.masked_attention(F64(inp.q), F64(inp.k), F64(inp.v), wl.n_frames, wl.patches, wl.n_text,
+                                        pattern)
+    check_attention(f64_of(out), ref, f"{name}/p{pattern}")
+    assert np.abs(f64_of(lse) - ref_lse).max() < 2e-3
+    if name == "longtext_2f":
+        assert plan.counts()["n_split_qtiles"] > 0  # the merge path ran
+
+
+def test_prefill_is_deterministic_and_output_buffer_reuse():
+    wl = SMALL["straddle_3f"]
+    inp = generate(wl, seed=3)
+    plan = _plan(wl, 3)
+    q, k, v = to_dev(inp.q), to_dev(inp.k), to_dev(inp.v)
+    a = pk.purekv_st_spattn_prefill(plan, q, k, v)
+    b = torch.full_like(a, float("nan"))
+    pk.purekv_st_spattn_prefill(plan, q, k, v, out=b)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(a), bits_of(b))
+
+
+def test_prefill_custom_scale():
+    wl = SMALL["ragged_3f"]
+    inp = generate(wl, seed=5)
+    plan = pk.Plan(wl.n_frames, wl.patch_h, wl.patch_w, wl.n_text, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, 3, 0.05)
+    out = pk.purekv_st_spattn_prefill(plan, to_dev(inp.q), to_dev(inp.k), to_dev(inp.v))
+    ref, _ = orc.masked_attention(F64(inp.q), F64(inp.k), F64(inp.v), wl.n_frames, wl.patches, wl.n_text, 3,
+                                  scale=float(np.float32(0.05)))
+    check_attention(f64_of(out), ref, "custom scale")
+
+
+@pytest.mark.parametrize("name,pattern,w", [
+    ("tiny_4f", 0, 32), ("tiny_4f", 3, 32), ("tiny_4f", 3, 100), ("tiny_4f", 2, 200), ("tiny_4f", 0, 288),
+    ("ragged_3f", 3, 19), ("ragged_3f", 1, 50), ("straddle_3f", 3, 70), ("straddle_3f", 0, 700),
+    ("notext_5f", 3, 33), ("longtext_2f", 0, 2100),
+])
+def test_importance_matches_oracle(name, pattern, w):
+    wl = SMALL[name]
+    inp = generate(wl, seed=12)
+    print(f"[case] importance {name} pattern={pattern} w={w}", flush=True)
+    plan = _plan(wl, pattern)
+    q, k, v = to_dev(inp.q), to_dev(inp.k), to_dev(inp.v)
+    _, lse = pk.purekv_st_spattn_prefill(plan, q, k, v, want_lse=True)
+    c = pk.purekv_lowlayer_importance(plan, q, k, lse, w)
+    torch.cuda.synchronize()
+    ref = orc.window_column_sums(F64(inp.q), F64(inp.k), wl.n_frames, wl.patches, wl.n_text, pattern, w)
+    got = f64_of(c)
+    assert got.shape == ref.shape
+    if ref.size:
+        assert np.all(np.abs(got - ref) <= IMPORTANCE_REL * np.maximum(np.abs(ref), 1e-12)), \
+            f"worst rel {np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-12)):.3g}"
+    # masked-out pairs contribute exactly nothing: a column no window row can see is exactly 0
+    assert np.all(got[ref == 0] == 0)
+
+
+@pytest.mark.parametrize("n_keys,h", [(256, 25), (256, 0), (256, 256), (1000, 1), (5000, 999), (40000, 8000)])
+def test_topk_exact_on_given_scores(n_keys, h):
+    """Stage-isolated: identical fp32 scores on both sides, so the kept sets must be identical (ties included)."""
+    w = 16
+    n = n_keys + w
+    plan = pk.Plan(1, 1, n_keys, w, 3, 3, 64, 0)  # geometry only carries N and Hkv here
+    rng = np.random.default_rng(n_keys + h)
+    s = rng.random((3, n_keys)).astype(np.float32)
+    s[1] = np.round(s[1] * 8) / 8                 # heavy ties
+    s[2, ::3] = 0.0                               # zeros, some negative zero
+    s[2, 3::6] = -0.0
+    idx = pk.purekv_topk_select(plan, torch.from_numpy(s).cuda(), None, w, h)
+    torch.cuda.synchronize()
+    ref = orc.topk_select(s.astype(np.float64), h, n, w)
+    assert np.array_equal(idx.cpu().numpy(), ref)
+
+
+def test_topk_negative_and_mixed_scores():
+    w, n_keys = 8, 3000
+    plan = pk.Plan(1, 1, n_keys, w, 2, 2, 64, 0)
+    rng = np.random.default_rng(9)
+    s = rng.standard_normal((2, n_keys)).astype(np.float32)
+    s[1] = -np.abs(s[1])
+    for h in (1, 500, 2999):
+        idx = pk.purekv_topk_select(plan, torch.from_numpy(s).cuda(), None, w, h)
+        ref = orc.topk_select(s.astype(np.float64), h, n_keys + w, w)
+        assert np.array_equal(idx.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("name", ["tiny_4f", "ragged_3f", "straddle_3f"])
+def test_vnorm_scores_and_selection_layers(name):
+    """Eq. 3 / Eq. 4: several layers' V share one C; scores within fp32 rounding, kept sets exact outside the band."""
+    wl = SMALL[name]
+    n, w = wl.n_tokens, wl.window
+    h = max(1, orc.budget(n, w, 0.3))
+    layers = [generate(wl, seed=20 + l) for l in range(3)]
+    rng = np.random.default_rng(1)
+    c = rng.random((wl.n_kv_heads, n - w)).astype(np.float32)
+    plan = _plan(wl, 3)
+    v_all = torch.stack([to_dev(x.v) for x in layers])
+    idx, s = pk.purekv_topk_select(plan, torch.from_numpy(c).cuda(), v_all, w, h, want_scores=True)
+    idx2 = pk.purekv_topk_select(plan, torch.from_numpy(c).cuda(), v_all, w, h)  # workspace path
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), idx2.cpu().numpy())
+    for l, x in enumerate(layers):
+        s_ref = orc.vnorm_scores(c.astype(np.float64), F64(x.v))
+        assert np.all(np.abs(f64_of(s[l]) - s_ref) <= 2e-6 * np.abs(s_ref) + 1e-30)
+        check_kept_sets(idx[l].cpu().numpy(), orc.topk_select(s_ref, h, n, w), s_ref, h)
+
+
+@pytest.mark.parametrize("name", ["tiny_4f", "ragged_3f", "straddle_3f"])
+def test_compaction_bit_exact_and_append(name):
+    wl = SMALL[name]
+    n, w = wl.n_tokens, wl.window
+    h = orc.budget(n, w, 0.4)
+    layers = [generate(wl, seed=30 + l) for l in range(2)]
+    rng = np.random.default_rng(2)
+    idx = np.stack([orc.topk_select(rng.random((wl.n_kv_heads, n - w)), h, n, w) for _ in layers])
+    plan = _plan(wl, 3)
+    k_all = torch.stack([to_dev(x.k) for x in layers])
+    v_all = torch.stack([to_dev(x.v) for x in layers])
+    cap = h + w + 3
+    kc = torch.zeros((2, wl.n_kv_heads, cap, wl.head_dim), dtype=torch.bfloat16, device="cuda")
+    vc = torch.zeros_like(kc)
+    pk.purekv_kv_compact(plan, k_all, v_all, torch.from_numpy(idx).cuda(), cap=cap, kc=kc, vc=vc)
+    torch.cuda.synchronize()
+    for l, x in enumerate(layers):
+        kr, vr = orc.compact(x.k, x.v, idx[l])
+        assert np.array_equal(bits_of(kc[l])[:, :h + w], kr) and np.array_equal(bits_of(vc[l])[:, :h + w], vr)
+        assert not bits_of(kc[l])[:, h + w:].any()  # rows beyond n_keep untouched
+    # append one decoded token to layer 0's cache
+    x = layers[0]
+    n1 = pk.purekv_kv_append(plan, to_dev(x.k_new[0]) if x.k_new.shape[0] else to_dev(x.k[:, 0]),
+                             to_dev(x.v_new[0]) if x.v_new.shape[0] else to_dev(x.v[:, 0]), kc[0], vc[0], h + w)
+    torch.cuda.synchronize()
+    assert n1 == h + w + 1
+    src = x.k_new[0] if x.k_new.shape[0] else x.k[:, 0]
+    assert np.array_equal(bits_of(kc[0])[:, h + w], src)
+
+
+@pytest.mark.parametrize("hq,hkv,d,n_cached", [(2, 1, 64, 57), (28, 4, 128, 1690), (32, 8, 128, 948), (12, 1, 128, 5),
+                                               (4, 4, 64, 1), (9, 3, 128, 333)])
+def test_decode_matches_oracle(hq, hkv, d, n_cached):
+    rng = np.random.default_rng(n_cached)
+    from workloads import f32_to_bf16_bits
+    q = f32_to_bf16_bits(rng.standard_normal((hq, d)).astype(np.float32))
+    cap = n_cached + 7
+    kc = f32_to_bf16_bits(rng.standard_normal((hkv, cap, d)).astype(np.float32))
+    vc = f32_to_bf16_bits(rng.standard_normal((hkv, cap, d)).astype(np.float32))
+    plan = pk.Plan(1, 4, 4, 4, hq, hkv, d, 3)
+    out = pk.purekv_decode_attn(plan, to_dev(q), to_dev(kc), to_dev(vc), n_cached)
+    torch.cuda.synchronize()
+    ref = orc.decode_attention(F64(q), F64(kc)[:, :n_cached], F64(vc)[:, :n_cached])
+    check_attention(f64_of(out), ref, "decode")
+
+
+def test_tiny_config_end_to_end_chain():
+    """Config 1: importance from the dense pass, ST-SpAttn prefill, V-norm top-h at ratio 0.2, compaction, one
+    decode step -- every stage fed by the GPU's own previous stage and compared with the oracle's chain."""
+    wl = WORKLOADS["tiny_4f"]
+    inp = generate(wl)
+    n, w = wl.n_tokens, wl.window
+    h = pk.purekv_budget(n, w, 0.2)
+    assert h == orc.budget(n, w, 0.2) == 25
+    q, k, v = to_dev(inp.q), to_dev(inp.k), to_dev(inp.v)
+    dense, st = _plan(wl, 0), _plan(wl, 3)
+    _, lse = pk.purekv_st_spattn_prefill(dense, q, k, v, want_lse=True)
+    c = pk.purekv_lowlayer_importance(dense, q, k, lse, w)
+    out = pk.purekv_st_spattn_prefill(st, q, k, v)
+    idx = pk.purekv_topk_select(st, c, v, w, h)
+    kc, vc = pk.purekv_kv_compact(st, k, v, idx, cap=h + w + 1)
+    n1 = pk.purekv_kv_append(st, to_dev(inp.k_new[0]), to_dev(inp.v_new[0]), kc, vc, h + w)
+    o_dec = pk.purekv_decode_attn(st, to_dev(inp.q_new[0]), kc, vc, n1)
+    torch.cuda.synchronize()
+
+    qf, kf, vf = F64(inp.q), F64(inp.k), F64(inp.v)
+    c_ref = orc.window_column_sums(qf, kf, wl.n_frames, wl.patches, wl.n_text, 0, w)
+    s_ref = orc.vnorm_scores(c_ref, vf)
+    idx_ref = orc.topk_select(s_ref, h, n, w)
+    out_ref, _ = orc.masked_attention(qf, kf, vf, wl.n_frames, wl.patches, wl.n_text, 3)
+    check_attention(f64_of(out), out_ref, "chain prefill")
+    assert np.all(np.abs(f64_of(c) - c_ref) <= IMPORTANCE_REL * np.maximum(c_ref, 1e-12))
+    idx_g = idx.cpu().numpy()
+    check_kept_sets(idx_g, idx_ref, s_ref, h)
+    kr, vr = orc.compact(inp.k, inp.v, idx_g)  # bit-exact given the indices the GPU chose
+    assert np.array_equal(bits_of(kc)[:, :h + w], kr) and np.array_equal(bits_of(vc)[:, :h + w], vr)
+    kcat = np.concatenate([F64(kr), F64(inp.k_new[0])[:, None]], 1)
+    vcat = np.concatenate([F64(vr), F64(inp.v_new[0])[:, None]], 1)
+    check_attention(f64_of(o_dec), orc.decode_attention(F64(inp.q_new[0]), kcat, vcat), "chain decode")
+
+
+def test_gpu_argument_errors():
+    wl = WORKLOADS["tiny_4f"]
+    plan = _plan(wl, 3)
+    inp = generate(wl)
+    q, k, v = to_dev(inp.q), to_dev(inp.k), to_dev(inp.v)
+    lib = pk.raw()
+    c = torch.zeros((1, 256), dtype=torch.float32, device="cuda")
+    idx = torch.zeros((1, 57), dtype=torch.int32, device="cuda")
+    P = lambda t: t.data_ptr()  # noqa: E731
+    assert lib.purekv_lowlayer_importance(plan.handle, P(q), P(k), P(c), 0, P(c), None, 0, None) == pk.EINVAL
+    assert lib.purekv_lowlayer_importance(plan.handle, P(q), P(k), P(c), 289, P(c), None, 0, None) == pk.EINVAL
+    assert lib.purekv_topk_select(plan.handle, P(c), None, 0, 1, 32, 257, P(idx), None, None, 0, None) == pk.EINVAL
+    assert lib.purekv_topk_select(plan.handle, P(c), P(v), 0, 1, 32, 25, P(idx), None, None, 0, None) == pk.EWORKSPACE
+    assert lib.purekv_topk_select(plan.handle, P(c), None, 0, 2, 32, 25, P(idx), None, None, 0, None) == pk.EINVAL
+    assert lib.purekv_kv_compact(plan.handle, P(k), P(v), 0, 1, P(idx), 57, P(k), P(v), 56, None) == pk.EINVAL
+    assert lib.purekv_kv_append(plan.handle, P(k), P(v), P(k), P(v), 57, 57, None) == pk.EINVAL
+    assert lib.purekv_decode_attn(plan.handle, P(q), P(k), P(v), 0, 57, P(q), P(c), 1 << 20, None) == pk.EINVAL
+    assert lib.purekv_decode_attn(plan.handle, P(q), P(k), P(v), 57, 57, P(q), None, 0, None) == pk.EWORKSPACE
+    long = pk.Plan.for_workload(SMALL["longtext_2f"], 3)
+    assert long.workspace_bytes(pk.OP_PREFILL) > 0
+    assert lib.purekv_st_spattn_prefill(long.handle, P(q), P(k), P(v), P(q), None, None, 0, None) == pk.EWORKSPACE
+    torch.cuda.synchronize()
