@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Benchmark of the PureKV hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input, in the paper's order
+(Sec. 3.1 / 3.2), for the 32-frame Qwen2.5-VL-7B-shaped workload:
+    low layer : dense causal prefill (+ log-sum-exp)  -> recent-window column sums C (Eq. 2)
+                -> V-norm top-h (Eq. 3) -> compaction
+    high layer: ST-SpAttn prefill -> V-norm top-h with the low layer's C (Eq. 4) -> compaction
+                -> append one decoded token -> decode attention on the compact cache
+All inputs are resident in HBM before the timed region.  Prints one JSON line.
+
+`value` is the metric's headline: TFLOP/s of the ST-SpAttn prefill counted on the key tiles it visits
+(prefill kernel + merge of split rows), from HIP events recorded on the launch stream inside the timed
+steps.  The same line carries the per-stage times, GB/s of the HBM-bound stages, the roofline object and
+the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBPS = 8000.0
+STAGES = ["dense_prefill", "importance", "topk_low", "compact_low", "st_prefill", "topk_high", "compact_high",
+          "append_decode"]
+
+
+def blas_threads() -> int:
+    """Threads NumPy's BLAS actually uses for the oracle's matrix products."""
+    try:
+        from threadpoolctl import threadpool_info
+        n = [p.get("num_threads", 0) for p in threadpool_info() if p.get("user_api") == "blas"]
+        if n:
+            return int(max(n))
+    except Exception:
+        pass
+    return int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="qwen25vl_32f")
+    ap.add_argument("--ratio", type=float, default=0.2)
+    ap.add_argument("--batched-layers", type=int, default=26, help="layers per batched top-k/compaction launch")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=28, help="query heads in the oracle's timed sample")
+    ap.add_argument("--only-stage", default=None, choices=STAGES,
+                    help="profiling aid: after one full warm-up step run only this stage --steps times and exit")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2510_25600_amd as pk
+    from workloads import WORKLOADS, generate
+
+    wl = WORKLOADS[args.workload]
+    n, w, d, hq, hkv = wl.n_tokens, wl.window, wl.head_dim, wl.n_q_heads, wl.n_kv_heads
+    h = pk.purekv_budget(n, w, args.ratio)
+    n_keep, cap = h + w, h + w + 1
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    def to_dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(dev)
+
+    low, high = generate(wl, seed=wl.seed, decode_steps=1), generate(wl, seed=wl.seed + 1, decode_steps=1)
+    q0, k0, v0 = to_dev(low.q), to_dev(low.k), to_dev(low.v)
+    q1, k1, v1 = to_dev(high.q), to_dev(high.k), to_dev(high.v)
+    q_new, k_new, v_new = to_dev(high.q_new[0]), to_dev(high.k_new[0]), to_dev(high.v_new[0])
+    dense = pk.Plan.for_workload(wl, pk.PATTERN_DENSE)
+    st = pk.Plan.for_workload(wl, pk.PATTERN_ST)
+
+    out0, out1 = torch.empty_like(q0), torch.empty_like(q1)
+    lse = torch.empty((hq, n), dtype=torch.float32, device=dev)
+    c = torch.empty((hkv, n - w), dtype=torch.float32, device=dev)
+    idx0 = torch.empty((1, hkv, n_keep), dtype=torch.int32, device=dev)
+    idx1 = torch.empty((1, hkv, n_keep), dtype=torch.int32, device=dev)
+    kc0 = torch.empty((hkv, cap, d), dtype=torch.bfloat16, device=dev)
+    vc0, kc1, vc1 = torch.empty_like(kc0), torch.empty_like(kc0), torch.empty_like(kc0)
+    o_dec = torch.empty((hq, d), dtype=torch.bfloat16, device=dev)
+
+    def step(ev=None):
+        def mark(i):
+            if ev is not None:
+                ev[i].record()
+        mark(0)
+        pk.purekv_st_spattn_prefill(dense, q0, k0, v0, out=out0, lse=lse)
+        mark(1)
+        pk.purekv_lowlayer_importance(dense, q0, k0, lse, w, c_out=c)
+        mark(2)
+        pk.purekv_topk_select(dense, c, v0, w, h, idx_out=idx0)
+        mark(3)
+        pk.purekv_kv_compact(dense, k0, v0, idx0[0], cap=cap, kc=kc0, vc=vc0)
+        mark(4)
+        pk.purekv_st_spattn_prefill(st, q1, k1, v1, out=out1)
+        mark(5)
+        pk.purekv_topk_select(st, c, v1, w, h, idx_out=idx1)
+        mark(6)
+        pk.purekv_kv_compact(st, k1, v1, idx1[0], cap=cap, kc=kc1, vc=vc1)
+        mark(7)
+        pk.purekv_kv_append(st, k_new, v_new, kc1, vc1, n_keep)
+        pk.purekv_decode_attn(st, q_new, kc1, vc1, n_keep + 1, out=o_dec)
+        mark(8)
+
+    if args.only_stage is not None:
+        step()
+        torch.cuda.synchronize()
+        one = {
+            "dense_prefill": lambda: pk.purekv_st_spattn_prefill(dense, q0, k0, v0, out=out0, lse=lse),
+            "importance": lambda: pk.purekv_lowlayer_importance(dense, q0, k0, lse, w, c_out=c),
+            "topk_low": lambda: pk.purekv_topk_select(dense, c, v0, w, h, idx_out=idx0),
+            "compact_low": lambda: pk.purekv_kv_compact(dense, k0, v0, idx0[0], cap=cap, kc=kc0, vc=vc0),
+            "st_prefill": lambda: pk.purekv_st_spattn_prefill(st, q1, k1, v1, out=out1),
+            "topk_high": lambda: pk.purekv_topk_select(st, c, v1, w, h, idx_out=idx1),
+            "compact_high": lambda: pk.purekv_kv_compact(st, k1, v1, idx1[0], cap=cap, kc=kc1, vc=vc1),
+            "append_decode": lambda: (pk.purekv_kv_append(st, k_new, v_new, kc1, vc1, n_keep),
+                                      pk.purekv_decode_attn(st, q_new, kc1, vc1, n_keep + 1, out=o_dec)),
+        }[args.only_stage]
+        for _ in range(args.steps):
+            one()
+        torch.cuda.synchronize()
+        print(f"ran {args.only_stage} x {args.steps}")
+        return 0
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(9)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(events[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    stage_ms = {name: float(np.mean([events[s][i].elapsed_time(events[s][i + 1]) for s in range(args.steps)]))
+                for i, name in enumerate(STAGES)}
+
+    # ---- back-to-back launches of single stages (no other kernel in between): per-call durations ----
+    def time_calls(fn, reps=30):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    st_ms = time_calls(lambda: pk.purekv_st_spattn_prefill(st, q1, k1, v1, out=out1))
+    dense_ms = time_calls(lambda: pk.purekv_st_spattn_prefill(dense, q0, k0, v0, out=out0, lse=lse), reps=10)
+
+    # batched over the high layers (Eq. 4: every high layer scores with the same C and its own V)
+    L = args.batched_layers
+    v_all = torch.empty((L, hkv, n, d), dtype=torch.bfloat16, device=dev)
+    k_all = torch.empty_like(v_all)
+    for l in range(L):  # distinct data per layer, derived on the device from the two generated layers
+        v_all[l] = v1.roll(l, dims=1)
+        k_all[l] = k1.roll(l, dims=1)
+    idx_all = torch.empty((L, hkv, n_keep), dtype=torch.int32, device=dev)
+    kc_all = torch.empty((L, hkv, n_keep, d), dtype=torch.bfloat16, device=dev)
+    vc_all = torch.empty_like(kc_all)
+    topk_b_ms = time_calls(lambda: pk.purekv_topk_select(st, c, v_all, w, h, idx_out=idx_all))
+    comp_b_ms = time_calls(lambda: pk.purekv_kv_compact(st, k_all, v_all, idx_all, kc=kc_all, vc=vc_all))
+    del v_all, k_all, kc_all, vc_all
+
+    kept_flops, mask_flops = st.kept_tile_flops(), st.mask_flops()
+    dense_kept = dense.kept_tile_flops()
+    st_tflops = kept_flops / (st_ms * 1e-3) / 1e12
+    topk_bytes = (n - w) * d * 2 * hkv + (n - w) * 4 * hkv * 3 + n_keep * 4 * hkv   # V read, C read, S write+read, idx
+    comp_bytes = 2 * 2 * n_keep * d * 2 * hkv + n_keep * 4 * hkv                    # K,V rows read + written, idx
+    dec_bytes = 2 * (n_keep + 1) * d * 2 * hkv
+
+    result = {
+        "metric": "st_spattn_prefill_kept_tile_tflops",
+        "value": round(st_tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.n_frames}f x {wl.patch_h}x{wl.patch_w} + {wl.n_text} text = {n} tokens, "
+                               f"{hq}q/{hkv}kv heads, d={d}, keep ratio {args.ratio} (h={h}, w={w})",
+                   "tile": f"{pk.BQ}x{pk.BK}", "step": "low layer (dense prefill+LSE, importance, top-h, compaction) + "
+                   "high layer (ST-SpAttn prefill, top-h, compaction, append+decode)"},
+        "prefill_ms_per_layer": round(st_ms, 4),
+        "mfma_peak_frac": round(st_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+        "mask_tflops": round(mask_flops / (st_ms * 1e-3) / 1e12, 2),
+        "dense_prefill_ms_per_layer": round(dense_ms, 4),
+        "dense_prefill_tflops": round(dense_kept / (dense_ms * 1e-3) / 1e12, 2),
+        "stage_ms_in_step": {k_: round(v_, 4) for k_, v_ in stage_ms.items()},
+        "per_layer_gbps": {
+            "topk": round(topk_bytes / (stage_ms["topk_high"] * 1e-3) / 1e9, 1),
+            "compaction": round(comp_bytes / (stage_ms["compact_high"] * 1e-3) / 1e9, 1),
+            "decode": round(dec_bytes / (stage_ms["append_decode"] * 1e-3) / 1e9, 1),
+        },
+        "batched": {
+            "layers": L,
+            "topk_ms": round(topk_b_ms, 4), "topk_gbps": round(L * topk_bytes / (topk_b_ms * 1e-3) / 1e9, 1),
+            "compaction_ms": round(comp_b_ms, 4),
+            "compaction_gbps": round(L * comp_bytes / (comp_b_ms * 1e-3) / 1e9, 1),
+            "compaction_hbm_frac": round(L * comp_bytes / (comp_b_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "topk_hbm_frac": round(L * topk_bytes / (topk_b_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        },
+        "roofline": {
+            "kernel": "prefill_kernel<128, ST> (+ merge_kernel for split rows), one ST-SpAttn layer",
+            "bound": "mfma", "achieved": round(st_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(st_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+        },
+        "context": "paper: 5.0x KV compression, 3.16x prefill speed-up, whole model on 1x A100 40GB (not comparable)",
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import purekv_oracle as orc
+        heads = list(range(0, hq, max(1, hq // args.cpu_heads)))[:args.cpu_heads]
+        qf, kf, vf = (orc.bf16_bits_to_f64(x) for x in (high.q, high.k, high.v))
+        t0 = time.perf_counter()
+        orc.masked_attention(qf, kf, vf, wl.n_frames, wl.patches, wl.n_text, 3, heads=heads)
+        t_cpu = time.perf_counter() - t0
+        sample_flops = mask_flops * len(heads) / hq
+        result["cpu_baseline"] = {
+            "value": round(sample_flops / t_cpu / 1e12, 5), "unit": "TFLOP/s", "cores": blas_threads(),
+            "kind": "oracle",
+            "sample": f"ST-SpAttn attention of {len(heads)} of {hq} query heads, all {n} rows, NumPy fp64 dense "
+                      f"scores under the boolean mask; flops counted on allowed pairs only; {t_cpu:.1f} s",
+        }
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -18,6 +18,7 @@ namespace {
 
 constexpr int BQ = PUREKV_BQ;
 constexpr int BK = PUREKV_BK;
+constexpr float kRescaleGap = 8.0f;
 
 struct PrefillArgs {
   const uint16_t* q;
@@ -35,14 +36,27 @@ struct PrefillArgs {
   float scale_log2;  // softmax scale * log2(e)
 };
 
-template <int D>
+// Element offset of 16-byte slot `u` of row `r` in a row-major bf16 LDS tile with ROW elements per row.
+// The slot index is XOR-ed with the row so that the 16 lanes the LDS serves together (rows that differ
+// in their low four bits) fall into 16 different 16-byte slots of a 256-byte bank period.
+template <int ROW>
+__device__ __forceinline__ int swz(int r, int u) {
+  if constexpr (ROW == 128) {
+    return r * 128 + ((u ^ (r & 15)) * 8);
+  } else {  // 64 elements = 128 bytes: two rows share one 256-byte period
+    return (r >> 1) * 128 + ((((r & 1) * 8 + u) ^ ((r >> 1) & 15)) * 8);
+  }
+}
+
+// ST = false: dense causal pattern only (no frame arithmetic, no side keys); ST = true: any pattern.
+template <int D, bool ST>
 __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
   constexpr int KSTEPS = D / 16;        // MFMA k-steps of the score product
   constexpr int DBLK = D / 32;          // 32-row blocks of O^T
   constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
   constexpr int KCH = BK * CPR / 256;   // K chunks staged per thread
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[BK * D];
-  __shared__ __attribute__((aligned(16))) uint16_t Vt[D * BK];
+  __shared__ __attribute__((aligned(16))) uint16_t Ks2[2][BK * D];   // double-buffered
+  __shared__ __attribute__((aligned(16))) uint16_t Vt2[2][D * BK];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, h = lane >> 5;
@@ -52,7 +66,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
   const int rowc = min(row, a.N - 1);
 
   // Block part of the mask for this lane's row: key j allowed iff j <= rowc and (j <= a_i or j >= lo_i).
-  const bool sparse_row = a.pattern != 0u && rowc < a.Nv;
+  const bool sparse_row = ST && a.pattern != 0u && rowc < a.Nv;
   const int frame = sparse_row ? rowc / a.P : 0;
   const int a_i = sparse_row ? min(rowc, a.P - 1) : rowc;
   const int lo_i = sparse_row ? ((a.pattern & 1u) ? frame * a.P : rowc + 1) : 0;
@@ -75,7 +89,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
     for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
 
   // ---- side keys of the temporal path (first slice of the row's list only) ----
-  if (it.split == 0 && (a.pattern & 2u)) {
+  if (ST && it.split == 0 && (a.pattern & 2u)) {
     const bool has_prev = sparse_row && frame >= 2;
     const bool has_self = sparse_row && !(a.pattern & 1u) && frame >= 1;
     const int js[2] = {has_prev ? rowc - a.P : rowc, rowc};
@@ -137,11 +151,13 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
       }
     }
   };
-  auto store_tile = [&]() {
+  auto store_tile = [&](int buf) {
+    uint16_t* Ks = Ks2[buf];
+    uint16_t* Vt = Vt2[buf];
 #pragma unroll
     for (int r = 0; r < KCH; ++r) {
       const int id = tid + 256 * r, rk = id / CPR, cc = id % CPR;
-      *reinterpret_cast<u32x4*>(Ks + rk * D + ((cc ^ (rk & 7)) * 8)) = kreg[r];
+      *reinterpret_cast<u32x4*>(Ks + swz<D>(rk, cc)) = kreg[r];
     }
     if (v_active) {
       // quad vg holds keys 16*grp + 8*aa + 4*hh + 0..3; the MFMA k-order wants, per 16 keys,
@@ -159,57 +175,82 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
           w[0] = (x0 & 0xffffu) | (x1 << 16);
           w[1] = (x2 & 0xffffu) | (x3 << 16);
         }
-        *reinterpret_cast<u32x2*>(Vt + dd * BK + ((unit ^ (dd & 7)) * 8) + half * 4) = w;
+        *reinterpret_cast<u32x2*>(Vt + swz<BK>(dd, unit) + half * 4) = w;
       }
     }
   };
 
-  if (it.n_tiles > 0) load_tile((a.tiles[it.list_begin] >> 1) * BK);
+  // Pipeline: tile t is computed from LDS buffer t&1 while tile t+1 sits in registers (loaded one
+  // iteration earlier) and is written to the other buffer; one barrier per tile.
+  if (it.n_tiles > 0) {
+    load_tile((a.tiles[it.list_begin] >> 1) * BK);
+    store_tile(0);
+    if (it.n_tiles > 1) load_tile((a.tiles[it.list_begin + 1] >> 1) * BK);
+    __syncthreads();
+  }
 
   for (int t = 0; t < it.n_tiles; ++t) {
     const int entry = a.tiles[it.list_begin + t];
     const int k0 = (entry >> 1) * BK;
     const bool full = entry & 1;
-    __syncthreads();  // every wave has finished reading the previous tile
-    store_tile();
-    __syncthreads();
-    if (t + 1 < it.n_tiles) load_tile((a.tiles[it.list_begin + t + 1] >> 1) * BK);  // in flight during the math
+    const uint16_t* Ks = Ks2[t & 1];
+    const uint16_t* Vt = Vt2[t & 1];
 
-    // S^T = K Q^T: two 32-key blocks x 32 queries
+    // S^T = K Q^T: two 32-key blocks x 32 queries; operand fragments are fetched one k-step ahead
     floatx16 sacc[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+    {
+      bf16x8 kf0 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(n, h));
+      bf16x8 kf1 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(32 + n, h));
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const int rk = 32 * kb + n;
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + rk * D + (((2 * s + h) ^ (n & 7)) * 8));
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[kb], 0, 0, 0);
+      for (int s = 0; s < KSTEPS; ++s) {
+        bf16x8 nk0 = kf0, nk1 = kf1;
+        if (s + 1 < KSTEPS) {
+          nk0 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(n, 2 * (s + 1) + h));
+          nk1 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(32 + n, 2 * (s + 1) + h));
+        }
+        sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[s], sacc[0], 0, 0, 0);
+        sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, qf[s], sacc[1], 0, 0, 0);
+        kf0 = nk0;
+        kf1 = nk1;
       }
+    }
 
-    // scale, mask, running maximum
+    // mask (partial tiles only: one wave-uniform branch, selects inside) and tile maximum on the raw scores
+    if (!full) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int j = k0 + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
+          const bool ok = ST ? ((j <= rowc) & ((j <= a_i) | (j >= lo_i))) : (j <= rowc);
+          sacc[kb][i] = ok ? sacc[kb][i] : -INFINITY;
+        }
+    }
     float mt = -INFINITY;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float x = sacc[kb][i] * a.scale_log2;
-        if (!full) {
-          const int j = k0 + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
-          const bool ok = (j <= rowc) && (j <= a_i || j >= lo_i);
-          x = ok ? x : -INFINITY;
-        }
-        sacc[kb][i] = x;
-        mt = fmaxf(mt, x);
-      }
-    mt = fmaxf(mt, other_half(mt));
-    const float m_new = fmaxf(m, mt);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-    m = m_new;
+      for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sacc[kb][i]);
+    mt = fmaxf(mt, other_half(mt)) * a.scale_log2;
+    // The reference maximum m only moves when a tile exceeds it by more than kRescaleGap (log2 units):
+    // probabilities then stay below 2^kRescaleGap, exact in fp32/bf16 range, and the accumulators are
+    // rescaled rarely.  The final normalisation divides the same factor out again.
+    if (__any(mt > m + kRescaleGap)) {
+      const float m_new = (mt > m + kRescaleGap) ? mt : m;
+      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m - m_ref);
+      l *= alpha;
+#pragma unroll
+      for (int b = 0; b < DBLK; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
+      m = m_new;
+    }
+    const float neg_m = (m == -INFINITY) ? 0.f : -m;
 
     // probabilities -> bf16 B-operand fragments; pf[ks] covers keys 16*ks .. 16*ks+15 of the tile
     float psum = 0.f;
@@ -221,27 +262,31 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
         u32x4 pk;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          const float p0 = __builtin_amdgcn_exp2f(sacc[kb][8 * half + 2 * w] - m_use);
-          const float p1 = __builtin_amdgcn_exp2f(sacc[kb][8 * half + 2 * w + 1] - m_use);
-          psum += p0 + p1;
-          pk[w] = pack_bf16(p0, p1);
+          floatx2 p;
+          p[0] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * half + 2 * w], a.scale_log2, neg_m));
+          p[1] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * half + 2 * w + 1], a.scale_log2, neg_m));
+          psum += p[0] + p[1];
+          pk[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
         }
         pf[2 * kb + half] = __builtin_bit_cast(bf16x8, pk);
       }
-    l = l * alpha + psum;
+    l += psum;
 
-    // O^T = alpha * O^T + V^T P^T
+    // O^T += V^T P^T
 #pragma unroll
     for (int b = 0; b < DBLK; ++b) {
+      bf16x8 vf[4];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
+      for (int ks = 0; ks < 4; ++ks)
+        vf[ks] = *reinterpret_cast<const bf16x8*>(Vt + swz<BK>(32 * b + n, 2 * ks + h));
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const int dr = 32 * b + n;
-        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(Vt + dr * BK + (((2 * ks + h) ^ (n & 7)) * 8));
-        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks], oacc[b], 0, 0, 0);
-      }
+      for (int ks = 0; ks < 4; ++ks)
+        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks], pf[ks], oacc[b], 0, 0, 0);
     }
+
+    if (t + 1 < it.n_tiles) store_tile((t + 1) & 1);
+    __syncthreads();
+    if (t + 2 < it.n_tiles) load_tile((a.tiles[it.list_begin + t + 2] >> 1) * BK);
   }
 
   // ---- epilogue ----
@@ -278,35 +323,45 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
   }
 }
 
-// Combines the partial results of a query tile whose key list was cut into slices.
+// Combines the partial results of a query tile whose key list was cut into slices.  One workgroup
+// handles 16 rows of one (query tile, head): thread -> (row, 4 consecutive output elements).
+constexpr int MERGE_ROWS = 16;
 template <int D>
 __global__ __launch_bounds__(256) void merge_kernel(const PrefillArgs a) {
-  const int mid = blockIdx.x / a.Hq, hq = blockIdx.x % a.Hq;
+  constexpr int C4 = D / 4, RB = BQ / MERGE_ROWS;
+  const int rb = blockIdx.x % RB, hq = (blockIdx.x / RB) % a.Hq, mid = blockIdx.x / (RB * a.Hq);
   const MergeItem mi = a.merges[mid];
-  constexpr int C4 = D / 4;
-  for (int task = threadIdx.x; task < BQ * C4; task += 256) {
-    const int r = task / C4, c4 = task % C4;
-    const int row = mi.qtile * BQ + r;
-    if (row >= a.N) continue;
-    float mx = -INFINITY;
-    for (int s = 0; s < mi.n_splits; ++s)
-      mx = fmaxf(mx, a.ws_lse[((size_t)(mi.slot0 + s) * a.Hq + hq) * BQ + r]);
-    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-    float wsum = 0.f;
-    for (int s = 0; s < mi.n_splits; ++s) {
-      const size_t prow = ((size_t)(mi.slot0 + s) * a.Hq + hq) * BQ + r;
-      const float w = __builtin_amdgcn_exp2f(a.ws_lse[prow] - mx);
-      const floatx4 o = *reinterpret_cast<const floatx4*>(a.ws_o + prow * D + 4 * c4);
-      acc += o * w;
-      wsum += w;
+  const int r = rb * MERGE_ROWS + threadIdx.x / 16;
+  const int row = mi.qtile * BQ + r;
+  if (row >= a.N) return;
+  float mx = -INFINITY;
+  for (int s = 0; s < mi.n_splits; ++s)
+    mx = fmaxf(mx, a.ws_lse[((size_t)(mi.slot0 + s) * a.Hq + hq) * BQ + r]);
+  float wsum = 0.f;
+  floatx4 acc[C4 / 16];
+#pragma unroll
+  for (int c = 0; c < C4 / 16; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < mi.n_splits; ++s) {
+    const size_t prow = ((size_t)(mi.slot0 + s) * a.Hq + hq) * BQ + r;
+    const float w = __builtin_amdgcn_exp2f(a.ws_lse[prow] - mx);
+    wsum += w;
+#pragma unroll
+    for (int c = 0; c < C4 / 16; ++c) {
+      const int c4 = (threadIdx.x % 16) + 16 * c;
+      acc[c] += *reinterpret_cast<const floatx4*>(a.ws_o + prow * D + 4 * c4) * w;
     }
-    const float inv = 1.f / wsum;
-    u32x2 w2;
-    w2[0] = pack_bf16(acc[0] * inv, acc[1] * inv);
-    w2[1] = pack_bf16(acc[2] * inv, acc[3] * inv);
-    *reinterpret_cast<u32x2*>(a.out + ((size_t)hq * a.N + row) * D + 4 * c4) = w2;
-    if (a.lse != nullptr && c4 == 0) a.lse[(size_t)hq * a.N + row] = (mx + __builtin_amdgcn_logf(wsum)) * kLn2;
   }
+  const float inv = 1.f / wsum;
+#pragma unroll
+  for (int c = 0; c < C4 / 16; ++c) {
+    const int c4 = (threadIdx.x % 16) + 16 * c;
+    u32x2 w2;
+    w2[0] = pack_bf16(acc[c][0] * inv, acc[c][1] * inv);
+    w2[1] = pack_bf16(acc[c][2] * inv, acc[c][3] * inv);
+    *reinterpret_cast<u32x2*>(a.out + ((size_t)hq * a.N + row) * D + 4 * c4) = w2;
+  }
+  if (a.lse != nullptr && (threadIdx.x % 16) == 0)
+    a.lse[(size_t)hq * a.N + row] = (mx + __builtin_amdgcn_logf(wsum)) * kLn2;
 }
 
 }  // namespace
@@ -336,12 +391,19 @@ int launch_prefill(const purekv_plan& p, const void* q, const void* k, const voi
   a.pattern = p.g.pattern;
   a.scale_log2 = p.g.scale * kLog2e;
   const dim3 grid((unsigned)(p.items.size() * p.g.Hq)), block(256);
-  const dim3 mgrid((unsigned)(p.merges.size() * p.g.Hq));
+  const dim3 mgrid((unsigned)(p.merges.size() * p.g.Hq * (BQ / MERGE_ROWS)));
+  const bool sparse = p.g.pattern != PUREKV_PATTERN_DENSE;
   if (p.g.d == 128) {
-    hipLaunchKernelGGL(prefill_kernel<128>, grid, block, 0, st, a);
+    if (sparse)
+      hipLaunchKernelGGL((prefill_kernel<128, true>), grid, block, 0, st, a);
+    else
+      hipLaunchKernelGGL((prefill_kernel<128, false>), grid, block, 0, st, a);
     if (!p.merges.empty()) hipLaunchKernelGGL(merge_kernel<128>, mgrid, block, 0, st, a);
   } else {
-    hipLaunchKernelGGL(prefill_kernel<64>, grid, block, 0, st, a);
+    if (sparse)
+      hipLaunchKernelGGL((prefill_kernel<64, true>), grid, block, 0, st, a);
+    else
+      hipLaunchKernelGGL((prefill_kernel<64, false>), grid, block, 0, st, a);
     if (!p.merges.empty()) hipLaunchKernelGGL(merge_kernel<64>, mgrid, block, 0, st, a);
   }
   PUREKV_HIP_TRY(hipGetLastError());
