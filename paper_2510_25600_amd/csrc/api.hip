@@ -21,7 +21,7 @@ static int check_shape(const purekv_shape_t* s) {
   if (s->n_q_heads < 1 || s->n_kv_heads < 1 || s->n_q_heads % s->n_kv_heads != 0) return PUREKV_EINVAL;
   if (!(s->softmax_scale >= 0.f) || std::isinf(s->softmax_scale)) return PUREKV_EINVAL;
   const int64_t p = (int64_t)s->patch_h * s->patch_w, n = p * s->n_frames + s->n_text;
-  if (p > (1 << 24) || n > (int64_t)1 << 26) return PUREKV_EINVAL;  // indices are 32-bit on the device
+  if (p > (1 << 22) || n > (int64_t)1 << 22) return PUREKV_EINVAL;  // 32-bit byte offsets within one head's K/V
   if (s->head_dim != 64 && s->head_dim != 128) return PUREKV_EUNSUPPORTED;
   if (s->pattern > PUREKV_PATTERN_ST) return PUREKV_EUNSUPPORTED;
   return PUREKV_OK;

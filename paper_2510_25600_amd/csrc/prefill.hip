@@ -9,6 +9,11 @@
 // transposed (the contraction index of the second product is the key), both XOR-swizzled in 16-byte
 // units so the 128-bit operand reads are conflict-free.  The attention matrix never exists.
 //
+// Pipeline: K/V tiles travel HBM -> registers (bounds-checked buffer loads: rows past the end read as
+// zero, a tile index past the list reads nothing) -> LDS, double-buffered, one barrier per tile.  While
+// tile t is multiplied out of buffer t&1, tile t+1 is written to the other buffer and tile t+2 is in
+// flight.
+//
 // The temporal path's single previous-frame key (and the self key when the spatial path is off) is not
 // worth a tile: it enters as one extra online-softmax step per row, computed with vector ALU dot products.
 #include "common.h"
@@ -27,14 +32,24 @@ struct PrefillArgs {
   uint16_t* out;
   float* lse;
   float* ws_o;    // [n_slots, Hq, BQ, D] normalised partial outputs
-  float* ws_lse;  // [n_slots, Hq, BQ]    log2-domain log-sum-exp of the partial
+  float* ws_lse;  // [n_slots, Hq, BQ, 2] log2-domain log-sum-exp of the partial: {merge weight, exact}
   const int32_t* tiles;
   const WorkItem* items;
   const MergeItem* merges;
   int32_t N, Nv, P, Hq, G;
   uint32_t pattern;
   float scale_log2;  // softmax scale * log2(e)
+#ifdef PUREKV_PHASE_TRACE
+  unsigned long long* trace;  // [grid, 8] timestamps, development builds only
+#endif
 };
+
+#ifdef PUREKV_PHASE_TRACE
+#define PHASE_MARK(i) \
+  if (threadIdx.x == 0) a.trace[(size_t)blockIdx.x * 8 + (i)] = __builtin_readcyclecounter()
+#else
+#define PHASE_MARK(i)
+#endif
 
 // Element offset of 16-byte slot `u` of row `r` in a row-major bf16 LDS tile with ROW elements per row.
 // The slot index is XOR-ed with the row so that the 16 lanes the LDS serves together (rows that differ
@@ -48,8 +63,17 @@ __device__ __forceinline__ int swz(int r, int u) {
   }
 }
 
-// ST = false: dense causal pattern only (no frame arithmetic, no side keys); ST = true: any pattern.
-template <int D, bool ST>
+// Raw buffer descriptor over `bytes` bytes at `p`: loads past the end return zero instead of faulting.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
+}
+
+// ST  = false: dense causal pattern only (no frame arithmetic, no side keys); true: any pattern.
+// LSE = true : also keeps the exact fp32 row sum for the log-sum-exp output.
+template <int D, bool ST, bool LSE>
 __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
   constexpr int KSTEPS = D / 16;        // MFMA k-steps of the score product
   constexpr int DBLK = D / 32;          // 32-row blocks of O^T
@@ -58,6 +82,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks2[2][BK * D];   // double-buffered
   __shared__ __attribute__((aligned(16))) uint16_t Vt2[2][D * BK];
 
+  PHASE_MARK(0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, h = lane >> 5;
   const int item_id = blockIdx.x / a.Hq, hq = blockIdx.x % a.Hq, kvh = hq / a.G;
@@ -73,6 +98,58 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
 
   const uint16_t* kbase = a.k + (size_t)kvh * a.N * D;
   const uint16_t* vbase = a.v + (size_t)kvh * a.N * D;
+  const uint32_t slab_bytes = (uint32_t)a.N * D * 2u;
+  const __amdgpu_buffer_rsrc_t krs = make_rsrc(kbase, slab_bytes), vrs = make_rsrc(vbase, slab_bytes);
+
+  // ---- staging maps (all per-thread constants) ----
+  // K: chunk id = tid + 256 r -> (row id / CPR, 16-byte chunk id % CPR): a row is read by CPR neighbouring lanes.
+  // V: a thread owns 4 consecutive keys (quad vg) x 8 consecutive d (chunk vc); 4 neighbouring lanes read 64
+  //    contiguous bytes of one row.  Quad vg holds keys 16*grp + 8*aa + 4*hh + 0..3; the MFMA k-order wants,
+  //    per 16 keys, [hh=0: aa=0, aa=1 | hh=1: aa=0, aa=1], i.e. 16-byte unit 2*grp + hh, 8-byte half aa.
+  const int vcl = tid & 3, vg = (tid >> 2) & 15, vc = (tid >> 6) * 4 + vcl;
+  const bool v_active = (16 * CPR >= 256) || vc < CPR;  // head_dim 128: every thread stages V
+  const int v_unit = 2 * (vg >> 2) + (vg & 1), v_half = (vg >> 1) & 1;
+  uint32_t k_goff[KCH], v_goff[4];
+  int k_loff[KCH];
+#pragma unroll
+  for (int r = 0; r < KCH; ++r) {
+    const int id = tid + 256 * r, rk = id / CPR, cc = id % CPR;
+    k_goff[r] = (uint32_t)(rk * D + cc * 8) * 2u;
+    k_loff[r] = swz<D>(rk, cc);
+  }
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+    v_goff[jj] = v_active ? (uint32_t)((4 * vg + jj) * D + vc * 8) * 2u : slab_bytes;  // idle threads read nothing
+  u32x4 kreg[KCH], vreg[4];
+
+  // k0 >= N (list exhausted) puts every offset past the end: zeros come back, no memory is touched.
+  auto load_tile = [&](int k0) {
+    const uint32_t base = (uint32_t)k0 * (D * 2u);
+#pragma unroll
+    for (int r = 0; r < KCH; ++r) kreg[r] = buffer_load16(krs, base + k_goff[r]);
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) vreg[jj] = buffer_load16(vrs, base + v_goff[jj]);
+  };
+  auto store_tile = [&](int buf) {
+    uint16_t* Ks = Ks2[buf];
+    uint16_t* Vt = Vt2[buf];
+#pragma unroll
+    for (int r = 0; r < KCH; ++r) *reinterpret_cast<u32x4*>(Ks + k_loff[r]) = kreg[r];
+    if (v_active) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int dd = 8 * vc + e;
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;  // high / low halves of two dwords
+        u32x2 w;
+        w[0] = __builtin_amdgcn_perm(vreg[1][e >> 1], vreg[0][e >> 1], sel);
+        w[1] = __builtin_amdgcn_perm(vreg[3][e >> 1], vreg[2][e >> 1], sel);
+        *reinterpret_cast<u32x2*>(Vt + swz<BK>(dd, v_unit) + v_half * 4) = w;
+      }
+    }
+  };
+  auto tile_k0 = [&](int t) { return t < it.n_tiles ? (a.tiles[it.list_begin + t] >> 1) * BK : a.N; };
+
+  load_tile(tile_k0(0));  // first tile in flight while Q and the side keys are fetched
 
   bf16x8 qf[KSTEPS];
   {
@@ -81,7 +158,9 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
     for (int s = 0; s < KSTEPS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s + 8 * h);
   }
 
-  float m = -INFINITY, l = 0.f;
+  // m: reference maximum (log2 units); l: sum of the bf16-rounded probabilities, i.e. exactly the weights
+  // the second product applies, so the output is a true convex combination; lx: exact fp32 sum (LSE only).
+  float m = -INFINITY, l = 0.f, lx = 0.f;
   floatx16 oacc[DBLK];
 #pragma unroll
   for (int b = 0; b < DBLK; ++b)
@@ -98,14 +177,22 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
     for (int t = 0; t < 2; ++t) {
       if (!__any(valid[t])) continue;
       const uint16_t* kr = kbase + (size_t)js[t] * D;
+      const uint16_t* vr = vbase + (size_t)js[t] * D;
+      u32x4 kk[KSTEPS];
+      u32x2 vv[DBLK][4];
+#pragma unroll
+      for (int s = 0; s < KSTEPS; ++s) kk[s] = *reinterpret_cast<const u32x4*>(kr + 16 * s + 8 * h);
+#pragma unroll
+      for (int b = 0; b < DBLK; ++b)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) vv[b][g4] = *reinterpret_cast<const u32x2*>(vr + 32 * b + 8 * g4 + 4 * h);
       float part = 0.f;
 #pragma unroll
       for (int s = 0; s < KSTEPS; ++s) {
-        const u32x4 kk = *reinterpret_cast<const u32x4*>(kr + 16 * s + 8 * h);
         const u32x4 qq = __builtin_bit_cast(u32x4, qf[s]);
 #pragma unroll
         for (int w = 0; w < 4; ++w)
-          part += bf16_lo(qq[w]) * bf16_lo(kk[w]) + bf16_hi(qq[w]) * bf16_hi(kk[w]);
+          part += bf16_lo(qq[w]) * bf16_lo(kk[s][w]) + bf16_hi(qq[w]) * bf16_hi(kk[s][w]);
       }
       float sdot = (part + other_half(part)) * a.scale_log2;
       if (!valid[t]) sdot = -INFINITY;
@@ -114,80 +201,27 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
       const float alpha = __builtin_amdgcn_exp2f(m - m_use);
       const float p = __builtin_amdgcn_exp2f(sdot - m_use);
       l = l * alpha + (h == 0 ? p : 0.f);
+      if (LSE) lx = lx * alpha + (h == 0 ? p : 0.f);
       m = m_new;
-      const uint16_t* vr = vbase + (size_t)js[t] * D;
 #pragma unroll
       for (int b = 0; b < DBLK; ++b)
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
-          const u32x2 vv = *reinterpret_cast<const u32x2*>(vr + 32 * b + 8 * g4 + 4 * h);
-          oacc[b][4 * g4 + 0] = oacc[b][4 * g4 + 0] * alpha + p * bf16_lo(vv[0]);
-          oacc[b][4 * g4 + 1] = oacc[b][4 * g4 + 1] * alpha + p * bf16_hi(vv[0]);
-          oacc[b][4 * g4 + 2] = oacc[b][4 * g4 + 2] * alpha + p * bf16_lo(vv[1]);
-          oacc[b][4 * g4 + 3] = oacc[b][4 * g4 + 3] * alpha + p * bf16_hi(vv[1]);
+          oacc[b][4 * g4 + 0] = oacc[b][4 * g4 + 0] * alpha + p * bf16_lo(vv[b][g4][0]);
+          oacc[b][4 * g4 + 1] = oacc[b][4 * g4 + 1] * alpha + p * bf16_hi(vv[b][g4][0]);
+          oacc[b][4 * g4 + 2] = oacc[b][4 * g4 + 2] * alpha + p * bf16_lo(vv[b][g4][1]);
+          oacc[b][4 * g4 + 3] = oacc[b][4 * g4 + 3] * alpha + p * bf16_hi(vv[b][g4][1]);
         }
     }
   }
 
-  // ---- staging maps ----
-  // V: a thread owns 4 consecutive keys (quad vg) x 8 consecutive d (chunk vc); 4 neighbouring lanes read 64
-  // contiguous bytes of one row.
-  const int vcl = tid & 3, vg = (tid >> 2) & 15, vc = (tid >> 6) * 4 + vcl;
-  const bool v_active = vc < CPR;
-  u32x4 kreg[KCH], vreg[4];
+  PHASE_MARK(1);
+  store_tile(0);
+  load_tile(tile_k0(1));
+  __syncthreads();
+  PHASE_MARK(2);
 
-  auto load_tile = [&](int k0) {
-#pragma unroll
-    for (int r = 0; r < KCH; ++r) {
-      const int id = tid + 256 * r, rk = id / CPR, cc = id % CPR;
-      const int j = min(k0 + rk, a.N - 1);
-      kreg[r] = *reinterpret_cast<const u32x4*>(kbase + (size_t)j * D + cc * 8);
-    }
-    if (v_active) {
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int j = min(k0 + 4 * vg + jj, a.N - 1);
-        vreg[jj] = *reinterpret_cast<const u32x4*>(vbase + (size_t)j * D + vc * 8);
-      }
-    }
-  };
-  auto store_tile = [&](int buf) {
-    uint16_t* Ks = Ks2[buf];
-    uint16_t* Vt = Vt2[buf];
-#pragma unroll
-    for (int r = 0; r < KCH; ++r) {
-      const int id = tid + 256 * r, rk = id / CPR, cc = id % CPR;
-      *reinterpret_cast<u32x4*>(Ks + swz<D>(rk, cc)) = kreg[r];
-    }
-    if (v_active) {
-      // quad vg holds keys 16*grp + 8*aa + 4*hh + 0..3; the MFMA k-order wants, per 16 keys,
-      // [hh=0: aa=0, aa=1 | hh=1: aa=0, aa=1], i.e. 16-byte unit 2*grp + hh, 8-byte half aa.
-      const int unit = 2 * (vg >> 2) + (vg & 1), half = (vg >> 1) & 1;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int dd = 8 * vc + e;
-        const uint32_t x0 = vreg[0][e >> 1], x1 = vreg[1][e >> 1], x2 = vreg[2][e >> 1], x3 = vreg[3][e >> 1];
-        u32x2 w;
-        if (e & 1) {
-          w[0] = (x0 >> 16) | (x1 & 0xffff0000u);
-          w[1] = (x2 >> 16) | (x3 & 0xffff0000u);
-        } else {
-          w[0] = (x0 & 0xffffu) | (x1 << 16);
-          w[1] = (x2 & 0xffffu) | (x3 << 16);
-        }
-        *reinterpret_cast<u32x2*>(Vt + swz<BK>(dd, unit) + half * 4) = w;
-      }
-    }
-  };
-
-  // Pipeline: tile t is computed from LDS buffer t&1 while tile t+1 sits in registers (loaded one
-  // iteration earlier) and is written to the other buffer; one barrier per tile.
-  if (it.n_tiles > 0) {
-    load_tile((a.tiles[it.list_begin] >> 1) * BK);
-    store_tile(0);
-    if (it.n_tiles > 1) load_tile((a.tiles[it.list_begin + 1] >> 1) * BK);
-    __syncthreads();
-  }
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
   for (int t = 0; t < it.n_tiles; ++t) {
     const int entry = a.tiles[it.list_begin + t];
@@ -196,27 +230,22 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
     const uint16_t* Ks = Ks2[t & 1];
     const uint16_t* Vt = Vt2[t & 1];
 
-    // S^T = K Q^T: two 32-key blocks x 32 queries; operand fragments are fetched one k-step ahead
+    // tile t+1: registers -> the other buffer (its last readers passed the barrier); tile t+2: start loading
+    store_tile((t + 1) & 1);
+    load_tile(tile_k0(t + 2));
+
+    // S^T = K Q^T: two 32-key blocks x 32 queries
     floatx16 sacc[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
-    {
-      bf16x8 kf0 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(n, h));
-      bf16x8 kf1 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(32 + n, h));
 #pragma unroll
-      for (int s = 0; s < KSTEPS; ++s) {
-        bf16x8 nk0 = kf0, nk1 = kf1;
-        if (s + 1 < KSTEPS) {
-          nk0 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(n, 2 * (s + 1) + h));
-          nk1 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(32 + n, 2 * (s + 1) + h));
-        }
-        sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[s], sacc[0], 0, 0, 0);
-        sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, qf[s], sacc[1], 0, 0, 0);
-        kf0 = nk0;
-        kf1 = nk1;
-      }
+    for (int s = 0; s < KSTEPS; ++s) {
+      const bf16x8 kf0 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(n, 2 * s + h));
+      const bf16x8 kf1 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(32 + n, 2 * s + h));
+      sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[s], sacc[0], 0, 0, 0);
+      sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, qf[s], sacc[1], 0, 0, 0);
     }
 
     // mask (partial tiles only: one wave-uniform branch, selects inside) and tile maximum on the raw scores
@@ -244,6 +273,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
       const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m - m_ref);
       l *= alpha;
+      if (LSE) lx *= alpha;
 #pragma unroll
       for (int b = 0; b < DBLK; ++b)
 #pragma unroll
@@ -253,7 +283,6 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
     const float neg_m = (m == -INFINITY) ? 0.f : -m;
 
     // probabilities -> bf16 B-operand fragments; pf[ks] covers keys 16*ks .. 16*ks+15 of the tile
-    float psum = 0.f;
     bf16x8 pf[4];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -265,12 +294,13 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
           floatx2 p;
           p[0] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * half + 2 * w], a.scale_log2, neg_m));
           p[1] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * half + 2 * w + 1], a.scale_log2, neg_m));
-          psum += p[0] + p[1];
-          pk[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
+          if (LSE) lx += p[0] + p[1];
+          const bf16x2 pb = __builtin_convertvector(p, bf16x2);
+          l = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, l, false);
+          pk[w] = __builtin_bit_cast(uint32_t, pb);
         }
         pf[2 * kb + half] = __builtin_bit_cast(bf16x8, pk);
       }
-    l += psum;
 
     // O^T += V^T P^T
 #pragma unroll
@@ -283,16 +313,15 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
       for (int ks = 0; ks < 4; ++ks)
         oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks], pf[ks], oacc[b], 0, 0, 0);
     }
-
-    if (t + 1 < it.n_tiles) store_tile((t + 1) & 1);
     __syncthreads();
-    if (t + 2 < it.n_tiles) load_tile((a.tiles[it.list_begin + t + 2] >> 1) * BK);
   }
 
   // ---- epilogue ----
+  PHASE_MARK(3);
   const float l_tot = l + other_half(l);
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   const float lse2 = m + __builtin_amdgcn_logf(l_tot);  // log2 domain; -inf when the slice saw no key
+  const float lse2x = LSE ? m + __builtin_amdgcn_logf(lx + other_half(lx)) : lse2;
   if (it.n_splits == 1) {
     if (row < a.N) {
       uint16_t* orow = a.out + ((size_t)hq * a.N + row) * D;
@@ -305,7 +334,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
           w[1] = pack_bf16(oacc[b][4 * g4 + 2] * inv, oacc[b][4 * g4 + 3] * inv);
           *reinterpret_cast<u32x2*>(orow + 32 * b + 8 * g4 + 4 * h) = w;
         }
-      if (a.lse != nullptr && h == 0) a.lse[(size_t)hq * a.N + row] = lse2 * kLn2;
+      if (LSE && h == 0) a.lse[(size_t)hq * a.N + row] = lse2x * kLn2;
     }
   } else {
     const size_t prow = ((size_t)it.slot * a.Hq + hq) * BQ + wave * 32 + n;
@@ -319,8 +348,12 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
         for (int r = 0; r < 4; ++r) w[r] = oacc[b][4 * g4 + r] * inv;
         *reinterpret_cast<floatx4*>(orow + 32 * b + 8 * g4 + 4 * h) = w;
       }
-    if (h == 0) a.ws_lse[prow] = lse2;
+    if (h == 0) {
+      a.ws_lse[2 * prow] = lse2;
+      a.ws_lse[2 * prow + 1] = lse2x;
+    }
   }
+  PHASE_MARK(4);
 }
 
 // Combines the partial results of a query tile whose key list was cut into slices.  One workgroup
@@ -334,17 +367,21 @@ __global__ __launch_bounds__(256) void merge_kernel(const PrefillArgs a) {
   const int r = rb * MERGE_ROWS + threadIdx.x / 16;
   const int row = mi.qtile * BQ + r;
   if (row >= a.N) return;
-  float mx = -INFINITY;
-  for (int s = 0; s < mi.n_splits; ++s)
-    mx = fmaxf(mx, a.ws_lse[((size_t)(mi.slot0 + s) * a.Hq + hq) * BQ + r]);
-  float wsum = 0.f;
+  float mx = -INFINITY, mxx = -INFINITY;
+  for (int s = 0; s < mi.n_splits; ++s) {
+    const size_t prow = ((size_t)(mi.slot0 + s) * a.Hq + hq) * BQ + r;
+    mx = fmaxf(mx, a.ws_lse[2 * prow]);
+    mxx = fmaxf(mxx, a.ws_lse[2 * prow + 1]);
+  }
+  float wsum = 0.f, xsum = 0.f;
   floatx4 acc[C4 / 16];
 #pragma unroll
   for (int c = 0; c < C4 / 16; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < mi.n_splits; ++s) {
     const size_t prow = ((size_t)(mi.slot0 + s) * a.Hq + hq) * BQ + r;
-    const float w = __builtin_amdgcn_exp2f(a.ws_lse[prow] - mx);
+    const float w = __builtin_amdgcn_exp2f(a.ws_lse[2 * prow] - mx);
     wsum += w;
+    xsum += __builtin_amdgcn_exp2f(a.ws_lse[2 * prow + 1] - mxx);
 #pragma unroll
     for (int c = 0; c < C4 / 16; ++c) {
       const int c4 = (threadIdx.x % 16) + 16 * c;
@@ -361,18 +398,26 @@ __global__ __launch_bounds__(256) void merge_kernel(const PrefillArgs a) {
     *reinterpret_cast<u32x2*>(a.out + ((size_t)hq * a.N + row) * D + 4 * c4) = w2;
   }
   if (a.lse != nullptr && (threadIdx.x % 16) == 0)
-    a.lse[(size_t)hq * a.N + row] = (mx + __builtin_amdgcn_logf(wsum)) * kLn2;
+    a.lse[(size_t)hq * a.N + row] = (mxx + __builtin_amdgcn_logf(xsum)) * kLn2;
+}
+
+template <int D, bool ST>
+void launch_variant(const PrefillArgs& a, dim3 grid, hipStream_t st) {
+  if (a.lse != nullptr)
+    hipLaunchKernelGGL((prefill_kernel<D, ST, true>), grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL((prefill_kernel<D, ST, false>), grid, dim3(256), 0, st, a);
 }
 
 }  // namespace
 
 size_t prefill_ws_bytes(const purekv_plan& p) {
-  return (size_t)p.n_slots * p.g.Hq * BQ * (p.g.d + 1) * sizeof(float);
+  return (size_t)p.n_slots * p.g.Hq * BQ * (p.g.d + 2) * sizeof(float);
 }
 
 int launch_prefill(const purekv_plan& p, const void* q, const void* k, const void* v, void* out, float* lse,
                    void* ws, hipStream_t st) {
-  PrefillArgs a;
+  PrefillArgs a{};
   a.q = static_cast<const uint16_t*>(q);
   a.k = static_cast<const uint16_t*>(k);
   a.v = static_cast<const uint16_t*>(v);
@@ -395,15 +440,15 @@ int launch_prefill(const purekv_plan& p, const void* q, const void* k, const voi
   const bool sparse = p.g.pattern != PUREKV_PATTERN_DENSE;
   if (p.g.d == 128) {
     if (sparse)
-      hipLaunchKernelGGL((prefill_kernel<128, true>), grid, block, 0, st, a);
+      launch_variant<128, true>(a, grid, st);
     else
-      hipLaunchKernelGGL((prefill_kernel<128, false>), grid, block, 0, st, a);
+      launch_variant<128, false>(a, grid, st);
     if (!p.merges.empty()) hipLaunchKernelGGL(merge_kernel<128>, mgrid, block, 0, st, a);
   } else {
     if (sparse)
-      hipLaunchKernelGGL((prefill_kernel<64, true>), grid, block, 0, st, a);
+      launch_variant<64, true>(a, grid, st);
     else
-      hipLaunchKernelGGL((prefill_kernel<64, false>), grid, block, 0, st, a);
+      launch_variant<64, false>(a, grid, st);
     if (!p.merges.empty()) hipLaunchKernelGGL(merge_kernel<64>, mgrid, block, 0, st, a);
   }
   PUREKV_HIP_TRY(hipGetLastError());

