@@ -44,6 +44,25 @@ def blas_threads() -> int:
     return int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
 
 
+def profiled_traffic_bytes():
+    """HBM bytes per ST-SpAttn prefill call from the committed rocprofv3 counter summary (prefill + merge kernels):
+    FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, the factors a 256 MiB device copy calibrates.  None if absent."""
+    path = os.path.join(ROOT, "profiles", "prefill_kernel_st_qwen25vl_32f.md")
+    try:
+        total, in_table = 0.0, False
+        for line in open(path):
+            in_table = in_table or line.startswith("## HBM-side byte counters")
+            cells = [c.strip() for c in line.split("|")]
+            if in_table and len(cells) >= 5 and (cells[1].startswith("`prefill_kernel<128, true") or cells[1].startswith("`merge_kernel")):
+                try:
+                    total += float(cells[2]) * 2.0 * 1024 + float(cells[3]) * 1024
+                except ValueError:
+                    pass
+        return int(total) if total > 0 else None
+    except OSError:
+        return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,7 +73,7 @@ def main() -> int:
     ap.add_argument("--batched-layers", type=int, default=26, help="layers per batched top-k/compaction launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=28, help="query heads in the oracle's timed sample")
-    ap.add_argument("--only-stage", default=None, choices=STAGES,
+    ap.add_argument("--only-stage", default=None, choices=STAGES + ["copy_calib"],
                     help="profiling aid: after one full warm-up step run only this stage --steps times and exit")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -119,7 +138,10 @@ def main() -> int:
     if args.only_stage is not None:
         step()
         torch.cuda.synchronize()
-        one = {
+        if args.only_stage == "copy_calib":
+            calib_src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
+            calib_dst = torch.empty_like(calib_src)
+        stages = {
             "dense_prefill": lambda: pk.purekv_st_spattn_prefill(dense, q0, k0, v0, out=out0, lse=lse),
             "importance": lambda: pk.purekv_lowlayer_importance(dense, q0, k0, lse, w, c_out=c),
             "topk_low": lambda: pk.purekv_topk_select(dense, c, v0, w, h, idx_out=idx0),
@@ -129,7 +151,10 @@ def main() -> int:
             "compact_high": lambda: pk.purekv_kv_compact(st, k1, v1, idx1[0], cap=cap, kc=kc1, vc=vc1),
             "append_decode": lambda: (pk.purekv_kv_append(st, k_new, v_new, kc1, vc1, n_keep),
                                       pk.purekv_decode_attn(st, q_new, kc1, vc1, n_keep + 1, out=o_dec)),
-        }[args.only_stage]
+            # plain device copy of a known size (256 MiB read + 256 MiB written): scale for the HBM byte counters
+            "copy_calib": lambda: calib_dst.copy_(calib_src),
+        }
+        one = stages[args.only_stage]
         for _ in range(args.steps):
             one()
         torch.cuda.synchronize()
@@ -182,7 +207,8 @@ def main() -> int:
 
     kept_flops, mask_flops = st.kept_tile_flops(), st.mask_flops()
     dense_kept = dense.kept_tile_flops()
-    st_tflops = kept_flops / (st_ms * 1e-3) / 1e12
+    st_call_ms = stage_ms["st_prefill"]           # prefill kernel + merge, events inside the timed steps
+    st_tflops = kept_flops / (st_call_ms * 1e-3) / 1e12
     topk_bytes = (n - w) * d * 2 * hkv + (n - w) * 4 * hkv * 3 + n_keep * 4 * hkv   # V read, C read, S write+read, idx
     comp_bytes = 2 * 2 * n_keep * d * 2 * hkv + n_keep * 4 * hkv                    # K,V rows read + written, idx
     dec_bytes = 2 * (n_keep + 1) * d * 2 * hkv
@@ -204,9 +230,10 @@ def main() -> int:
                                f"{hq}q/{hkv}kv heads, d={d}, keep ratio {args.ratio} (h={h}, w={w})",
                    "tile": f"{pk.BQ}x{pk.BK}", "step": "low layer (dense prefill+LSE, importance, top-h, compaction) + "
                    "high layer (ST-SpAttn prefill, top-h, compaction, append+decode)"},
-        "prefill_ms_per_layer": round(st_ms, 4),
+        "prefill_ms_per_layer": round(st_call_ms, 4),
+        "prefill_ms_per_layer_back_to_back": round(st_ms, 4),
         "mfma_peak_frac": round(st_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-        "mask_tflops": round(mask_flops / (st_ms * 1e-3) / 1e12, 2),
+        "mask_tflops": round(mask_flops / (st_call_ms * 1e-3) / 1e12, 2),
         "dense_prefill_ms_per_layer": round(dense_ms, 4),
         "dense_prefill_tflops": round(dense_kept / (dense_ms * 1e-3) / 1e12, 2),
         "stage_ms_in_step": {k_: round(v_, 4) for k_, v_ in stage_ms.items()},
@@ -226,7 +253,8 @@ def main() -> int:
         "roofline": {
             "kernel": "prefill_kernel<128, ST> (+ merge_kernel for split rows), one ST-SpAttn layer",
             "bound": "mfma", "achieved": round(st_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(st_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+            "frac": round(st_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": profiled_traffic_bytes(),
+            "algorithmic_flops_per_launch": kept_flops, "launch_ms": round(st_call_ms, 4),
         },
         "context": "paper: 5.0x KV compression, 3.16x prefill speed-up, whole model on 1x A100 40GB (not comparable)",
     }
