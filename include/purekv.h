@@ -74,34 +74,41 @@ typedef enum {
 
 /*
  * Plan: the static block structure of the mask for one shape (Sec. 3.2: the pattern depends only on
- * F, P, T).  For every tile of PUREKV_BQ query rows it lists the tiles of PUREKV_BK keys that hold at
- * least one allowed (query, key) pair of the "block part" of the mask -- causal keys of the first
- * frame, of the query's own frame (spatial bit), and everything for text queries or the dense pattern --
- * flags tiles in which every pair is allowed, and cuts long lists into balanced work items.  The
- * single previous-frame key and the self key of the temporal path are not tiles: the kernel adds them
- * per query row.
+ * F, P, T) and the static schedule of the prefill kernel.  For every tile of PUREKV_BQ query rows it
+ * lists the tiles of PUREKV_BK keys that hold at least one allowed (query, key) pair, with two bit masks
+ * over the tile's PUREKV_WAVES row blocks of 32 rows: `need` (the block has an allowed pair in the key
+ * tile) and `full` (every pair of the block with the key tile is allowed, so no element mask is
+ * needed).  Long lists are cut into slices (work items) whose partial results are merged; every (work
+ * item, query head) unit is dealt to one of the persistent workgroups of the prefill kernel (one per
+ * compute unit), longest first, KV heads kept on fixed XCDs where the head counts allow it.
  *
- * purekv_plan_create builds the lists on the host and uploads them to the current device (a few KB to
+ * purekv_plan_create builds the lists on the host and uploads them to the current device (KB to a few
  * MB, owned by the plan; `stream` orders the upload).  purekv_plan_create_host only builds the host
- * lists (no GPU needed; such a plan can be inspected but not launched: compute calls return EINVAL).
- * `*out` is written only on success.  Destroy with purekv_plan_destroy (NULL is accepted).
+ * lists for `n_workgroups` persistent workgroups (no GPU needed; such a plan can be inspected but not
+ * launched: compute calls return EINVAL).  `*out` is written only on success.  Destroy with
+ * purekv_plan_destroy (NULL is accepted).
  */
-#define PUREKV_BQ 128
+#define PUREKV_BQ 256
 #define PUREKV_BK 64
+#define PUREKV_WAVES 8
 PUREKV_API int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* stream);
-PUREKV_API int purekv_plan_create_host(const purekv_shape_t* shape, purekv_plan_t** out);
+PUREKV_API int purekv_plan_create_host(const purekv_shape_t* shape, int32_t n_workgroups, purekv_plan_t** out);
 PUREKV_API int purekv_plan_destroy(purekv_plan_t* plan);
 
-/* Plan inspection (host memory).  counts[0..5] = N, number of query tiles, number of work items,
- * number of (query tile, key tile) references, number of those flagged full, number of query tiles
- * whose list is split over several work items. */
-PUREKV_API int purekv_plan_counts(const purekv_plan_t* plan, int64_t counts[6]);
-/* Copies the key-tile list of query tile `qt` into tiles[0..cap): entry = key_tile_index * 2 + full.
- * Returns the list length (may exceed cap; then only cap entries are written) or a negative status. */
-PUREKV_API int purekv_plan_qtile_list(const purekv_plan_t* plan, int32_t qt, int32_t* tiles, int32_t cap);
+/* Plan inspection (host memory).  counts[0..7] = N, number of query tiles, number of work items,
+ * number of (query tile, key tile) references, number of (reference, row block) pairs computed, number
+ * of those flagged full, number of query tiles whose list is split, number of persistent workgroups. */
+PUREKV_API int purekv_plan_counts(const purekv_plan_t* plan, int64_t counts[8]);
+/* Copies the key-tile list of query tile `qt` into refs[0 .. 3*cap): triples {key tile index, need mask,
+ * full mask}.  Returns the list length (may exceed cap; then only cap triples are written) or a negative
+ * status. */
+PUREKV_API int purekv_plan_qtile_list(const purekv_plan_t* plan, int32_t qt, int32_t* refs, int32_t cap);
 /* Copies work item `it` as {query tile, first list position, tile count, split index, number of
  * splits, partial-result slot or -1}.  Returns PUREKV_OK or a negative status. */
 PUREKV_API int purekv_plan_item(const purekv_plan_t* plan, int32_t it, int32_t item[6]);
+/* Copies the units of persistent workgroup `wg`, in execution order, into units[0 .. 2*cap): pairs {work
+ * item, query head}.  Returns the number of units (may exceed cap) or a negative status. */
+PUREKV_API int purekv_plan_queue(const purekv_plan_t* plan, int32_t wg, int32_t* units, int32_t cap);
 
 /* Device workspace bytes needed by `op` for this plan.  `n_layers`, `w` and `cap` are read by the ops
  * that take them (TOPK: n_layers, w; DECODE: cap); pass 0 otherwise. */
@@ -168,8 +175,8 @@ PUREKV_API int purekv_decode_attn(const purekv_plan_t* plan, const void* q_new, 
 /* h = max(0, floor(ratio * n) - w): the keep budget counts the recent window (20 % budget = 5.0x). */
 PUREKV_API int32_t purekv_budget(int32_t n, int32_t w, double ratio);
 
-/* Work counts for reporting: flops of one prefill call counted on the key tiles the kernel visits
- * (4 * BQ * BK * d per tile reference and query head) and on the allowed pairs of the mask only. */
+/* Work counts for reporting: flops of one prefill call counted on the (32-row block, key tile) pairs the
+ * kernel computes (4 * 32 * BK * d per pair and query head) and on the allowed pairs of the mask only. */
 PUREKV_API double purekv_plan_kept_tile_flops(const purekv_plan_t* plan);
 PUREKV_API double purekv_plan_mask_flops(const purekv_plan_t* plan);
 

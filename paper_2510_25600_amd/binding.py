@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libpurekv.so")
 PATTERN_DENSE, PATTERN_SPATIAL, PATTERN_TEMPORAL, PATTERN_ST = 0, 1, 2, 3
 OP_PREFILL, OP_IMPORTANCE, OP_TOPK, OP_COMPACT, OP_DECODE = 0, 1, 2, 3, 4
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5
-BQ, BK = 128, 64
+BQ, BK, WAVES = 256, 64, 8
 
 
 class Shape(ctypes.Structure):
@@ -45,11 +45,12 @@ def _load() -> ctypes.CDLL:
     P = c_void_p
     sig = {
         "purekv_plan_create": (c_int, [POINTER(Shape), POINTER(P), P]),
-        "purekv_plan_create_host": (c_int, [POINTER(Shape), POINTER(P)]),
+        "purekv_plan_create_host": (c_int, [POINTER(Shape), c_int32, POINTER(P)]),
         "purekv_plan_destroy": (c_int, [P]),
         "purekv_plan_counts": (c_int, [P, POINTER(c_int64)]),
         "purekv_plan_qtile_list": (c_int, [P, c_int32, POINTER(c_int32), c_int32]),
         "purekv_plan_item": (c_int, [P, c_int32, POINTER(c_int32)]),
+        "purekv_plan_queue": (c_int, [P, c_int32, POINTER(c_int32), c_int32]),
         "purekv_workspace_bytes": (c_size_t, [P, c_int, c_int32, c_int32, c_int32]),
         "purekv_st_spattn_prefill": (c_int, [P, P, P, P, P, P, P, c_size_t, P]),
         "purekv_lowlayer_importance": (c_int, [P, P, P, P, c_int32, P, P, c_size_t, P]),
@@ -72,7 +73,7 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 EXPORTS = (
     "purekv_plan_create", "purekv_plan_create_host", "purekv_plan_destroy", "purekv_plan_counts",
-    "purekv_plan_qtile_list", "purekv_plan_item", "purekv_workspace_bytes", "purekv_st_spattn_prefill",
+    "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_workspace_bytes", "purekv_st_spattn_prefill",
     "purekv_lowlayer_importance", "purekv_topk_select", "purekv_kv_compact", "purekv_kv_append",
     "purekv_decode_attn", "purekv_budget", "purekv_plan_kept_tile_flops", "purekv_plan_mask_flops",
     "purekv_strerror",
@@ -115,12 +116,14 @@ class Plan:
     """Owns a purekv_plan_t.  `host_only` plans can be inspected without a GPU but not launched."""
 
     def __init__(self, n_frames: int, patch_h: int, patch_w: int, n_text: int, n_q_heads: int, n_kv_heads: int,
-                 head_dim: int, pattern: int = PATTERN_ST, softmax_scale: float = 0.0, host_only: bool = False):
+                 head_dim: int, pattern: int = PATTERN_ST, softmax_scale: float = 0.0, host_only: bool = False,
+                 n_workgroups: int = 256):
         self.shape = Shape(n_frames, patch_h, patch_w, n_text, n_q_heads, n_kv_heads, head_dim, pattern,
                            softmax_scale)
         self._h = c_void_p()
         if host_only:
-            _check(_lib.purekv_plan_create_host(byref(self.shape), byref(self._h)), "purekv_plan_create_host")
+            _check(_lib.purekv_plan_create_host(byref(self.shape), n_workgroups, byref(self._h)),
+                   "purekv_plan_create_host")
         else:
             _check(_lib.purekv_plan_create(byref(self.shape), byref(self._h), _stream()), "purekv_plan_create")
         self.N = n_frames * patch_h * patch_w + n_text
@@ -128,9 +131,9 @@ class Plan:
         self._ws = {}
 
     @classmethod
-    def for_workload(cls, wl, pattern: int = PATTERN_ST, host_only: bool = False) -> "Plan":
+    def for_workload(cls, wl, pattern: int = PATTERN_ST, host_only: bool = False, n_workgroups: int = 256) -> "Plan":
         return cls(wl.n_frames, wl.patch_h, wl.patch_w, wl.n_text, wl.n_q_heads, wl.n_kv_heads, wl.head_dim,
-                   pattern, 0.0, host_only)
+                   pattern, 0.0, host_only, n_workgroups)
 
     @property
     def handle(self) -> c_void_p:
@@ -150,17 +153,28 @@ class Plan:
 
     # ---- inspection -------------------------------------------------------------------------------
     def counts(self) -> dict:
-        c = (c_int64 * 6)()
+        c = (c_int64 * 8)()
         _check(_lib.purekv_plan_counts(self._h, c), "purekv_plan_counts")
-        return dict(N=c[0], n_qtiles=c[1], n_items=c[2], n_tile_refs=c[3], n_full=c[4], n_split_qtiles=c[5])
+        return dict(N=c[0], n_qtiles=c[1], n_items=c[2], n_tile_refs=c[3], n_wave_tiles=c[4], n_full_wave_tiles=c[5],
+                    n_split_qtiles=c[6], n_workgroups=c[7])
 
     def qtile_list(self, qt: int) -> list:
+        """[(key tile, need mask, full mask)] of query tile `qt`."""
         n = _lib.purekv_plan_qtile_list(self._h, qt, None, 0)
         if n < 0:
             raise PureKVError(n, "purekv_plan_qtile_list")
-        buf = (c_int32 * max(n, 1))()
+        buf = (c_int32 * max(3 * n, 1))()
         _lib.purekv_plan_qtile_list(self._h, qt, buf, n)
-        return [(buf[i] >> 1, buf[i] & 1) for i in range(n)]
+        return [(buf[3 * i], buf[3 * i + 1], buf[3 * i + 2]) for i in range(n)]
+
+    def queue(self, wg: int) -> list:
+        """[(work item, query head)] run by persistent workgroup `wg`, in order."""
+        n = _lib.purekv_plan_queue(self._h, wg, None, 0)
+        if n < 0:
+            raise PureKVError(n, "purekv_plan_queue")
+        buf = (c_int32 * max(2 * n, 1))()
+        _lib.purekv_plan_queue(self._h, wg, buf, n)
+        return [(buf[2 * i], buf[2 * i + 1]) for i in range(n)]
 
     def item(self, it: int) -> Tuple[int, ...]:
         buf = (c_int32 * 6)()

@@ -21,7 +21,8 @@ static int check_shape(const purekv_shape_t* s) {
   if (s->n_q_heads < 1 || s->n_kv_heads < 1 || s->n_q_heads % s->n_kv_heads != 0) return PUREKV_EINVAL;
   if (!(s->softmax_scale >= 0.f) || std::isinf(s->softmax_scale)) return PUREKV_EINVAL;
   const int64_t p = (int64_t)s->patch_h * s->patch_w, n = p * s->n_frames + s->n_text;
-  if (p > (1 << 22) || n > (int64_t)1 << 22) return PUREKV_EINVAL;  // 32-bit byte offsets within one head's K/V
+  if (p > (1 << 22) || n > (int64_t)1 << 22) return PUREKV_EINVAL;
+  if (n * s->n_kv_heads * s->head_dim * 2 > ((int64_t)1 << 31)) return PUREKV_EINVAL;  // 32-bit byte offsets into K/V
   if (s->head_dim != 64 && s->head_dim != 128) return PUREKV_EUNSUPPORTED;
   if (s->pattern > PUREKV_PATTERN_ST) return PUREKV_EUNSUPPORTED;
   return PUREKV_OK;
@@ -55,7 +56,7 @@ static int make_plan(const purekv_shape_t* s, purekv_plan_t** out, int n_cu) {
   return PUREKV_OK;
 }
 
-static bool launchable(const purekv_plan_t* p) { return p != nullptr && p->d_items != nullptr; }
+static bool launchable(const purekv_plan_t* p) { return p != nullptr && p->d_stream != nullptr; }
 
 }  // namespace purekv
 
@@ -63,7 +64,10 @@ using namespace purekv;
 
 extern "C" {
 
-int purekv_plan_create_host(const purekv_shape_t* shape, purekv_plan_t** out) { return make_plan(shape, out, 256); }
+int purekv_plan_create_host(const purekv_shape_t* shape, int32_t n_workgroups, purekv_plan_t** out) {
+  if (n_workgroups < 1 || n_workgroups > 65536) return PUREKV_EINVAL;
+  return make_plan(shape, out, n_workgroups);
+}
 
 int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* stream) {
   if (out == nullptr) return PUREKV_EINVAL;
@@ -77,15 +81,17 @@ int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* s
   if (rc != PUREKV_OK) return rc;
   p->device = dev;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const size_t tb = p->tiles.size() * sizeof(int32_t), ib = p->items.size() * sizeof(WorkItem),
-               mb = p->merges.size() * sizeof(MergeItem);
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_tiles), tb ? tb : 4);
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_items), ib ? ib : 4);
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_merges), mb ? mb : 4);
-  if (e == hipSuccess && tb) e = hipMemcpyAsync(p->d_tiles, p->tiles.data(), tb, hipMemcpyHostToDevice, st);
-  if (e == hipSuccess && ib) e = hipMemcpyAsync(p->d_items, p->items.data(), ib, hipMemcpyHostToDevice, st);
+  const size_t sb = p->stream.size() * sizeof(StreamEntry), ub = p->units.size() * sizeof(Unit),
+               qb = p->queue_begin.size() * sizeof(int32_t), mb = p->merges.size() * sizeof(MergeItem);
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_stream), sb ? sb : 16);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_units), ub ? ub : 16);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_queue_begin), qb ? qb : 16);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_merges), mb ? mb : 16);
+  if (e == hipSuccess && sb) e = hipMemcpyAsync(p->d_stream, p->stream.data(), sb, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess && ub) e = hipMemcpyAsync(p->d_units, p->units.data(), ub, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess && qb) e = hipMemcpyAsync(p->d_queue_begin, p->queue_begin.data(), qb, hipMemcpyHostToDevice, st);
   if (e == hipSuccess && mb) e = hipMemcpyAsync(p->d_merges, p->merges.data(), mb, hipMemcpyHostToDevice, st);
-  if (e == hipSuccess) e = hipStreamSynchronize(st);  // host vectors may be reallocated later; finish the copy now
+  if (e == hipSuccess) e = hipStreamSynchronize(st);  // the host vectors must outlive the copies: finish them now
   if (e != hipSuccess) {
     purekv_plan_destroy(p);
     return note_hip_error(e);
@@ -96,28 +102,45 @@ int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* s
 
 int purekv_plan_destroy(purekv_plan_t* p) {
   if (p == nullptr) return PUREKV_OK;
-  if (p->d_tiles) (void)hipFree(p->d_tiles);
-  if (p->d_items) (void)hipFree(p->d_items);
+  if (p->d_stream) (void)hipFree(p->d_stream);
+  if (p->d_units) (void)hipFree(p->d_units);
+  if (p->d_queue_begin) (void)hipFree(p->d_queue_begin);
   if (p->d_merges) (void)hipFree(p->d_merges);
   delete p;
   return PUREKV_OK;
 }
 
-int purekv_plan_counts(const purekv_plan_t* p, int64_t counts[6]) {
+int purekv_plan_counts(const purekv_plan_t* p, int64_t counts[8]) {
   if (p == nullptr || counts == nullptr) return PUREKV_EINVAL;
   counts[0] = p->g.N;
   counts[1] = p->n_qtiles;
   counts[2] = (int64_t)p->items.size();
   counts[3] = (int64_t)p->tiles.size();
-  counts[4] = p->n_full;
-  counts[5] = (int64_t)p->merges.size();
+  counts[4] = p->n_wave_tiles;
+  counts[5] = p->n_full_wave_tiles;
+  counts[6] = (int64_t)p->merges.size();
+  counts[7] = p->n_queues;
   return PUREKV_OK;
 }
 
-int purekv_plan_qtile_list(const purekv_plan_t* p, int32_t qt, int32_t* tiles, int32_t cap) {
-  if (p == nullptr || qt < 0 || qt >= p->n_qtiles || cap < 0 || (cap > 0 && tiles == nullptr)) return PUREKV_EINVAL;
+int purekv_plan_qtile_list(const purekv_plan_t* p, int32_t qt, int32_t* refs, int32_t cap) {
+  if (p == nullptr || qt < 0 || qt >= p->n_qtiles || cap < 0 || (cap > 0 && refs == nullptr)) return PUREKV_EINVAL;
   const int32_t b = p->qtile_begin[qt], len = p->qtile_begin[qt + 1] - b;
-  for (int32_t i = 0; i < len && i < cap; ++i) tiles[i] = p->tiles[b + i];
+  for (int32_t i = 0; i < len && i < cap; ++i) {
+    refs[3 * i] = p->tiles[b + i].tile;
+    refs[3 * i + 1] = p->tiles[b + i].need;
+    refs[3 * i + 2] = p->tiles[b + i].full;
+  }
+  return len;
+}
+
+int purekv_plan_queue(const purekv_plan_t* p, int32_t wg, int32_t* units, int32_t cap) {
+  if (p == nullptr || wg < 0 || wg >= p->n_queues || cap < 0 || (cap > 0 && units == nullptr)) return PUREKV_EINVAL;
+  const int32_t b = p->queue_units_begin[wg], len = p->queue_units_begin[wg + 1] - b;
+  for (int32_t i = 0; i < len && i < cap; ++i) {
+    units[2 * i] = p->queue_units[2 * (b + i)];
+    units[2 * i + 1] = p->queue_units[2 * (b + i) + 1];
+  }
   return len;
 }
 
@@ -135,7 +158,7 @@ int purekv_plan_item(const purekv_plan_t* p, int32_t it, int32_t item[6]) {
 
 double purekv_plan_kept_tile_flops(const purekv_plan_t* p) {
   if (p == nullptr) return 0.0;
-  return 4.0 * PUREKV_BQ * PUREKV_BK * p->g.d * (double)p->tiles.size() * p->g.Hq;
+  return 4.0 * kRowsPerWave * PUREKV_BK * p->g.d * (double)p->n_wave_tiles * p->g.Hq;
 }
 
 double purekv_plan_mask_flops(const purekv_plan_t* p) {

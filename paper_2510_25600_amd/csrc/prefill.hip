@@ -33,10 +33,11 @@ struct PrefillArgs {
   float* lse;
   float* ws_o;    // [n_slots, Hq, BQ, D] normalised partial outputs
   float* ws_lse;  // [n_slots, Hq, BQ, 2] log2-domain log-sum-exp of the partial: {merge weight, exact}
-  const int32_t* tiles;
-  const WorkItem* items;
+  const StreamEntry* stream;
+  const Unit* units;
+  const int32_t* queue_begin;
   const MergeItem* merges;
-  int32_t N, Nv, P, Hq, G;
+  int32_t N, Nv, P, Hq, Hkv;
   uint32_t pattern;
   float scale_log2;  // softmax scale * log2(e)
 #ifdef PUREKV_PHASE_TRACE
@@ -71,60 +72,54 @@ __device__ __forceinline__ u32x4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_
   return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
 }
 
-// ST  = false: dense causal pattern only (no frame arithmetic, no side keys); true: any pattern.
+// ST  = false: dense causal pattern only (no frame arithmetic); true: any pattern.
 // LSE = true : also keeps the exact fp32 row sum for the log-sum-exp output.
+//
+// Persistent kernel: workgroup q walks stream[queue_begin[q] .. queue_begin[q+1]).  Every stream entry is one
+// key tile: all 8 wavefronts stage it, the wavefronts whose `need` bit is set multiply it.  Units (query tile
+// slice x head) follow each other in the stream without draining the K/V pipeline.
 template <int D, bool ST, bool LSE>
-__global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
+__global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   constexpr int KSTEPS = D / 16;        // MFMA k-steps of the score product
   constexpr int DBLK = D / 32;          // 32-row blocks of O^T
   constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
-  constexpr int KCH = BK * CPR / 256;   // K chunks staged per thread
+  constexpr int KCH = BK * CPR / 512;   // K chunks staged per thread
   __shared__ __attribute__((aligned(16))) uint16_t Ks2[2][BK * D];   // double-buffered
   __shared__ __attribute__((aligned(16))) uint16_t Vt2[2][D * BK];
 
   PHASE_MARK(0);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, h = lane >> 5;
-  const int item_id = blockIdx.x / a.Hq, hq = blockIdx.x % a.Hq, kvh = hq / a.G;
-  const WorkItem it = a.items[item_id];
-  const int row = it.qtile * BQ + wave * 32 + n;
-  const int rowc = min(row, a.N - 1);
+  const int t_begin = a.queue_begin[blockIdx.x], t_end = a.queue_begin[blockIdx.x + 1];
+  if (t_begin >= t_end) return;
 
-  // Block part of the mask for this lane's row: key j allowed iff j <= rowc and (j <= a_i or j >= lo_i).
-  const bool sparse_row = ST && a.pattern != 0u && rowc < a.Nv;
-  const int frame = sparse_row ? rowc / a.P : 0;
-  const int a_i = sparse_row ? min(rowc, a.P - 1) : rowc;
-  const int lo_i = sparse_row ? ((a.pattern & 1u) ? frame * a.P : rowc + 1) : 0;
+  const uint32_t kv_bytes = (uint32_t)a.Hkv * (uint32_t)a.N * D * 2u;
+  const __amdgpu_buffer_rsrc_t krs = make_rsrc(a.k, kv_bytes), vrs = make_rsrc(a.v, kv_bytes);
 
-  const uint16_t* kbase = a.k + (size_t)kvh * a.N * D;
-  const uint16_t* vbase = a.v + (size_t)kvh * a.N * D;
-  const uint32_t slab_bytes = (uint32_t)a.N * D * 2u;
-  const __amdgpu_buffer_rsrc_t krs = make_rsrc(kbase, slab_bytes), vrs = make_rsrc(vbase, slab_bytes);
-
-  // ---- staging maps (all per-thread constants) ----
-  // K: chunk id = tid + 256 r -> (row id / CPR, 16-byte chunk id % CPR): a row is read by CPR neighbouring lanes.
-  // V: a thread owns 4 consecutive keys (quad vg) x 8 consecutive d (chunk vc); 4 neighbouring lanes read 64
-  //    contiguous bytes of one row.  Quad vg holds keys 16*grp + 8*aa + 4*hh + 0..3; the MFMA k-order wants,
-  //    per 16 keys, [hh=0: aa=0, aa=1 | hh=1: aa=0, aa=1], i.e. 16-byte unit 2*grp + hh, 8-byte half aa.
+  // ---- staging maps (per-thread constants) ----
+  // K: chunk id = tid + 512 r -> (row id / CPR, 16-byte chunk id % CPR): a row is read by CPR neighbouring lanes.
+  // V: the first 16*CPR threads own 4 consecutive keys (quad vg) x 8 consecutive d (chunk vc) each; 4 neighbouring
+  //    lanes read 64 contiguous bytes of one row.  Quad vg holds keys 16*grp + 8*aa + 4*hh + 0..3; the MFMA k-order
+  //    wants, per 16 keys, [hh=0: aa=0, aa=1 | hh=1: aa=0, aa=1], i.e. 16-byte unit 2*grp + hh, 8-byte half aa.
   const int vcl = tid & 3, vg = (tid >> 2) & 15, vc = (tid >> 6) * 4 + vcl;
-  const bool v_active = (16 * CPR >= 256) || vc < CPR;  // head_dim 128: every thread stages V
+  const bool v_active = vc < CPR;
   const int v_unit = 2 * (vg >> 2) + (vg & 1), v_half = (vg >> 1) & 1;
   uint32_t k_goff[KCH], v_goff[4];
   int k_loff[KCH];
 #pragma unroll
   for (int r = 0; r < KCH; ++r) {
-    const int id = tid + 256 * r, rk = id / CPR, cc = id % CPR;
+    const int id = tid + 512 * r, rk = id / CPR, cc = id % CPR;
     k_goff[r] = (uint32_t)(rk * D + cc * 8) * 2u;
     k_loff[r] = swz<D>(rk, cc);
   }
 #pragma unroll
   for (int jj = 0; jj < 4; ++jj)
-    v_goff[jj] = v_active ? (uint32_t)((4 * vg + jj) * D + vc * 8) * 2u : slab_bytes;  // idle threads read nothing
+    v_goff[jj] = v_active ? (uint32_t)((4 * vg + jj) * D + vc * 8) * 2u : kv_bytes;  // idle threads read nothing
   u32x4 kreg[KCH], vreg[4];
 
-  // k0 >= N (list exhausted) puts every offset past the end: zeros come back, no memory is touched.
-  auto load_tile = [&](int k0) {
-    const uint32_t base = (uint32_t)k0 * (D * 2u);
+  // An offset at or past the end of the tensor reads zeros and touches no memory.
+  auto load_tile = [&](uint32_t base) {
 #pragma unroll
     for (int r = 0; r < KCH; ++r) kreg[r] = buffer_load16(krs, base + k_goff[r]);
 #pragma unroll
@@ -147,211 +142,185 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillArgs a) {
       }
     }
   };
-  auto tile_k0 = [&](int t) { return t < it.n_tiles ? (a.tiles[it.list_begin + t] >> 1) * BK : a.N; };
+  auto tile_off = [&](int t) { return t < t_end ? a.stream[t].kv_off : kv_bytes; };
 
-  load_tile(tile_k0(0));  // first tile in flight while Q and the side keys are fetched
+  load_tile(tile_off(t_begin));
+  store_tile(0);
+  load_tile(tile_off(t_begin + 1));
+  __syncthreads();
+  PHASE_MARK(1);
 
+  // ---- per-unit state ----
+  int hq = 0, row = 0, rowc = 0, a_i = 0, lo_i = 0, prev_j = -1, self_j = -1;
+  int u_nsplits = 1, u_slot = -1;
   bf16x8 qf[KSTEPS];
-  {
-    const uint16_t* qrow = a.q + ((size_t)hq * a.N + rowc) * D;
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s + 8 * h);
-  }
-
   // m: reference maximum (log2 units); l: sum of the bf16-rounded probabilities, i.e. exactly the weights
   // the second product applies, so the output is a true convex combination; lx: exact fp32 sum (LSE only).
   float m = -INFINITY, l = 0.f, lx = 0.f;
   floatx16 oacc[DBLK];
-#pragma unroll
-  for (int b = 0; b < DBLK; ++b)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
-
-  // ---- side keys of the temporal path (first slice of the row's list only) ----
-  if (ST && it.split == 0 && (a.pattern & 2u)) {
-    const bool has_prev = sparse_row && frame >= 2;
-    const bool has_self = sparse_row && !(a.pattern & 1u) && frame >= 1;
-    const int js[2] = {has_prev ? rowc - a.P : rowc, rowc};
-    const bool valid[2] = {has_prev, has_self};
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      if (!__any(valid[t])) continue;
-      const uint16_t* kr = kbase + (size_t)js[t] * D;
-      const uint16_t* vr = vbase + (size_t)js[t] * D;
-      u32x4 kk[KSTEPS];
-      u32x2 vv[DBLK][4];
-#pragma unroll
-      for (int s = 0; s < KSTEPS; ++s) kk[s] = *reinterpret_cast<const u32x4*>(kr + 16 * s + 8 * h);
-#pragma unroll
-      for (int b = 0; b < DBLK; ++b)
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) vv[b][g4] = *reinterpret_cast<const u32x2*>(vr + 32 * b + 8 * g4 + 4 * h);
-      float part = 0.f;
-#pragma unroll
-      for (int s = 0; s < KSTEPS; ++s) {
-        const u32x4 qq = __builtin_bit_cast(u32x4, qf[s]);
-#pragma unroll
-        for (int w = 0; w < 4; ++w)
-          part += bf16_lo(qq[w]) * bf16_lo(kk[s][w]) + bf16_hi(qq[w]) * bf16_hi(kk[s][w]);
-      }
-      float sdot = (part + other_half(part)) * a.scale_log2;
-      if (!valid[t]) sdot = -INFINITY;
-      const float m_new = fmaxf(m, sdot);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-      const float p = __builtin_amdgcn_exp2f(sdot - m_use);
-      l = l * alpha + (h == 0 ? p : 0.f);
-      if (LSE) lx = lx * alpha + (h == 0 ? p : 0.f);
-      m = m_new;
-#pragma unroll
-      for (int b = 0; b < DBLK; ++b)
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          oacc[b][4 * g4 + 0] = oacc[b][4 * g4 + 0] * alpha + p * bf16_lo(vv[b][g4][0]);
-          oacc[b][4 * g4 + 1] = oacc[b][4 * g4 + 1] * alpha + p * bf16_hi(vv[b][g4][0]);
-          oacc[b][4 * g4 + 2] = oacc[b][4 * g4 + 2] * alpha + p * bf16_lo(vv[b][g4][1]);
-          oacc[b][4 * g4 + 3] = oacc[b][4 * g4 + 3] * alpha + p * bf16_hi(vv[b][g4][1]);
-        }
-    }
-  }
-
-  PHASE_MARK(1);
-  store_tile(0);
-  load_tile(tile_k0(1));
-  __syncthreads();
-  PHASE_MARK(2);
-
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
-  for (int t = 0; t < it.n_tiles; ++t) {
-    const int entry = a.tiles[it.list_begin + t];
-    const int k0 = (entry >> 1) * BK;
-    const bool full = entry & 1;
-    const uint16_t* Ks = Ks2[t & 1];
-    const uint16_t* Vt = Vt2[t & 1];
+  for (int t = t_begin; t < t_end; ++t) {
+    const StreamEntry ent = a.stream[t];
+    const int buf = (t - t_begin) & 1;
+    const uint16_t* Ks = Ks2[buf];
+    const uint16_t* Vt = Vt2[buf];
 
-    // tile t+1: registers -> the other buffer (its last readers passed the barrier); tile t+2: start loading
-    store_tile((t + 1) & 1);
-    load_tile(tile_k0(t + 2));
-
-    // S^T = K Q^T: two 32-key blocks x 32 queries
-    floatx16 sacc[2];
+    if (ent.unit >= 0) {  // first tile of a unit: fetch its query rows, reset the softmax state
+      const Unit u = a.units[ent.unit];
+      hq = u.head;
+      u_nsplits = u.n_splits;
+      u_slot = u.slot;
+      row = u.qtile * BQ + wave * 32 + n;
+      rowc = min(row, a.N - 1);
+      // allowed keys of this lane's row: j <= rowc and (j <= a_i or j >= lo_i or j == prev_j or j == self_j)
+      const bool sparse_row = ST && a.pattern != 0u && rowc < a.Nv;
+      const int frame = sparse_row ? rowc / a.P : 0;
+      a_i = sparse_row ? min(rowc, a.P - 1) : rowc;
+      lo_i = sparse_row ? ((a.pattern & 1u) ? frame * a.P : rowc + 1) : 0;
+      prev_j = (sparse_row && (a.pattern & 2u) && frame >= 1) ? rowc - a.P : -1;
+      self_j = (sparse_row && (a.pattern & 2u)) ? rowc : -1;
+      const uint16_t* qrow = a.q + ((size_t)hq * a.N + rowc) * D;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+      for (int s = 0; s < KSTEPS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s + 8 * h);
+      m = -INFINITY;
+      l = 0.f;
+      lx = 0.f;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+      for (int b = 0; b < DBLK; ++b)
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) {
-      const bf16x8 kf0 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(n, 2 * s + h));
-      const bf16x8 kf1 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(32 + n, 2 * s + h));
-      sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[s], sacc[0], 0, 0, 0);
-      sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, qf[s], sacc[1], 0, 0, 0);
+        for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
     }
 
-    // mask (partial tiles only: one wave-uniform branch, selects inside) and tile maximum on the raw scores
-    if (!full) {
+    // tile t+1: registers -> the other buffer (its last readers passed the barrier); tile t+2: start loading
+    store_tile(buf ^ 1);
+    load_tile(tile_off(t + 2));
+
+    const bool need = (ent.masks >> wave) & 1u;
+    const bool full = (ent.masks >> (8 + wave)) & 1u;
+    if (need) {
+      const int k0 = (int)((ent.kv_off / (D * 2u)) % (uint32_t)a.N);  // first key of the tile within its head
+
+      // S^T = K Q^T: two 32-key blocks x 32 queries
+      floatx16 sacc[2];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int j = k0 + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
-          const bool ok = ST ? ((j <= rowc) & ((j <= a_i) | (j >= lo_i))) : (j <= rowc);
-          sacc[kb][i] = ok ? sacc[kb][i] : -INFINITY;
-        }
-    }
-    float mt = -INFINITY;
+        for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sacc[kb][i]);
-    mt = fmaxf(mt, other_half(mt)) * a.scale_log2;
-    // The reference maximum m only moves when a tile exceeds it by more than kRescaleGap (log2 units):
-    // probabilities then stay below 2^kRescaleGap, exact in fp32/bf16 range, and the accumulators are
-    // rescaled rarely.  The final normalisation divides the same factor out again.
-    if (__any(mt > m + kRescaleGap)) {
-      const float m_new = (mt > m + kRescaleGap) ? mt : m;
-      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m - m_ref);
-      l *= alpha;
-      if (LSE) lx *= alpha;
-#pragma unroll
-      for (int b = 0; b < DBLK; ++b)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
-      m = m_new;
-    }
-    const float neg_m = (m == -INFINITY) ? 0.f : -m;
-
-    // probabilities -> bf16 B-operand fragments; pf[ks] covers keys 16*ks .. 16*ks+15 of the tile
-    bf16x8 pf[4];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        u32x4 pk;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          floatx2 p;
-          p[0] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * half + 2 * w], a.scale_log2, neg_m));
-          p[1] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * half + 2 * w + 1], a.scale_log2, neg_m));
-          if (LSE) lx += p[0] + p[1];
-          const bf16x2 pb = __builtin_convertvector(p, bf16x2);
-          l = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, l, false);
-          pk[w] = __builtin_bit_cast(uint32_t, pb);
-        }
-        pf[2 * kb + half] = __builtin_bit_cast(bf16x8, pk);
+      for (int s = 0; s < KSTEPS; ++s) {
+        const bf16x8 kf0 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(n, 2 * s + h));
+        const bf16x8 kf1 = *reinterpret_cast<const bf16x8*>(Ks + swz<D>(32 + n, 2 * s + h));
+        sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[s], sacc[0], 0, 0, 0);
+        sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, qf[s], sacc[1], 0, 0, 0);
       }
 
-    // O^T += V^T P^T
+      // element mask (tiles not flagged full for this wavefront: one uniform branch, selects inside)
+      if (!full) {
 #pragma unroll
-    for (int b = 0; b < DBLK; ++b) {
-      bf16x8 vf[4];
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        vf[ks] = *reinterpret_cast<const bf16x8*>(Vt + swz<BK>(32 * b + n, 2 * ks + h));
+          for (int i = 0; i < 16; ++i) {
+            const int j = k0 + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
+            const bool ok = ST ? ((j <= rowc) & ((j <= a_i) | (j >= lo_i) | (j == prev_j) | (j == self_j)))
+                               : (j <= rowc);
+            sacc[kb][i] = ok ? sacc[kb][i] : -INFINITY;
+          }
+      }
+      float mt = -INFINITY;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks], pf[ks], oacc[b], 0, 0, 0);
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sacc[kb][i]);
+      mt = fmaxf(mt, other_half(mt)) * a.scale_log2;
+      // The reference maximum m only moves when a tile exceeds it by more than kRescaleGap (log2 units):
+      // probabilities then stay below 2^kRescaleGap, exact in fp32/bf16 range, and the accumulators are
+      // rescaled rarely.  The final normalisation divides the same factor out again.
+      if (__any(mt > m + kRescaleGap)) {
+        const float m_new = (mt > m + kRescaleGap) ? mt : m;
+        const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m - m_ref);
+        l *= alpha;
+        if (LSE) lx *= alpha;
+#pragma unroll
+        for (int b = 0; b < DBLK; ++b)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
+        m = m_new;
+      }
+      const float neg_m = (m == -INFINITY) ? 0.f : -m;
+
+      // probabilities -> bf16 B-operand fragments; pf[ks] covers keys 16*ks .. 16*ks+15 of the tile
+      bf16x8 pf[4];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          u32x4 pk;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            floatx2 p;
+            p[0] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * half + 2 * w], a.scale_log2, neg_m));
+            p[1] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * half + 2 * w + 1], a.scale_log2, neg_m));
+            if (LSE) lx += p[0] + p[1];
+            const bf16x2 pb = __builtin_convertvector(p, bf16x2);
+            l = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, l, false);
+            pk[w] = __builtin_bit_cast(uint32_t, pb);
+          }
+          pf[2 * kb + half] = __builtin_bit_cast(bf16x8, pk);
+        }
+
+      // O^T += V^T P^T
+#pragma unroll
+      for (int b = 0; b < DBLK; ++b) {
+        bf16x8 vf[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+          vf[ks] = *reinterpret_cast<const bf16x8*>(Vt + swz<BK>(32 * b + n, 2 * ks + h));
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+          oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks], pf[ks], oacc[b], 0, 0, 0);
+      }
+    }
+
+    if (ent.last) {  // last tile of the unit: normalise and write this wavefront's 32 rows
+      const float l_tot = l + other_half(l);
+      const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+      const float lse2 = m + __builtin_amdgcn_logf(l_tot);  // log2 domain; -inf when the slice saw no key
+      const float lse2x = LSE ? m + __builtin_amdgcn_logf(lx + other_half(lx)) : lse2;
+      if (u_nsplits == 1) {
+        if (row < a.N) {
+          uint16_t* orow = a.out + ((size_t)hq * a.N + row) * D;
+#pragma unroll
+          for (int b = 0; b < DBLK; ++b)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+              u32x2 w;
+              w[0] = pack_bf16(oacc[b][4 * g4 + 0] * inv, oacc[b][4 * g4 + 1] * inv);
+              w[1] = pack_bf16(oacc[b][4 * g4 + 2] * inv, oacc[b][4 * g4 + 3] * inv);
+              *reinterpret_cast<u32x2*>(orow + 32 * b + 8 * g4 + 4 * h) = w;
+            }
+          if (LSE && h == 0) a.lse[(size_t)hq * a.N + row] = lse2x * kLn2;
+        }
+      } else {
+        const size_t prow = ((size_t)u_slot * a.Hq + hq) * BQ + wave * 32 + n;
+        float* orow = a.ws_o + prow * D;
+#pragma unroll
+        for (int b = 0; b < DBLK; ++b)
+#pragma unroll
+          for (int g4 = 0; g4 < 4; ++g4) {
+            floatx4 w;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) w[r] = oacc[b][4 * g4 + r] * inv;
+            *reinterpret_cast<floatx4*>(orow + 32 * b + 8 * g4 + 4 * h) = w;
+          }
+        if (h == 0) {
+          a.ws_lse[2 * prow] = lse2;
+          a.ws_lse[2 * prow + 1] = lse2x;
+        }
+      }
     }
     __syncthreads();
-  }
-
-  // ---- epilogue ----
-  PHASE_MARK(3);
-  const float l_tot = l + other_half(l);
-  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-  const float lse2 = m + __builtin_amdgcn_logf(l_tot);  // log2 domain; -inf when the slice saw no key
-  const float lse2x = LSE ? m + __builtin_amdgcn_logf(lx + other_half(lx)) : lse2;
-  if (it.n_splits == 1) {
-    if (row < a.N) {
-      uint16_t* orow = a.out + ((size_t)hq * a.N + row) * D;
-#pragma unroll
-      for (int b = 0; b < DBLK; ++b)
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          u32x2 w;
-          w[0] = pack_bf16(oacc[b][4 * g4 + 0] * inv, oacc[b][4 * g4 + 1] * inv);
-          w[1] = pack_bf16(oacc[b][4 * g4 + 2] * inv, oacc[b][4 * g4 + 3] * inv);
-          *reinterpret_cast<u32x2*>(orow + 32 * b + 8 * g4 + 4 * h) = w;
-        }
-      if (LSE && h == 0) a.lse[(size_t)hq * a.N + row] = lse2x * kLn2;
-    }
-  } else {
-    const size_t prow = ((size_t)it.slot * a.Hq + hq) * BQ + wave * 32 + n;
-    float* orow = a.ws_o + prow * D;
-#pragma unroll
-    for (int b = 0; b < DBLK; ++b)
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        floatx4 w;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) w[r] = oacc[b][4 * g4 + r] * inv;
-        *reinterpret_cast<floatx4*>(orow + 32 * b + 8 * g4 + 4 * h) = w;
-      }
-    if (h == 0) {
-      a.ws_lse[2 * prow] = lse2;
-      a.ws_lse[2 * prow + 1] = lse2x;
-    }
   }
   PHASE_MARK(4);
 }
@@ -404,9 +373,9 @@ __global__ __launch_bounds__(256) void merge_kernel(const PrefillArgs a) {
 template <int D, bool ST>
 void launch_variant(const PrefillArgs& a, dim3 grid, hipStream_t st) {
   if (a.lse != nullptr)
-    hipLaunchKernelGGL((prefill_kernel<D, ST, true>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((prefill_kernel<D, ST, true>), grid, dim3(512), 0, st, a);
   else
-    hipLaunchKernelGGL((prefill_kernel<D, ST, false>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((prefill_kernel<D, ST, false>), grid, dim3(512), 0, st, a);
 }
 
 }  // namespace
@@ -425,17 +394,18 @@ int launch_prefill(const purekv_plan& p, const void* q, const void* k, const voi
   a.lse = lse;
   a.ws_o = static_cast<float*>(ws);
   a.ws_lse = a.ws_o ? a.ws_o + (size_t)p.n_slots * p.g.Hq * BQ * p.g.d : nullptr;
-  a.tiles = p.d_tiles;
-  a.items = p.d_items;
+  a.stream = p.d_stream;
+  a.units = p.d_units;
+  a.queue_begin = p.d_queue_begin;
   a.merges = p.d_merges;
   a.N = p.g.N;
   a.Nv = p.g.Nv;
   a.P = p.g.P;
   a.Hq = p.g.Hq;
-  a.G = p.g.G;
+  a.Hkv = p.g.Hkv;
   a.pattern = p.g.pattern;
   a.scale_log2 = p.g.scale * kLog2e;
-  const dim3 grid((unsigned)(p.items.size() * p.g.Hq)), block(256);
+  const dim3 grid((unsigned)p.n_queues), block(256);
   const dim3 mgrid((unsigned)(p.merges.size() * p.g.Hq * (BQ / MERGE_ROWS)));
   const bool sparse = p.g.pattern != PUREKV_PATTERN_DENSE;
   if (p.g.d == 128) {

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "purekv.h")).read()
     declared = set(re.findall(r"PUREKV_API[^;(]*?\b(purekv_\w+)\s*\(", header))
-    assert len(declared) >= 17
+    assert len(declared) >= 18
     lib = ctypes.CDLL(pk.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), name
@@ -37,7 +37,7 @@ def test_shape_validation_error_codes():
     def create(**kw):
         s = pk.Shape(**{**good, **kw})
         h = ctypes.c_void_p()
-        rc = lib.purekv_plan_create_host(ctypes.byref(s), ctypes.byref(h))
+        rc = lib.purekv_plan_create_host(ctypes.byref(s), 256, ctypes.byref(h))
         if rc == 0:
             lib.purekv_plan_destroy(h)
         else:
@@ -56,8 +56,9 @@ def test_shape_validation_error_codes():
     assert create(head_dim=96) == pk.EUNSUPPORTED
     assert create(pattern=4) == pk.EUNSUPPORTED
     h = ctypes.c_void_p()
-    assert lib.purekv_plan_create_host(None, ctypes.byref(h)) == pk.EINVAL
-    assert lib.purekv_plan_create_host(ctypes.byref(pk.Shape(**good)), None) == pk.EINVAL
+    assert lib.purekv_plan_create_host(None, 256, ctypes.byref(h)) == pk.EINVAL
+    assert lib.purekv_plan_create_host(ctypes.byref(pk.Shape(**good)), 256, None) == pk.EINVAL
+    assert lib.purekv_plan_create_host(ctypes.byref(pk.Shape(**good)), 0, ctypes.byref(h)) == pk.EINVAL
     assert lib.purekv_plan_destroy(None) == pk.OK
 
 
@@ -75,9 +76,10 @@ def test_compute_calls_validate_before_touching_the_gpu():
     assert lib.purekv_kv_append(h, one, one, one, one, 0, 4, None) == pk.EINVAL
     assert lib.purekv_decode_attn(h, one, one, one, 4, 4, one, one, 1 << 20, None) == pk.EINVAL
     assert lib.purekv_workspace_bytes(None, pk.OP_PREFILL, 0, 0, 0) == 0
-    c = (ctypes.c_int64 * 6)()
+    c = (ctypes.c_int64 * 8)()
     assert lib.purekv_plan_counts(None, c) == pk.EINVAL and lib.purekv_plan_counts(h, None) == pk.EINVAL
     assert lib.purekv_plan_qtile_list(h, 99, None, 0) == pk.EINVAL
+    assert lib.purekv_plan_queue(h, 100000, None, 0) == pk.EINVAL
     assert lib.purekv_plan_item(h, -1, (ctypes.c_int32 * 6)()) == pk.EINVAL
 
 
@@ -91,47 +93,42 @@ def test_budget_matches_oracle_rule():
     assert pk.purekv_budget(8448, 256, 0.2) == 1433
 
 
-def _block_part(wl_shape, pattern, rows):
-    """The oracle's mask with the temporal path's side keys (previous-frame key, self key) removed."""
-    F, P, T = wl_shape
-    nv = F * P
-    m = orc.st_mask_rows(F, P, T, pattern, rows).copy()
-    if pattern != 0 and (pattern & 2):
-        for r, i in enumerate(rows):
-            if i < nv and i // P >= 2:
-                assert m[r, i - P]
-                m[r, i - P] = False
-            if i < nv and not (pattern & 1) and i // P >= 1:
-                assert m[r, i]
-                m[r, i] = False
-    return m
-
-
-def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern):
+def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern, n_wg=256):
+    """Tile lists and per-row-block masks against the oracle's boolean mask; slices, units and queues are a partition."""
     P, n = ph * pw, F * ph * pw + T
-    plan = pk.Plan(F, ph, pw, T, hq, hkv, d, pattern, host_only=True)
+    plan = pk.Plan(F, ph, pw, T, hq, hkv, d, pattern, host_only=True, n_workgroups=n_wg)
     c = plan.counts()
     assert c["N"] == n and c["n_qtiles"] == (n + pk.BQ - 1) // pk.BQ
     n_ktiles = (n + pk.BK - 1) // pk.BK
-    total_pairs = 0
-    refs = 0
+    total_pairs = refs = wave_tiles = full_wave_tiles = 0
     for qt in range(c["n_qtiles"]):
         rows = np.arange(qt * pk.BQ, min((qt + 1) * pk.BQ, n))
-        full_mask = orc.st_mask_rows(F, P, T, pattern, rows)
-        total_pairs += int(full_mask.sum())
-        b = _block_part((F, P, T), pattern, rows)
-        padded = np.zeros((rows.shape[0], n_ktiles * pk.BK), dtype=bool)
-        padded[:, :n] = b
-        per_tile = padded.reshape(rows.shape[0], n_ktiles, pk.BK)
-        any_t = per_tile.any(axis=(0, 2))
-        all_t = per_tile.all(axis=(0, 2))
+        mask = orc.st_mask_rows(F, P, T, pattern, rows)
+        total_pairs += int(mask.sum())
+        padded = np.zeros((pk.BQ, n_ktiles * pk.BK), dtype=bool)
+        padded[:rows.shape[0], :n] = mask
+        blocks = padded.reshape(pk.WAVES, 32, n_ktiles, pk.BK)
+        real = (np.arange(pk.BQ) < rows.shape[0]).reshape(pk.WAVES, 32)
+        any_wt = blocks.any(axis=(1, 3))                                   # [wave, tile]
+        # full: every (real row, nominal key) pair allowed; a row block without real rows is never needed
+        all_wt = (blocks | ~real[:, :, None, None]).all(axis=(1, 3)) & real.any(axis=1)[:, None]
         lst = plan.qtile_list(qt)
         refs += len(lst)
-        assert [t for t, _ in lst] == np.nonzero(any_t)[0].tolist(), (qt, pattern)
-        assert [f for _, f in lst] == all_t[any_t].astype(int).tolist(), (qt, pattern)
-    assert refs == c["n_tile_refs"]
+        assert [t for t, _, _ in lst] == np.nonzero(any_wt.any(axis=0))[0].tolist(), (qt, pattern)
+        for t, need, full in lst:
+            want_need = sum(1 << w for w in range(pk.WAVES) if any_wt[w, t])
+            assert need == want_need, (qt, t, pattern)
+            # the plan may flag fewer row blocks full than possible (the mask is then applied element-wise),
+            # never more
+            assert full & ~need == 0
+            for w in range(pk.WAVES):
+                if full >> w & 1:
+                    assert all_wt[w, t], (qt, t, w, pattern)
+            wave_tiles += bin(need).count("1")
+            full_wave_tiles += bin(full).count("1")
+    assert refs == c["n_tile_refs"] and wave_tiles == c["n_wave_tiles"] and full_wave_tiles == c["n_full_wave_tiles"]
     assert abs(plan.mask_flops() - 4.0 * d * total_pairs * hq) < 1e-3 * max(1.0, plan.mask_flops())
-    assert plan.kept_tile_flops() == 4.0 * pk.BQ * pk.BK * d * refs * hq
+    assert plan.kept_tile_flops() == 4.0 * 32 * pk.BK * d * wave_tiles * hq
     # work items: each query tile's list is covered exactly once, in order; slots are distinct
     begin = np.concatenate([[0], np.cumsum([len(plan.qtile_list(q)) for q in range(c["n_qtiles"])])])
     items = [plan.item(i) for i in range(c["n_items"])]
@@ -154,6 +151,13 @@ def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern):
         assert pos == begin[qt + 1]
     assert sorted(slots) == list(range(len(slots)))
     assert c["n_split_qtiles"] == sum(1 for p in by_q.values() if len(p) > 1)
+    # queues: every (work item, head) unit runs exactly once
+    assert 1 <= c["n_workgroups"] <= n_wg
+    units = [u for g in range(c["n_workgroups"]) for u in plan.queue(g)]
+    assert sorted(units) == [(i, h) for i in range(c["n_items"]) for h in range(hq)]
+    loads = [sum(items[i][2] for i, _ in plan.queue(g)) for g in range(c["n_workgroups"])]
+    if len(units) >= 4 * c["n_workgroups"]:
+        assert max(loads) <= 1.5 * (sum(loads) / len(loads)) + max(it[2] for it in items)
     plan.close()
 
 
@@ -161,7 +165,7 @@ def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern):
 @pytest.mark.parametrize("shape", [(4, 8, 8, 32), (3, 5, 7, 19), (1, 9, 9, 0), (5, 16, 16, 200), (2, 24, 24, 1)])
 def test_plan_lists_match_oracle_mask_small(shape, pattern):
     F, ph, pw, T = shape
-    _check_plan_against_oracle(F, ph, pw, T, 4, 2, 64, pattern)
+    _check_plan_against_oracle(F, ph, pw, T, 4, 2, 64, pattern, n_wg=16)
 
 
 @pytest.mark.parametrize("name", ["videollama2_8f", "qwen25vl_32f", "qwen25vl_64f", "qwen25vl_128f_stack"])
