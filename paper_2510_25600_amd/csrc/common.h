@@ -33,7 +33,12 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 }
 
 // Value held by the lane 32 positions away (the other half of the wavefront).
-__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
+// v_permlane32_swap exchanges the two halves in the vector ALU (no LDS traffic, unlike ds_bpermute).
+__device__ __forceinline__ float other_half(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  // r[0]: lanes 0-31 keep their own value and lanes 32-63 receive lanes 0-31's; r[1] the converse
+  return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
 
 // Records a failed HIP call for purekv_strerror and maps it to PUREKV_EHIP.
 int note_hip_error(hipError_t e);
