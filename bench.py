@@ -228,7 +228,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.n_frames}f x {wl.patch_h}x{wl.patch_w} + {wl.n_text} text = {n} tokens, "
                                f"{hq}q/{hkv}kv heads, d={d}, keep ratio {args.ratio} (h={h}, w={w})",
-                   "tile": f"32-row block x {pk.BK} keys (8 blocks per {pk.BQ}-row workgroup tile)", "step": "low layer (dense prefill+LSE, importance, top-h, compaction) + "
+                   "tile": f"{pk.BLOCK}-row block x {pk.BLOCK}-key block ({pk.WAVES} wavefronts of {pk.BLOCK} rows per workgroup, {pk.BK}-key tiles)", "step": "low layer (dense prefill+LSE, importance, top-h, compaction) + "
                    "high layer (ST-SpAttn prefill, top-h, compaction, append+decode)"},
         "prefill_ms_per_layer": round(st_call_ms, 4),
         "prefill_ms_per_layer_back_to_back": round(st_ms, 4),

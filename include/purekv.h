@@ -74,13 +74,20 @@ typedef enum {
 
 /*
  * Plan: the static block structure of the mask for one shape (Sec. 3.2: the pattern depends only on
- * F, P, T) and the static schedule of the prefill kernel.  For every tile of PUREKV_BQ query rows it
- * lists the tiles of PUREKV_BK keys that hold at least one allowed (query, key) pair, with two bit masks
- * over the tile's PUREKV_WAVES row blocks of 32 rows: `need` (the block has an allowed pair in the key
- * tile) and `full` (every pair of the block with the key tile is allowed, so no element mask is
- * needed).  Long lists are cut into slices (work items) whose partial results are merged; every (work
- * item, query head) unit is dealt to one of the persistent workgroups of the prefill kernel (one per
- * compute unit), longest first, KV heads kept on fixed XCDs where the head counts allow it.
+ * F, P, T) and the static schedule of the prefill kernel.
+ *
+ * A prefill workgroup has PUREKV_WAVES wavefronts of PUREKV_BLOCK (32) query rows each.  The plan stacks
+ * Gs query heads that share a KV head times R row blocks in one workgroup (wavefront w: row block w / Gs,
+ * head w % Gs; Gs * R <= PUREKV_WAVES), because the mask depends on the row and not on the head: stacked
+ * heads need exactly the same key tiles.  A query tile is R * 32 rows.  For every query tile the plan lists
+ * the tiles of PUREKV_BK (64) keys that hold at least one allowed (query, key) pair and, per (row block rb,
+ * 32-key half kb) of such a tile, a `need` bit (bit 2*rb + kb: the pair of blocks holds an allowed pair) and a
+ * two-bit kind (bits 4*rb + 2*kb of `kinds`) that says how cheaply the element mask can be applied:
+ * PUREKV_KIND_FULL (every pair allowed), _CAUSAL (allowed <=> key <= query), _PREV (allowed <=> key ==
+ * query - P) or _GENERAL (the whole predicate).  Long lists are cut into slices (work items) whose partial
+ * results are merged; every (work item, head group) unit is dealt to one of the persistent workgroups of the
+ * prefill kernel (one per compute unit), longest first, KV heads kept on fixed XCDs where the head counts
+ * allow it.
  *
  * purekv_plan_create builds the lists on the host and uploads them to the current device (KB to a few
  * MB, owned by the plan; `stream` orders the upload).  purekv_plan_create_host only builds the host
@@ -88,26 +95,32 @@ typedef enum {
  * launched: compute calls return EINVAL).  `*out` is written only on success.  Destroy with
  * purekv_plan_destroy (NULL is accepted).
  */
-#define PUREKV_BQ 256
+#define PUREKV_BLOCK 32
 #define PUREKV_BK 64
 #define PUREKV_WAVES 8
+#define PUREKV_KIND_FULL 0u
+#define PUREKV_KIND_CAUSAL 1u
+#define PUREKV_KIND_PREV 2u
+#define PUREKV_KIND_GENERAL 3u
 PUREKV_API int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* stream);
 PUREKV_API int purekv_plan_create_host(const purekv_shape_t* shape, int32_t n_workgroups, purekv_plan_t** out);
 PUREKV_API int purekv_plan_destroy(purekv_plan_t* plan);
 
-/* Plan inspection (host memory).  counts[0..7] = N, number of query tiles, number of work items,
- * number of (query tile, key tile) references, number of (reference, row block) pairs computed, number
- * of those flagged full, number of query tiles whose list is split, number of persistent workgroups. */
-PUREKV_API int purekv_plan_counts(const purekv_plan_t* plan, int64_t counts[8]);
-/* Copies the key-tile list of query tile `qt` into refs[0 .. 3*cap): triples {key tile index, need mask,
- * full mask}.  Returns the list length (may exceed cap; then only cap triples are written) or a negative
+/* Plan inspection (host memory).  counts[0..15] = N, number of query tiles, number of work items,
+ * number of (query tile, key tile) references, number of (row block, 32-key block) pairs computed per
+ * query head, number of query tiles whose list is split, number of persistent workgroups, R (row blocks
+ * per query tile), Gs (stacked heads), number of head groups (Hq / Gs), then the computed pairs by kind
+ * (full, causal, prev, general), then two zeros. */
+PUREKV_API int purekv_plan_counts(const purekv_plan_t* plan, int64_t counts[16]);
+/* Copies the key-tile list of query tile `qt` into refs[0 .. 3*cap): triples {key tile index, need bits,
+ * kind bits}.  Returns the list length (may exceed cap; then only cap triples are written) or a negative
  * status. */
 PUREKV_API int purekv_plan_qtile_list(const purekv_plan_t* plan, int32_t qt, int32_t* refs, int32_t cap);
 /* Copies work item `it` as {query tile, first list position, tile count, split index, number of
  * splits, partial-result slot or -1}.  Returns PUREKV_OK or a negative status. */
 PUREKV_API int purekv_plan_item(const purekv_plan_t* plan, int32_t it, int32_t item[6]);
 /* Copies the units of persistent workgroup `wg`, in execution order, into units[0 .. 2*cap): pairs {work
- * item, query head}.  Returns the number of units (may exceed cap) or a negative status. */
+ * item, first query head of the group}.  Returns the number of units (may exceed cap) or a negative status. */
 PUREKV_API int purekv_plan_queue(const purekv_plan_t* plan, int32_t wg, int32_t* units, int32_t cap);
 
 /* Device workspace bytes needed by `op` for this plan.  `n_layers`, `w` and `cap` are read by the ops
@@ -175,8 +188,8 @@ PUREKV_API int purekv_decode_attn(const purekv_plan_t* plan, const void* q_new, 
 /* h = max(0, floor(ratio * n) - w): the keep budget counts the recent window (20 % budget = 5.0x). */
 PUREKV_API int32_t purekv_budget(int32_t n, int32_t w, double ratio);
 
-/* Work counts for reporting: flops of one prefill call counted on the (32-row block, key tile) pairs the
- * kernel computes (4 * 32 * BK * d per pair and query head) and on the allowed pairs of the mask only. */
+/* Work counts for reporting: flops of one prefill call counted on the (32-row block, 32-key block) pairs the
+ * kernel computes (4 * 32 * 32 * d per pair and query head) and on the allowed pairs of the mask only. */
 PUREKV_API double purekv_plan_kept_tile_flops(const purekv_plan_t* plan);
 PUREKV_API double purekv_plan_mask_flops(const purekv_plan_t* plan);
 

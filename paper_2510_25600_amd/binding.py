@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libpurekv.so")
 PATTERN_DENSE, PATTERN_SPATIAL, PATTERN_TEMPORAL, PATTERN_ST = 0, 1, 2, 3
 OP_PREFILL, OP_IMPORTANCE, OP_TOPK, OP_COMPACT, OP_DECODE = 0, 1, 2, 3, 4
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5
-BQ, BK, WAVES = 256, 64, 8
+BLOCK, BK, WAVES = 32, 64, 8
+KIND_FULL, KIND_CAUSAL, KIND_PREV, KIND_GENERAL = 0, 1, 2, 3
 
 
 class Shape(ctypes.Structure):
@@ -153,22 +154,23 @@ class Plan:
 
     # ---- inspection -------------------------------------------------------------------------------
     def counts(self) -> dict:
-        c = (c_int64 * 8)()
+        c = (c_int64 * 16)()
         _check(_lib.purekv_plan_counts(self._h, c), "purekv_plan_counts")
-        return dict(N=c[0], n_qtiles=c[1], n_items=c[2], n_tile_refs=c[3], n_wave_tiles=c[4], n_full_wave_tiles=c[5],
-                    n_split_qtiles=c[6], n_workgroups=c[7])
+        return dict(N=c[0], n_qtiles=c[1], n_items=c[2], n_tile_refs=c[3], n_blocks=c[4], n_split_qtiles=c[5],
+                    n_workgroups=c[6], row_blocks=c[7], stacked_heads=c[8], n_head_groups=c[9],
+                    n_full_blocks=c[10], n_causal_blocks=c[11], n_prev_blocks=c[12], n_general_blocks=c[13])
 
     def qtile_list(self, qt: int) -> list:
-        """[(key tile, need mask, full mask)] of query tile `qt`."""
+        """[(key tile, need bits, kind bits)] of query tile `qt`: need bit 2*rb + kb, kind bits 4*rb + 2*kb."""
         n = _lib.purekv_plan_qtile_list(self._h, qt, None, 0)
         if n < 0:
             raise PureKVError(n, "purekv_plan_qtile_list")
         buf = (c_int32 * max(3 * n, 1))()
         _lib.purekv_plan_qtile_list(self._h, qt, buf, n)
-        return [(buf[3 * i], buf[3 * i + 1], buf[3 * i + 2]) for i in range(n)]
+        return [(buf[3 * i], buf[3 * i + 1] & 0xFFFFFFFF, buf[3 * i + 2] & 0xFFFFFFFF) for i in range(n)]
 
     def queue(self, wg: int) -> list:
-        """[(work item, query head)] run by persistent workgroup `wg`, in order."""
+        """[(work item, first query head of the group)] run by persistent workgroup `wg`, in order."""
         n = _lib.purekv_plan_queue(self._h, wg, None, 0)
         if n < 0:
             raise PureKVError(n, "purekv_plan_queue")

@@ -86,10 +86,13 @@ int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* s
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_stream), sb ? sb : 16);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_units), ub ? ub : 16);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_queue_begin), qb ? qb : 16);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_queue_unit0), qb ? qb : 16);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_merges), mb ? mb : 16);
   if (e == hipSuccess && sb) e = hipMemcpyAsync(p->d_stream, p->stream.data(), sb, hipMemcpyHostToDevice, st);
   if (e == hipSuccess && ub) e = hipMemcpyAsync(p->d_units, p->units.data(), ub, hipMemcpyHostToDevice, st);
   if (e == hipSuccess && qb) e = hipMemcpyAsync(p->d_queue_begin, p->queue_begin.data(), qb, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess && qb)
+    e = hipMemcpyAsync(p->d_queue_unit0, p->queue_units_begin.data(), qb, hipMemcpyHostToDevice, st);
   if (e == hipSuccess && mb) e = hipMemcpyAsync(p->d_merges, p->merges.data(), mb, hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);  // the host vectors must outlive the copies: finish them now
   if (e != hipSuccess) {
@@ -105,21 +108,26 @@ int purekv_plan_destroy(purekv_plan_t* p) {
   if (p->d_stream) (void)hipFree(p->d_stream);
   if (p->d_units) (void)hipFree(p->d_units);
   if (p->d_queue_begin) (void)hipFree(p->d_queue_begin);
+  if (p->d_queue_unit0) (void)hipFree(p->d_queue_unit0);
   if (p->d_merges) (void)hipFree(p->d_merges);
   delete p;
   return PUREKV_OK;
 }
 
-int purekv_plan_counts(const purekv_plan_t* p, int64_t counts[8]) {
+int purekv_plan_counts(const purekv_plan_t* p, int64_t counts[16]) {
   if (p == nullptr || counts == nullptr) return PUREKV_EINVAL;
   counts[0] = p->g.N;
   counts[1] = p->n_qtiles;
   counts[2] = (int64_t)p->items.size();
   counts[3] = (int64_t)p->tiles.size();
-  counts[4] = p->n_wave_tiles;
-  counts[5] = p->n_full_wave_tiles;
-  counts[6] = (int64_t)p->merges.size();
-  counts[7] = p->n_queues;
+  counts[4] = p->n_blocks;
+  counts[5] = (int64_t)p->merges.size();
+  counts[6] = p->n_queues;
+  counts[7] = p->g.R;
+  counts[8] = p->g.Gs;
+  counts[9] = p->g.n_groups;
+  for (int k = 0; k < 4; ++k) counts[10 + k] = p->n_kind[k];
+  counts[14] = counts[15] = 0;
   return PUREKV_OK;
 }
 
@@ -128,8 +136,8 @@ int purekv_plan_qtile_list(const purekv_plan_t* p, int32_t qt, int32_t* refs, in
   const int32_t b = p->qtile_begin[qt], len = p->qtile_begin[qt + 1] - b;
   for (int32_t i = 0; i < len && i < cap; ++i) {
     refs[3 * i] = p->tiles[b + i].tile;
-    refs[3 * i + 1] = p->tiles[b + i].need;
-    refs[3 * i + 2] = p->tiles[b + i].full;
+    refs[3 * i + 1] = (int32_t)p->tiles[b + i].need;
+    refs[3 * i + 2] = (int32_t)p->tiles[b + i].kinds;
   }
   return len;
 }
@@ -158,7 +166,7 @@ int purekv_plan_item(const purekv_plan_t* p, int32_t it, int32_t item[6]) {
 
 double purekv_plan_kept_tile_flops(const purekv_plan_t* p) {
   if (p == nullptr) return 0.0;
-  return 4.0 * kRowsPerWave * PUREKV_BK * p->g.d * (double)p->n_wave_tiles * p->g.Hq;
+  return 4.0 * kBlockRows * kBlockKeys * p->g.d * (double)p->n_blocks * p->g.Hq;
 }
 
 double purekv_plan_mask_flops(const purekv_plan_t* p) {

@@ -1,5 +1,5 @@
-// Host planner: turns (F, P, T, pattern) into per-query-tile key-tile lists with per-wavefront masks, cuts long
-// lists into slices, and deals (slice, head) units onto persistent workgroups.
+// Host planner: turns (F, P, T, pattern) into per-query-tile key-tile lists with per-block masks, cuts long
+// lists into slices, and deals (slice, head group) units onto persistent workgroups.
 // The mask follows the two ST-SpAttn paragraphs of Sec. 3.2 (spatial: first frame + own frame;
 // temporal: first frame + same patch one frame back), always causal, text queries dense.
 #include "plan.h"
@@ -27,15 +27,25 @@ inline RowSet row_set(const Geometry& g, int32_t i) {
   return r;
 }
 
+inline bool in_range(int32_t x, int32_t k0, int32_t k1) { return x >= k0 && x <= k1; }
+
+// Some key of [k0, k1] is allowed.
 inline bool row_hits(const RowSet& s, int32_t i, int32_t k0, int32_t k1) {
-  return (k0 <= s.a) || (std::max(k0, s.lo) <= std::min(k1, i)) || (s.prev >= k0 && s.prev <= k1) ||
-         (s.self >= k0 && s.self <= k1);
+  return (k0 <= s.a) || (std::max(k0, s.lo) <= std::min(k1, i)) || in_range(s.prev, k0, k1) ||
+         in_range(s.self, k0, k1);
 }
 
-// Every key of [k0, k1] allowed (single keys of the temporal path cannot fill a tile and are ignored here).
+// Every key of [k0, k1] is allowed; an empty range counts as allowed.  Single keys of the temporal path
+// are ignored here, so the answer can be a conservative "no".
 inline bool row_full(const RowSet& s, int32_t i, int32_t k0, int32_t k1) {
+  if (k0 > k1) return true;
   if (s.lo <= s.a + 1) return k1 <= i;
   return (k1 <= s.a) || (k0 >= s.lo && k1 <= i);
+}
+
+// The only key of [k0, k1] that can be allowed is the previous-frame key.
+inline bool row_prev_only(const RowSet& s, int32_t i, int32_t k0, int32_t k1) {
+  return k0 > s.a && !(std::max(k0, s.lo) <= std::min(k1, i)) && !in_range(s.self, k0, k1);
 }
 
 inline double row_pairs(const RowSet& s, int32_t i) {
@@ -45,55 +55,79 @@ inline double row_pairs(const RowSet& s, int32_t i) {
   return cnt;
 }
 
+// Largest divisor of g that is at most `cap`.
+inline int32_t largest_divisor_up_to(int32_t g, int32_t cap) {
+  for (int32_t x = std::min(g, cap); x >= 1; --x)
+    if (g % x == 0) return x;
+  return 1;
+}
+
 }  // namespace
 
 void build_plan(purekv_plan& p, int n_cu) {
-  const Geometry& g = p.g;
-  const int32_t BQ = PUREKV_BQ, BK = PUREKV_BK;
+  Geometry& g = p.g;
+  const int32_t BK = PUREKV_BK;
   p.n_cu = n_cu;
-  p.n_qtiles = (g.N + BQ - 1) / BQ;
+
+  // ---- workgroup shape ----
+  // Stacking the query heads of a KV group in one workgroup makes every wavefront of the workgroup need the
+  // same key tiles (the mask depends on the row, not on the head), so nobody waits at the tile barriers for
+  // work it does not share.  The dense pattern has little such imbalance (only the diagonal tiles): it stacks
+  // only when that fills all wavefronts, else one head x 8 row blocks keeps every SIMD busy.
+  {
+    const int32_t gs = largest_divisor_up_to(g.G, kWaves), r = kWaves / gs;
+    const bool stack = (g.pattern != PUREKV_PATTERN_DENSE && gs >= 2) || (gs * r == kWaves && gs >= 2);
+    g.Gs = stack ? gs : 1;
+    g.R = stack ? r : kWaves;
+    g.n_groups = g.Hq / g.Gs;
+  }
+  const int32_t rows_per_qtile = g.R * kBlockRows;
+  p.n_qtiles = (g.N + rows_per_qtile - 1) / rows_per_qtile;
   const int32_t n_ktiles = (g.N + BK - 1) / BK;
   p.qtile_begin.assign(1, 0);
   p.tiles.clear();
-  p.n_full_wave_tiles = 0;
-  p.n_wave_tiles = 0;
+  p.n_blocks = 0;
+  for (auto& c : p.n_kind) c = 0;
   p.mask_pairs = 0;
 
-  std::vector<RowSet> sets(BQ);
+  std::vector<RowSet> sets(rows_per_qtile);
   for (int32_t qt = 0; qt < p.n_qtiles; ++qt) {
-    const int32_t r0 = qt * BQ, r1 = std::min(r0 + BQ, g.N);  // rows [r0, r1)
+    const int32_t r0 = qt * rows_per_qtile, r1 = std::min(r0 + rows_per_qtile, g.N);  // rows [r0, r1)
     for (int32_t i = r0; i < r1; ++i) {
       sets[i - r0] = row_set(g, i);
       p.mask_pairs += row_pairs(sets[i - r0], i);
     }
     const int32_t last_tile = std::min((r1 - 1) / BK, n_ktiles - 1);  // causal: no key beyond the last row
     for (int32_t c = 0; c <= last_tile; ++c) {
-      const int32_t k0 = c * BK, k1 = k0 + BK - 1;
-      uint16_t need = 0, full = 0;
-      for (int32_t w = 0; w < kWaves; ++w) {
-        const int32_t w0 = r0 + w * kRowsPerWave, w1 = std::min(w0 + kRowsPerWave, r1);
-        if (w0 >= w1) continue;
-        bool any = false, all = true;
-        for (int32_t i = w0; i < w1; ++i) {
-          any |= row_hits(sets[i - r0], i, k0, k1);
-          all &= row_full(sets[i - r0], i, k0, k1);
-        }
-        if (any) {
-          need |= uint16_t(1u << w);
-          if (all) full |= uint16_t(1u << w);
+      uint32_t need = 0, kinds = 0;
+      for (int32_t rb = 0; rb < g.R; ++rb) {
+        const int32_t w0 = r0 + rb * kBlockRows, w1 = std::min(w0 + kBlockRows, r1);
+        if (w0 >= w1) continue;  // a row block without real rows is never needed
+        for (int32_t kb = 0; kb < 2; ++kb) {
+          const int32_t k0 = c * BK + kb * kBlockKeys, k1 = k0 + kBlockKeys - 1;
+          bool any = false, full = true, causal = true, prev = true;
+          for (int32_t i = w0; i < w1; ++i) {
+            const RowSet& s = sets[i - r0];
+            any |= row_hits(s, i, k0, k1);
+            full &= row_full(s, i, k0, k1);
+            causal &= row_full(s, i, k0, std::min(k1, i));
+            prev &= row_prev_only(s, i, k0, k1);
+          }
+          if (!any) continue;
+          const uint32_t kind = full ? kKindFull : causal ? kKindCausal : prev ? kKindPrev : kKindGeneral;
+          need |= 1u << (2 * rb + kb);
+          kinds |= kind << (4 * rb + 2 * kb);
+          ++p.n_blocks;
+          ++p.n_kind[kind];
         }
       }
-      if (need) {
-        p.tiles.push_back({c, need, full});
-        p.n_wave_tiles += __builtin_popcount(need);
-        p.n_full_wave_tiles += __builtin_popcount(full);
-      }
+      if (need) p.tiles.push_back({c, need, kinds});
     }
     p.qtile_begin.push_back(static_cast<int32_t>(p.tiles.size()));
   }
 
   // ---- work items: cut lists that are long against the average load of one workgroup ----
-  const double total_steps = double(p.tiles.size()) * g.Hq;
+  const double total_steps = double(p.tiles.size()) * g.n_groups;
   const int32_t chunk = std::max<int32_t>(8, static_cast<int32_t>(0.8 * total_steps / std::max(1, n_cu) + 0.5));
   p.items.clear();
   p.merges.clear();
@@ -118,17 +152,17 @@ void build_plan(purekv_plan& p, int n_cu) {
   std::stable_sort(p.items.begin(), p.items.end(),
                    [](const WorkItem& x, const WorkItem& y) { return x.n_tiles > y.n_tiles; });
 
-  // ---- deal (item, head) units onto persistent workgroups: longest first, least-loaded queue ----
+  // ---- deal (item, head group) units onto persistent workgroups: longest first, least-loaded queue ----
   // Workgroup q runs on XCD q % 8 (round-robin dispatch); when the head counts allow it, the units of one
   // KV head stay on a fixed set of XCDs so that each L2 holds the K/V of few KV heads.
-  const int64_t n_units = int64_t(p.items.size()) * g.Hq;
+  const int64_t n_units = int64_t(p.items.size()) * g.n_groups;
   p.n_queues = static_cast<int32_t>(std::min<int64_t>(std::max(1, n_cu), std::max<int64_t>(1, n_units)));
   const bool affinity = (p.n_queues % 8 == 0) && (g.Hkv % 8 == 0 || 8 % g.Hkv == 0);
-  std::vector<std::vector<int32_t>> queues(p.n_queues);  // flat (item, head) pairs
+  std::vector<std::vector<int32_t>> queues(p.n_queues);  // flat (item, group) pairs
   std::vector<int64_t> load(p.n_queues, 0);
   for (size_t it = 0; it < p.items.size(); ++it) {
-    for (int32_t h = 0; h < g.Hq; ++h) {
-      const int32_t kvh = h / g.G;
+    for (int32_t grp = 0; grp < g.n_groups; ++grp) {
+      const int32_t kvh = grp * g.Gs / g.G;
       int32_t best = -1;
       for (int32_t q = 0; q < p.n_queues; ++q) {
         if (affinity) {
@@ -139,8 +173,8 @@ void build_plan(purekv_plan& p, int n_cu) {
         if (best < 0 || load[q] < load[best]) best = q;
       }
       queues[best].push_back(static_cast<int32_t>(it));
-      queues[best].push_back(h);
-      load[best] += p.items[it].n_tiles + 3;
+      queues[best].push_back(grp);
+      load[best] += p.items[it].n_tiles + 2;
     }
   }
 
@@ -153,24 +187,31 @@ void build_plan(purekv_plan& p, int n_cu) {
   for (int32_t q = 0; q < p.n_queues; ++q) {
     for (size_t u = 0; u + 1 < queues[q].size(); u += 2) {
       const WorkItem& w = p.items[queues[q][u]];
-      const int32_t h = queues[q][u + 1], kvh = h / g.G;
+      const int32_t grp = queues[q][u + 1], head0 = grp * g.Gs, kvh = head0 / g.G;
       p.queue_units.push_back(queues[q][u]);
-      p.queue_units.push_back(h);
-      const int32_t uid = static_cast<int32_t>(p.units.size());
-      p.units.push_back({w.qtile, h, w.split, w.n_splits, w.slot, 0, 0, 0});
+      p.queue_units.push_back(head0);
+      Unit un{};
+      un.row0 = w.qtile * rows_per_qtile;
+      un.head0 = head0;
+      un.n_splits = w.n_splits;
+      un.ws_row0 = w.slot >= 0 ? (w.slot * g.n_groups + grp) * (kWaves * kBlockRows) : -1;
+      p.units.push_back(un);
       for (int32_t t = 0; t < w.n_tiles; ++t) {
         const TileRef& r = p.tiles[w.list_begin + t];
         StreamEntry e;
         e.kv_off = (uint32_t(kvh) * uint32_t(g.N) + uint32_t(r.tile) * BK) * row_bytes;
-        e.masks = uint32_t(r.need) | (uint32_t(r.full) << 8);
-        e.unit = (t == 0) ? uid : -1;
-        e.last = (t == w.n_tiles - 1) ? 1 : 0;
+        const int32_t k0 = r.tile * BK, rows = std::min(BK, g.N - k0);
+        e.need = r.need | ((t == w.n_tiles - 1) ? (1u << 16) : 0u) | ((t == 0) ? (1u << 17) : 0u) |
+                 (uint32_t(rows - 1) << 18);
+        e.kinds = r.kinds;
+        e.k0 = k0;
         p.stream.push_back(e);
       }
     }
     p.queue_begin.push_back(static_cast<int32_t>(p.stream.size()));
     p.queue_units_begin.push_back(static_cast<int32_t>(p.queue_units.size() / 2));
   }
+  p.units.push_back(Unit{});  // spare record: the kernel fetches the record after the current unit unconditionally
 }
 
 }  // namespace purekv

@@ -7,12 +7,21 @@
 
 namespace purekv {
 
-constexpr int kWaves = 8;        // wavefronts per prefill workgroup
-constexpr int kRowsPerWave = 32; // query rows per wavefront; PUREKV_BQ = kWaves * kRowsPerWave
+constexpr int kWaves = PUREKV_WAVES;        // wavefronts per prefill workgroup
+constexpr int kBlockRows = PUREKV_BLOCK;    // query rows per wavefront
+constexpr int kBlockKeys = PUREKV_BLOCK;    // keys per mask block: a key tile (PUREKV_BK keys) holds two
+
+// How the allowed pairs of one (row block, key block) pair are told apart from the others.
+enum BlockKind : uint32_t {
+  kKindFull = PUREKV_KIND_FULL,        // every pair allowed: no element mask
+  kKindCausal = PUREKV_KIND_CAUSAL,    // allowed  <=>  key <= query
+  kKindPrev = PUREKV_KIND_PREV,        // allowed  <=>  key == query - P (same patch, previous frame)
+  kKindGeneral = PUREKV_KIND_GENERAL,  // the full predicate of the pattern
+};
 
 // One unit of prefill work: a query tile and a contiguous slice of its key-tile list.
 struct WorkItem {
-  int32_t qtile;       // query rows [qtile*BQ, qtile*BQ + BQ)
+  int32_t qtile;       // query rows [qtile*rows_per_qtile, (qtile+1)*rows_per_qtile)
   int32_t list_begin;  // first position in the flat tile list
   int32_t n_tiles;     // tiles in this slice
   int32_t split;       // index of this slice within the query tile's list (0 = first)
@@ -28,24 +37,30 @@ struct MergeItem {
   int32_t pad;
 };
 
-// One (key tile, wave masks) reference of a query tile's list.
+// One key tile of a query tile's list.  Bit 2*rb + kb of `need`: row block rb of the query tile has an allowed
+// pair among keys [tile*BK + 32*kb, +32).  Bits 4*rb + 2*kb, +1 of `kinds`: the BlockKind of that pair of blocks.
 struct TileRef {
-  int32_t tile;        // key tile index (keys [tile*BK, tile*BK + BK))
-  uint16_t need;       // bit w: wavefront w (rows 32w..32w+31 of the query tile) has an allowed pair in this tile
-  uint16_t full;       // bit w: every pair of wavefront w's rows with this tile's keys is allowed
+  int32_t tile;
+  uint32_t need;
+  uint32_t kinds;
 };
 
-// One step of a persistent workgroup's stream: stage this key tile, compute it for the wavefronts that need it.
+// One step of a persistent workgroup's stream: stage this key tile, compute it for the row blocks that need it.
 struct StreamEntry {
   uint32_t kv_off;     // byte offset of the tile's first row within the K (and V) tensor: (kvh*N + k0)*d*2
-  uint32_t masks;      // need | full << 8
-  int32_t unit;        // index into the unit table when this is the first step of a unit, else -1
-  int32_t last;        // 1 when this is the last step of its unit
+  uint32_t need;       // TileRef::need | last << 16 | first << 17 | (rows - 1) << 18: last / first step of its
+                       // unit (units are numbered in stream order); rows = keys of the tile that exist (1..64)
+  uint32_t kinds;      // TileRef::kinds
+  int32_t k0;          // first key of the tile
 };
 
-// A unit = work item x query head, run by one workgroup from its first to its last stream entry.
+// A unit = work item x group of stacked query heads, run by one workgroup from its first to its last stream entry.
 struct Unit {
-  int32_t qtile, head, split, n_splits, slot, k0_first, pad0, pad1;
+  int32_t row0;        // first query row of the tile
+  int32_t head0;       // first query head of the group (the group shares one KV head)
+  int32_t n_splits;    // 1: the unit writes the output; > 1: it writes a partial result
+  int32_t ws_row0;     // first row of the unit's partial result in the workspace (PUREKV_WAVES*32 rows), or -1
+  int32_t pad[4];
 };
 
 struct Geometry {
@@ -53,6 +68,9 @@ struct Geometry {
   int32_t Hq, Hkv, G, d;
   uint32_t pattern;
   float scale;
+  // Workgroup shape: Gs query heads of one KV group x R row blocks of 32 rows, one wavefront each
+  // (wavefront w: row block w / Gs, head w % Gs); Gs * R <= PUREKV_WAVES.
+  int32_t Gs, R, n_groups;   // n_groups = Hq / Gs
 };
 
 }  // namespace purekv
@@ -64,26 +82,28 @@ struct purekv_plan {
   std::vector<purekv::TileRef> tiles;
   std::vector<purekv::WorkItem> items;     // longest first
   std::vector<purekv::MergeItem> merges;
-  std::vector<purekv::Unit> units;
+  std::vector<purekv::Unit> units;         // in stream order, plus one spare record at the end
   std::vector<purekv::StreamEntry> stream; // all queues, back to back
   std::vector<int32_t> queue_begin;        // [n_queues + 1] offsets into stream
-  std::vector<int32_t> queue_units;        // (item, head) pairs per queue, for inspection
+  std::vector<int32_t> queue_units;        // (item, first head) pairs per queue, for inspection
   std::vector<int32_t> queue_units_begin;  // [n_queues + 1] offsets into queue_units (in pairs)
   int32_t n_queues = 0;
   int32_t n_slots = 0;
-  int64_t n_full_wave_tiles = 0;           // (tile, wavefront) pairs flagged full
-  int64_t n_wave_tiles = 0;                // (tile, wavefront) pairs computed, per query head
+  int64_t n_blocks = 0;                    // (row block, key block) pairs computed, per query head
+  int64_t n_kind[4] = {0, 0, 0, 0};        // of those, per BlockKind
   double mask_pairs = 0;                   // allowed (query, key) pairs per head
   // device copies (null for host-only plans)
   purekv::StreamEntry* d_stream = nullptr;
   purekv::Unit* d_units = nullptr;
   int32_t* d_queue_begin = nullptr;
+  int32_t* d_queue_unit0 = nullptr;        // [n_queues + 1] first unit of each queue
   purekv::MergeItem* d_merges = nullptr;
   int device = -1;
   int n_cu = 256;
 };
 
 namespace purekv {
-// Fills every host field of `p` from p.g; `n_cu` = number of persistent workgroups (one per compute unit).
+// Fills every host field of `p` from p.g (all but Gs, R, n_groups, which it chooses); `n_cu` = number of
+// persistent workgroups (one per compute unit).
 void build_plan(purekv_plan& p, int n_cu);
 }  // namespace purekv

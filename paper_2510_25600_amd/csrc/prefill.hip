@@ -1,12 +1,18 @@
 // ST-SpAttn / dense causal prefill attention for gfx950 (Sec. 3.2; Eq. 1 for the dense pattern).
 //
 // A persistent workgroup of 8 wavefronts walks a host-planned stream of 64-key tiles.  Each wavefront owns 32
-// query rows of one head.  Scores are formed transposed, S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so that a
-// lane holds 16 keys of ONE query: the softmax row maximum is an in-lane reduction plus one exchange between
-// the two halves of the wavefront, and the probabilities leave the accumulator already in the register layout
-// that the second product O^T = V^T P^T takes as its B operand.  K tiles sit in LDS row-major, V tiles
-// transposed (the contraction index of the second product is the key), both XOR-swizzled in 16-byte units so
-// the 128-bit operand reads are conflict-free.  The attention matrix never exists.
+// query rows of one head; the workgroup stacks Gs heads of one KV group x R row blocks (the mask depends on
+// the row only, so stacked heads need the same tiles and nobody idles at the tile barriers).  Scores are
+// formed transposed, S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so that a lane holds 16 keys of ONE query: the
+// softmax row maximum is an in-lane reduction plus one exchange between the two halves of the wavefront, and
+// the probabilities leave the accumulator already in the register layout that the second product
+// O^T = V^T P^T takes as its B operand.  The attention matrix never exists.
+//
+// K and V tiles sit in LDS row-major, XOR-swizzled in 16-byte units, and get there straight from global memory
+// (16-byte loads whose destination is LDS: no staging registers, no vector ALU work, no LDS write instructions).
+// K fragments are 128-bit LDS reads.  The second product contracts over the key, which runs ACROSS the rows of
+// a row-major V tile: its fragments come from the LDS transpose read (ds_read_b64_tr_b16), which hands each
+// lane 4 consecutive keys of one column.
 //
 // The softmax denominator is the sum of the bf16-ROUNDED probabilities, i.e. exactly the weights the second
 // product applies, so each output row is a true convex combination of V rows.  It comes from the matrix pipe
@@ -14,20 +20,21 @@
 //
 // Two-phase schedule.  Wavefronts w and w+4 share a SIMD.  A step of a wavefront is a matrix phase (second
 // product of the previous tile, score product of this tile) and a vector phase (mask, maximum, exponentials,
-// K/V staging), separated by workgroup barriers.  Wavefronts 4-7 run one phase behind wavefronts 0-3, so on
-// every SIMD one wavefront is in its matrix phase while the other is in its vector phase and the two pipes
-// overlap without relying on instruction scheduling inside a wavefront.
+// issue of the K/V loads), separated by workgroup barriers.  Wavefronts 4-7 run one phase behind wavefronts
+// 0-3, so on every SIMD one wavefront is in its matrix phase while the other is in its vector phase and the
+// two pipes overlap without relying on instruction scheduling inside a wavefront.
 //
-// K/V tiles travel HBM -> registers (bounds-checked buffer loads: rows past the end read as zero, a tile index
-// past the list reads nothing) -> LDS, through rings of three K and three V buffers: while tile t is multiplied,
-// wavefronts 0-3 write their share of tile t+1 and wavefronts 4-7 (one phase later) theirs of tile t+2.
+// K and V each rotate through three LDS buffers.  In the vector phase of its step t a leading wavefront starts
+// the loads of its rows of K tile t+2 and V tile t+1, a lagging wavefront (one phase later) those of K tile t+2
+// and V tile t+2: each targets a buffer whose last reader finished at least one barrier earlier, and every load
+// is waited for at the end of the issuing wavefront's next matrix phase, two barriers before its first reader.
 #include "common.h"
 
 namespace purekv {
 namespace {
 
-constexpr int BQ = PUREKV_BQ;
 constexpr int BK = PUREKV_BK;
+constexpr int WG_ROWS = PUREKV_WAVES * PUREKV_BLOCK;   // rows of one workgroup's partial result
 constexpr float kRescaleGap = 8.0f;
 
 struct PrefillArgs {
@@ -36,13 +43,15 @@ struct PrefillArgs {
   const uint16_t* v;
   uint16_t* out;
   float* lse;
-  float* ws_o;    // [n_slots, Hq, BQ, D] normalised partial outputs
-  float* ws_lse;  // [n_slots, Hq, BQ, 2] log2-domain log-sum-exp of the partial: {merge weight, exact}
+  float* ws_o;    // [n_slots, n_groups, WG_ROWS, D] normalised partial outputs
+  float* ws_lse;  // [n_slots, n_groups, WG_ROWS, 2] log2-domain log-sum-exp of the partial: {merge weight, exact}
   const StreamEntry* stream;
   const Unit* units;
-  const int32_t* queue_begin;
+  const int32_t* queue_begin;   // [n_queues + 1] offsets into stream
+  const int32_t* queue_unit0;   // [n_queues + 1] first unit of each queue (units are numbered in stream order)
   const MergeItem* merges;
   int32_t N, Nv, P, Hq, Hkv;
+  int32_t Gs, R, n_groups;   // workgroup shape: wavefront w -> row block w / Gs, head w % Gs
   uint32_t pattern;
   float scale_log2;  // softmax scale * log2(e)
 #ifdef PUREKV_PHASE_TRACE
@@ -58,116 +67,139 @@ struct PrefillArgs {
 #define PHASE_MARK(i)
 #endif
 
-// Element offset of 16-byte slot `u` of row `r` in a row-major bf16 LDS tile with ROW elements per row.
-// The slot index is XOR-ed with the row so that the 16 lanes the LDS serves together (rows that differ
-// in their low four bits) fall into 16 different 16-byte slots of a 256-byte bank period.
-template <int ROW>
-__device__ __forceinline__ int swz(int r, int u) {
-  if constexpr (ROW == 128) {
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) shortx4* LdsShortx4;
+typedef __attribute__((address_space(3))) void* LdsPtr;
+typedef const __attribute__((address_space(1))) void* GlobalPtr;
+
+// K tile [BK][D] bf16 in LDS: element offset of 16-byte slot `u` of row `r`.  The slot index is XOR-ed with the
+// row so that the 16 lanes the LDS serves together (rows that differ in their low four bits) fall into 16
+// different 16-byte slots of a 256-byte bank period.
+template <int D>
+__device__ __forceinline__ int kswz(int r, int u) {
+  if constexpr (D == 128) {
     return r * 128 + ((u ^ (r & 15)) * 8);
   } else {  // 64 elements = 128 bytes: two rows share one 256-byte period
     return (r >> 1) * 128 + ((((r & 1) * 8 + u) ^ ((r >> 1) & 15)) * 8);
   }
 }
-
-// Raw buffer descriptor over `bytes` bytes at `p`: loads past the end return zero instead of faulting.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+// Inverse: 16-byte position p of the tile -> (row, slot) stored there.
+template <int D>
+__device__ __forceinline__ void kunswz(int p, int& r, int& u) {
+  if constexpr (D == 128) {
+    r = p >> 4;
+    u = (p & 15) ^ (r & 15);
+  } else {
+    const int rr = p >> 4, y = (p & 15) ^ (rr & 15);
+    r = 2 * rr + (y >> 3);
+    u = y & 7;
+  }
 }
-__device__ __forceinline__ u32x4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
-  return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
+// V tile [BK][D] bf16 in LDS, row-major; the transpose read of a 16-lane group touches 4 consecutive rows x 32
+// bytes, two such groups run side by side: XOR-ing the 32-byte pair index with the row's low bits keeps them on
+// distinct banks.
+template <int D>
+__device__ __forceinline__ int vswz(int r, int u) {
+  return r * D + ((u ^ ((r & (D / 32 - 1)) << 2)) * 8);
+}
+template <int D>
+__device__ __forceinline__ void vunswz(int p, int& r, int& u) {
+  constexpr int CPR = D / 8;
+  r = p / CPR;
+  u = (p % CPR) ^ ((r & (D / 32 - 1)) << 2);
 }
 
-// ST  = false: dense causal pattern only (no frame arithmetic); true: any pattern.
+// Wave-uniform, read-only tables are fetched through the scalar cache (constant address space).
+typedef const u32x4 __attribute__((address_space(4))) * ConstQuads;
+
+// Stream entry as the kernel uses it.
+struct Step {
+  uint32_t kv_off;   // byte offset of the tile in K and V
+  uint32_t need;     // need bits | last << 16 | first << 17 | (valid rows - 1) << 18
+  uint32_t kinds;
+  int32_t k0;        // first key of the tile
+};
+
+// ST  = false: dense causal pattern only (block kinds full and causal); true: any pattern.
 // LSE = true : also keeps the exact fp32 row sum for the log-sum-exp output.
 //
 // Persistent kernel: workgroup q walks stream[queue_begin[q] .. queue_begin[q+1]).  Every stream entry is one
-// key tile: all wavefronts stage it, the wavefronts whose `need` bit is set multiply it.  Units (query tile
-// slice x head) follow each other in the stream without draining the K/V pipeline.
+// key tile: all wavefronts load it, the wavefronts whose row block needs it multiply the 32-key halves they
+// need.  Units (query tile slice x head group) follow each other in the stream without draining the K/V
+// pipeline; the query rows of the next unit are fetched while the last tile of the current one is finished.
 template <int D, bool ST, bool LSE>
 __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   constexpr int KSTEPS = D / 16;        // MFMA k-steps of the score product
   constexpr int DBLK = D / 32;          // 32-row blocks of O^T
   constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
-  constexpr int KCH = BK * CPR / 512;   // K chunks staged per thread
+  constexpr int NLD = BK * CPR / 512;   // 16-byte loads per thread and tile, for K and for V
   constexpr int NBUF = 3;
+  static_assert(sizeof(StreamEntry) == 16 && sizeof(Unit) == 32, "tables are read as 16-byte quads");
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   uint16_t* const Ks_base = smem;                     // NBUF x [BK][D]
-  uint16_t* const Vt_base = smem + NBUF * BK * D;     // NBUF x [D][BK]
+  uint16_t* const Vs_base = smem + NBUF * BK * D;     // NBUF x [BK][D]
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = wave >> 2;            // 0: leading wavefronts, 1: the ones that run one phase behind
   const int n = lane & 31, h = lane >> 5;
+  const int rb = wave / a.Gs, hl = wave - rb * a.Gs;   // row block and stacked head of this wavefront
+  const bool active = wave < a.Gs * a.R;
   const int t_begin = a.queue_begin[blockIdx.x], t_end = a.queue_begin[blockIdx.x + 1];
   if (t_begin >= t_end) return;
 
-  const uint32_t kv_bytes = (uint32_t)a.Hkv * (uint32_t)a.N * D * 2u;
-  const __amdgpu_buffer_rsrc_t krs = make_rsrc(a.k, kv_bytes), vrs = make_rsrc(a.v, kv_bytes);
-
-  // ---- staging maps (per-thread constants) ----
-  // K: chunk id = tid + 512 r -> (row id / CPR, 16-byte chunk id % CPR): a row is read by CPR neighbouring lanes.
-  // V: the first 16*CPR threads (all in wavefronts 0-3) own 4 consecutive keys (quad vg) x 8 consecutive d
-  //    (chunk vc) each; 4 neighbouring lanes read 64 contiguous bytes of one row.  Quad vg holds keys
-  //    16*grp + 8*aa + 4*hh + 0..3; the MFMA k-order wants, per 16 keys, [hh=0: aa=0, aa=1 | hh=1: aa=0, aa=1],
-  //    i.e. 16-byte unit 2*grp + hh, 8-byte half aa.
-  const int vcl = tid & 3, vg = (tid >> 2) & 15, vc = (tid >> 6) * 4 + vcl;
-  const bool v_active = vc < CPR;
-  const int v_unit = 2 * (vg >> 2) + (vg & 1), v_half = (vg >> 1) & 1;
-  uint32_t k_goff[KCH], v_goff[4];
-  int k_loff[KCH];
+  // ---- load maps (per-thread constants) ----
+  // Load i of this wavefront fills 16-byte positions (NLD*wave + i)*64 + lane of a tile: 1 KB of LDS, contiguous
+  // (the hardware writes lane l's 16 bytes at base + 16 l); which (row, slot) of the global tile a lane fetches
+  // follows from the swizzle of that position.  Rows past the end of the sequence re-read the last valid row
+  // (their scores are masked, their probabilities zero).
+  int k_row[NLD], v_row[NLD];
+  uint32_t k_col[NLD], v_col[NLD];   // byte offset within the row
 #pragma unroll
-  for (int r = 0; r < KCH; ++r) {
-    const int id = tid + 512 * r, rk = id / CPR, cc = id % CPR;
-    k_goff[r] = (uint32_t)(rk * D + cc * 8) * 2u;
-    k_loff[r] = swz<D>(rk, cc);
+  for (int i = 0; i < NLD; ++i) {
+    const int p = (NLD * wave + i) * 64 + lane;
+    int r, u;
+    kunswz<D>(p, r, u);
+    k_row[i] = r;
+    k_col[i] = (uint32_t)u * 16u;
+    vunswz<D>(p, r, u);
+    v_row[i] = r;
+    v_col[i] = (uint32_t)u * 16u;
   }
+  const char* const k_bytes = reinterpret_cast<const char*>(a.k);
+  const char* const v_bytes = reinterpret_cast<const char*>(a.v);
+  auto issue_k = [&](const Step& s, int buf) {
+    const int rv = (int)((s.need >> 18) & 63u);
 #pragma unroll
-  for (int jj = 0; jj < 4; ++jj)
-    v_goff[jj] = v_active ? (uint32_t)((4 * vg + jj) * D + vc * 8) * 2u : kv_bytes;  // idle threads read nothing
-  u32x4 kreg[KCH], vreg[4];
-
-  // An offset at or past the end of the tensor reads zeros and touches no memory.
-  auto load_tile = [&](uint32_t base) {
-#pragma unroll
-    for (int r = 0; r < KCH; ++r) kreg[r] = buffer_load16(krs, base + k_goff[r]);
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) vreg[jj] = buffer_load16(vrs, base + v_goff[jj]);
-  };
-  auto store_tile = [&](int buf) {
-    uint16_t* Ks = Ks_base + buf * (BK * D);
-    uint16_t* Vt = Vt_base + buf * (D * BK);
-#pragma unroll
-    for (int r = 0; r < KCH; ++r) *reinterpret_cast<u32x4*>(Ks + k_loff[r]) = kreg[r];
-    if (v_active) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int dd = 8 * vc + e;
-        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;  // high / low halves of two dwords
-        u32x2 w;
-        w[0] = __builtin_amdgcn_perm(vreg[1][e >> 1], vreg[0][e >> 1], sel);
-        w[1] = __builtin_amdgcn_perm(vreg[3][e >> 1], vreg[2][e >> 1], sel);
-        *reinterpret_cast<u32x2*>(Vt + swz<BK>(dd, v_unit) + v_half * 4) = w;
-      }
+    for (int i = 0; i < NLD; ++i) {
+      const uint32_t off = s.kv_off + (uint32_t)min(k_row[i], rv) * (D * 2u) + k_col[i];
+      __builtin_amdgcn_global_load_lds((GlobalPtr)(k_bytes + off),
+                                       (LdsPtr)(Ks_base + buf * (BK * D) + (NLD * wave + i) * 512), 16, 0, 0);
     }
   };
-  // Stream entries are wave-uniform and read-only: fetch them through the scalar cache (constant address space),
-  // one step before they are used, so that no phase waits for a global load.
-  static_assert(sizeof(StreamEntry) == 16, "a stream entry is read as four dwords");
-  typedef const u32x4 __attribute__((address_space(4))) * ConstStream;
-  const ConstStream stream_c = (ConstStream)(uintptr_t)a.stream;
-  auto stream_entry = [&](int t) {
-    const u32x4 w = stream_c[t];
-    StreamEntry e;
-    e.kv_off = w[0];
-    e.masks = w[1];
-    e.unit = (int32_t)w[2];
-    e.last = (int32_t)w[3];
-    return e;
+  auto issue_v = [&](const Step& s, int buf) {
+    const int rv = (int)((s.need >> 18) & 63u);
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const uint32_t off = s.kv_off + (uint32_t)min(v_row[i], rv) * (D * 2u) + v_col[i];
+      __builtin_amdgcn_global_load_lds((GlobalPtr)(v_bytes + off),
+                                       (LdsPtr)(Vs_base + buf * (BK * D) + (NLD * wave + i) * 512), 16, 0, 0);
+    }
   };
-  auto tile_off = [&](int t) {
-    const uint32_t off = stream_c[min(t, t_end - 1)][0];
-    return t < t_end ? off : kv_bytes;
+  // All loads of this wavefront have written LDS (vmcnt == 0; the other counters are left alone).
+  auto wait_loads = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };
+
+  // Stream entries and unit records: fetched before they are needed, so that no phase waits for a global load.
+  const ConstQuads stream_c = (ConstQuads)(uintptr_t)a.stream;
+  const ConstQuads units_c = (ConstQuads)(uintptr_t)a.units;
+  auto fetch_step = [&](int t) {   // entries past the end repeat the last one; their loads are skipped
+    const u32x4 w = stream_c[min(t, t_end - 1)];
+    Step s;
+    s.kv_off = w[0];
+    s.need = w[1];
+    s.kinds = w[2];
+    s.k0 = (int32_t)w[3];
+    return s;
   };
   auto next_buf = [](int b) { return b == NBUF - 1 ? 0 : b + 1; };
   // Barrier between phases; the scheduling fences keep the matrix work of a phase on its side.
@@ -179,7 +211,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 
   // ---- per-unit state ----
   int hq = 0, row = 0, rowc = 0, a_i = 0, lo_i = 0, prev_j = -1, self_j = -1;
-  int u_nsplits = 1, u_slot = -1;
+  int u_nsplits = 1, u_ws_row0 = -1;
   bf16x8 qf[KSTEPS];
   // m: reference maximum (log2 units); lacc: every element holds the sum of the bf16-rounded probabilities of
   // query n (accumulated by the matrix pipe against an all-ones operand); lx: exact fp32 sum (LSE only).
@@ -189,12 +221,21 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) ones8[i] = (__bf16)1.0f;
 
-  auto begin_unit = [&](int uid) {
-    const Unit u = a.units[uid];
-    hq = u.head;
-    u_nsplits = u.n_splits;
-    u_slot = u.slot;
-    row = u.qtile * BQ + wave * 32 + n;
+  // Unit record {row0, head0, n_splits, ws_row0}: start fetching this wavefront's 32 query rows.  The fragment
+  // registers are free from the last score product of a unit to the first of the next.
+  auto prefetch_q = [&](const u32x4 un) {
+    if (active) {
+      const int r = min((int)un[0] + rb * 32 + n, a.N - 1);
+      const uint16_t* qrow = a.q + ((size_t)((int)un[1] + hl) * a.N + r) * D;
+#pragma unroll
+      for (int s = 0; s < KSTEPS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s + 8 * h);
+    }
+  };
+  auto begin_unit = [&](const u32x4 un) {
+    hq = (int)un[1] + hl;
+    u_nsplits = (int)un[2];
+    u_ws_row0 = (int)un[3];
+    row = (int)un[0] + rb * 32 + n;
     rowc = min(row, a.N - 1);
     // allowed keys of this lane's row: j <= rowc and (j <= a_i or j >= lo_i or j == prev_j or j == self_j)
     const bool sparse_row = ST && a.pattern != 0u && rowc < a.Nv;
@@ -203,9 +244,6 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     lo_i = sparse_row ? ((a.pattern & 1u) ? frame * a.P : rowc + 1) : 0;
     prev_j = (sparse_row && (a.pattern & 2u) && frame >= 1) ? rowc - a.P : -1;
     self_j = (sparse_row && (a.pattern & 2u)) ? rowc : -1;
-    const uint16_t* qrow = a.q + ((size_t)hq * a.N + rowc) * D;
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s + 8 * h);
     m = -INFINITY;
     lx = 0.f;
 #pragma unroll
@@ -218,6 +256,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 
   // Normalise and write this wavefront's 32 rows of the unit that just finished.
   auto finish_unit = [&]() {
+    if (!active) return;
     const float l_tot = lacc[0];
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     const float lse2 = m + __builtin_amdgcn_logf(l_tot);  // log2 domain; -inf when the slice saw no key
@@ -237,7 +276,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
         if (LSE && h == 0) a.lse[(size_t)hq * a.N + row] = lse2x * kLn2;
       }
     } else {
-      const size_t prow = ((size_t)u_slot * a.Hq + hq) * BQ + wave * 32 + n;
+      const size_t prow = (size_t)u_ws_row0 + wave * 32 + n;
       float* orow = a.ws_o + prow * D;
 #pragma unroll
       for (int b = 0; b < DBLK; ++b)
@@ -257,35 +296,42 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 
   // Operand fragments are read from LDS two MFMAs ahead of their use (ring of three registers); the scheduling
   // fences keep that order, so each wait covers only the oldest read.
-  // S^T = K Q^T: two 32-key blocks x 32 queries
-  auto qk_tile = [&](int buf, floatx16 (&sacc)[2]) {
-    const uint16_t* Ks = Ks_base + buf * (BK * D);
-    constexpr int NF = 2 * KSTEPS;
-    auto rd = [&](int i) {   // fragment i: k-step i/2 of key block i%2
-      return *reinterpret_cast<const bf16x8*>(Ks + swz<D>(32 * (i & 1) + n, 2 * (i >> 1) + h));
-    };
+  // Scores of one 32-key half: S^T[32 keys, 32 queries] = K Q^T; Kh = first row of the half in its LDS tile.
+  auto qk_half = [&](const uint16_t* Kh, floatx16& s) {
+    auto rd = [&](int i) { return *reinterpret_cast<const bf16x8*>(Kh + kswz<D>(n, 2 * i + h)); };
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
     bf16x8 f[3];
     f[0] = rd(0);
     f[1] = rd(1);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < NF; ++i) {
-      if (i + 2 < NF) f[(i + 2) % 3] = rd(i + 2);
-      sacc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % 3], qf[i >> 1], sacc[i & 1], 0, 0, 0);
+    for (int i = 0; i < KSTEPS; ++i) {
+      if (i + 2 < KSTEPS) f[(i + 2) % 3] = rd(i + 2);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % 3], qf[i], s, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  // O^T += V^T P^T, row sums += 1 P^T
+  // O^T += V^T P^T and row sums += 1 P^T over the four 16-key steps of a tile (a half the row block does not
+  // need carries zero probabilities).
+  // A operand of step ks, output block b: lane (d = 32 b + n, key group h) needs keys 16 ks + 4 h + {0..3} and
+  // 16 ks + 8 + 4 h + {0..3} of column d, in that order (the order the probabilities have in the B operand).
+  // One transpose read gives the lanes of a 16-lane group 4 consecutive rows of 16 consecutive columns: lane s
+  // of the group supplies the address of row (s / 4), columns 4 (s % 4) .. +3, and lane j receives column j.
+  const int tr_row = 4 * h + ((lane & 15) >> 2);                 // row within a 16-key step, first read
+  const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);    // column within a 32-column block
+  int v_off[DBLK];
+#pragma unroll
+  for (int b = 0; b < DBLK; ++b) v_off[b] = vswz<D>(tr_row, (32 * b + tr_col) >> 3) + (tr_col & 7);
   auto pv_tile = [&](int buf, const bf16x8 (&pf)[4]) {
-    const uint16_t* Vt = Vt_base + buf * (D * BK);
+    const uint16_t* Vs = Vs_base + buf * (BK * D);
     constexpr int NF = 4 * DBLK;
-    auto rd = [&](int i) {   // fragment i: 16-key step i%4 of output block i/4
-      return *reinterpret_cast<const bf16x8*>(Vt + swz<BK>(32 * (i >> 2) + n, 2 * (i & 3) + h));
+    auto rd = [&](int i) {   // fragment i: 16-key step i % 4 of output block i / 4
+      const uint16_t* p = Vs + v_off[i >> 2] + 16 * (i & 3) * D;   // rows 16 ks + .. : the swizzle ignores them
+      const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsShortx4)p);
+      const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsShortx4)(p + 8 * D));
+      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
     bf16x8 f[3];
     f[0] = rd(0);
@@ -302,26 +348,63 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     }
   };
 
-  // Mask, running maximum, exponentials: scores of one tile -> bf16 B-operand fragments; pf[ks] covers keys
-  // 16*ks .. 16*ks+15 of the tile.
-  auto softmax_tile = [&](floatx16 (&sacc)[2], bf16x8 (&pf)[4], int k0, bool full) {
-    // element mask (tiles not flagged full for this wavefront: one uniform branch, selects inside)
-    if (!full) {
+  // Element mask of one 32-key block whose first key is `kbase`; element i of the accumulator is key
+  // kbase + 4h + 8 (i / 4) + i % 4 of this lane's query.  One uniform branch per block, selects inside.
+  auto mask_block = [&](floatx16& s, uint32_t kind, int kbase) {
+    if (kind == kKindFull) return;
+    const int jb = kbase + 4 * h;
+    if (!ST || kind == kKindCausal) {
+      const int thr = rowc - jb;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int i = 0; i < 16; ++i) s[i] = (8 * (i >> 2) + (i & 3) <= thr) ? s[i] : -INFINITY;
+    } else if (kind == kKindPrev) {
+      const int eq = prev_j - jb;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int j = k0 + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
-          const bool ok = ST ? ((j <= rowc) & ((j <= a_i) | (j >= lo_i) | (j == prev_j) | (j == self_j)))
-                             : (j <= rowc);
-          sacc[kb][i] = ok ? sacc[kb][i] : -INFINITY;
-        }
+      for (int i = 0; i < 16; ++i) s[i] = (8 * (i >> 2) + (i & 3) == eq) ? s[i] : -INFINITY;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int j = jb + 8 * (i >> 2) + (i & 3);
+        const bool ok = (j <= rowc) & ((j <= a_i) | (j >= lo_i) | (j == prev_j) | (j == self_j));
+        s[i] = ok ? s[i] : -INFINITY;
+      }
     }
+  };
+  auto max_block = [&](const floatx16& s, float mt) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mt = fmaxf(mt, s[i]);
+    return mt;
+  };
+  // Probabilities of one block -> two bf16 B-operand fragments (16 keys each).
+  auto exp_block = [&](const floatx16& s, float neg_m, bf16x8& p0, bf16x8& p1) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      u32x4 pk;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * half + 2 * w], a.scale_log2, neg_m));
+        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * half + 2 * w + 1], a.scale_log2, neg_m));
+        if (LSE) lx += e0 + e1;
+        pk[w] = pack_bf16(e0, e1);
+      }
+      if (half == 0)
+        p0 = __builtin_bit_cast(bf16x8, pk);
+      else
+        p1 = __builtin_bit_cast(bf16x8, pk);
+    }
+  };
+  // Mask, running maximum, exponentials of the needed halves (bits nb) of one tile; pf[ks] covers keys
+  // 16*ks .. 16*ks+15 of the tile.
+  auto softmax_tile = [&](floatx16 (&sacc)[2], bf16x8 (&pf)[4], uint32_t nb, uint32_t kinds, int k0) {
     float mt = -INFINITY;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sacc[kb][i]);
+    if (nb & 1u) {
+      mask_block(sacc[0], kinds & 3u, k0);
+      mt = max_block(sacc[0], mt);
+    }
+    if (nb & 2u) {
+      mask_block(sacc[1], (kinds >> 2) & 3u, k0 + 32);
+      mt = max_block(sacc[1], mt);
+    }
     mt = fmaxf(mt, other_half(mt)) * a.scale_log2;
     // The reference maximum m only moves when a tile exceeds it by more than kRescaleGap (log2 units):
     // probabilities then stay below 2^kRescaleGap, exact in fp32/bf16 range, and the accumulators are
@@ -339,96 +422,109 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
       m = m_new;
     }
     const float neg_m = (m == -INFINITY) ? 0.f : -m;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        u32x4 pk;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * half + 2 * w], a.scale_log2, neg_m));
-          const float p1 =
-              __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * half + 2 * w + 1], a.scale_log2, neg_m));
-          if (LSE) lx += p0 + p1;
-          pk[w] = pack_bf16(p0, p1);
-        }
-        pf[2 * kb + half] = __builtin_bit_cast(bf16x8, pk);
-      }
+    const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+    if (nb & 1u)
+      exp_block(sacc[0], neg_m, pf[0], pf[1]);
+    else
+      pf[0] = pf[1] = zero8;
+    if (nb & 2u)
+      exp_block(sacc[1], neg_m, pf[2], pf[3]);
+    else
+      pf[2] = pf[3] = zero8;
   };
 
-  // ---- pipeline fill: tile 0 complete in LDS, the lagging wavefronts' share of tile 1 too ----
-  load_tile(tile_off(t_begin));
-  store_tile(0);
-  load_tile(tile_off(t_begin + 1));
-  if (grp == 1) {
-    store_tile(1);
-    load_tile(tile_off(t_begin + 2));
+  // ---- pipeline fill: K tiles 0 and 1 and V tile 0 complete in LDS, the lagging wavefronts' rows of V tile 1 ----
+  Step st0 = fetch_step(t_begin), st1 = fetch_step(t_begin + 1), st2 = fetch_step(t_begin + 2);
+  int unit_id = a.queue_unit0[blockIdx.x];
+  u32x4 un_next = units_c[2 * unit_id];   // the first entry of a queue always starts a unit
+  prefetch_q(un_next);
+  issue_k(st0, 0);
+  issue_v(st0, 0);
+  if (t_begin + 1 < t_end) {
+    issue_k(st1, 1);
+    if (grp == 1) issue_v(st1, 1);
   }
+  wait_loads();
   __syncthreads();
   if (grp == 1) phase_barrier();   // run one phase behind wavefronts 0-3
 
   int buf = 0;                     // LDS buffer of tile t
   int pv_buf = 0;
-  bool pv_pending = false, fin_pending = false;
+  uint32_t pv_bits = 0;            // halves of the previous tile whose probabilities wait for the second product
+  bool fin_pending = false;
   bf16x8 pf[4];
   floatx16 sacc[2];
 
-  StreamEntry ent = stream_entry(t_begin);
-  uint32_t off_stage = tile_off(t_begin + 2 + grp);   // tile whose loads start in this step's vector phase
   for (int t = t_begin; t < t_end; ++t) {
-    const StreamEntry ent_next = stream_entry(min(t + 1, t_end - 1));
-    const uint32_t off_stage_next = tile_off(t + 3 + grp);
-    const bool need = (ent.masks >> wave) & 1u;
-    const bool full = (ent.masks >> (8 + wave)) & 1u;
+    const Step st3 = fetch_step(t + 3);
+    const u32x4 un_fetch = units_c[2 * (unit_id + 1)];   // the unit table ends with a spare record
+    const uint32_t nb = active ? (st0.need >> (2 * rb)) & 3u : 0u;
+    const uint32_t kinds = (st0.kinds >> (4 * rb)) & 15u;
+    const bool last = (st0.need >> 16) & 1u, first = (st0.need >> 17) & 1u;
 
     // ---- matrix phase: second product of the previous tile, unit switch, score product of this tile ----
     PHASE_MARK(0);
-    if (pv_pending) pv_tile(pv_buf, pf);
+    if (pv_bits) pv_tile(pv_buf, pf);
     PHASE_MARK(4);
     if (fin_pending) finish_unit();
-    if (ent.unit >= 0) begin_unit(ent.unit);
-    if (need) qk_tile(buf, sacc);
+    if (first) begin_unit(un_next);
+    {
+      const uint16_t* Ks = Ks_base + buf * (BK * D);
+      if (nb & 1u) qk_half(Ks, sacc[0]);
+      if (nb & 2u) qk_half(Ks + 32 * D, sacc[1]);
+    }
+    wait_loads();   // the loads this wavefront issued in its last vector phase have landed
     PHASE_MARK(1);
     phase_barrier();
     PHASE_MARK(2);
 
-    // ---- vector phase: stage this wavefront's share of tile t+1+grp, start loading t+2+grp; softmax ----
-    const int b1 = next_buf(buf);
-    store_tile(grp ? next_buf(b1) : b1);
-    load_tile(off_stage);
-    PHASE_MARK(5);
-    if (need) {
-      const int k0 = (int)((ent.kv_off / (D * 2u)) % (uint32_t)a.N);  // first key of the tile within its head
-      softmax_tile(sacc, pf, k0, full);
+    // ---- vector phase: start the loads of this wavefront's rows of the coming tiles; softmax ----
+    const int b1 = next_buf(buf), b2 = next_buf(b1);
+    if (t + 2 < t_end) issue_k(st2, b2);
+    if (grp == 0) {
+      if (t + 1 < t_end) issue_v(st1, b1);
+    } else {
+      if (t + 2 < t_end) issue_v(st2, b2);
     }
-    pv_pending = need;
+    if (last && t + 1 < t_end) {   // the next entry starts a unit: its query rows travel while this one is finished
+      un_next = un_fetch;
+      ++unit_id;
+      prefetch_q(un_next);
+    }
+    PHASE_MARK(5);
+    if (nb) softmax_tile(sacc, pf, nb, kinds, st0.k0);
+    pv_bits = nb;
     pv_buf = buf;
-    fin_pending = ent.last != 0;
+    fin_pending = last;
     buf = b1;
-    ent = ent_next;
-    off_stage = off_stage_next;
+    st0 = st1;
+    st1 = st2;
+    st2 = st3;
     PHASE_MARK(3);
     phase_barrier();
   }
-  if (pv_pending) pv_tile(pv_buf, pf);
+  if (pv_bits) pv_tile(pv_buf, pf);
   if (fin_pending) finish_unit();
   if (grp == 0) phase_barrier();   // matches the extra barrier the lagging wavefronts took at the start
 }
 
 // Combines the partial results of a query tile whose key list was cut into slices.  One workgroup
-// handles 16 rows of one (query tile, head): thread -> (row, 4 consecutive output elements).
+// handles 16 rows of one (query tile, head group, wavefront): thread -> (row, 4 consecutive output elements).
 constexpr int MERGE_ROWS = 16;
 template <int D>
 __global__ __launch_bounds__(256) void merge_kernel(const PrefillArgs a) {
-  constexpr int C4 = D / 4, RB = BQ / MERGE_ROWS;
-  const int rb = blockIdx.x % RB, hq = (blockIdx.x / RB) % a.Hq, mid = blockIdx.x / (RB * a.Hq);
+  constexpr int C4 = D / 4;
+  const int parts = 2 * a.Gs * a.R;   // 16-row halves of the active wavefronts
+  const int part = blockIdx.x % parts, grp = (blockIdx.x / parts) % a.n_groups, mid = blockIdx.x / (parts * a.n_groups);
+  const int wave = part >> 1, rb = wave / a.Gs, hl = wave - rb * a.Gs;
   const MergeItem mi = a.merges[mid];
-  const int r = rb * MERGE_ROWS + threadIdx.x / 16;
-  const int row = mi.qtile * BQ + r;
+  const int r = wave * 32 + (part & 1) * MERGE_ROWS + threadIdx.x / 16;   // row within the workgroup's partial
+  const int hq = grp * a.Gs + hl;
+  const int row = mi.qtile * (a.R * 32) + rb * 32 + (part & 1) * MERGE_ROWS + threadIdx.x / 16;
   if (row >= a.N) return;
   float mx = -INFINITY, mxx = -INFINITY;
   for (int s = 0; s < mi.n_splits; ++s) {
-    const size_t prow = ((size_t)(mi.slot0 + s) * a.Hq + hq) * BQ + r;
+    const size_t prow = ((size_t)(mi.slot0 + s) * a.n_groups + grp) * WG_ROWS + r;
     mx = fmaxf(mx, a.ws_lse[2 * prow]);
     mxx = fmaxf(mxx, a.ws_lse[2 * prow + 1]);
   }
@@ -437,7 +533,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const PrefillArgs a) {
 #pragma unroll
   for (int c = 0; c < C4 / 16; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < mi.n_splits; ++s) {
-    const size_t prow = ((size_t)(mi.slot0 + s) * a.Hq + hq) * BQ + r;
+    const size_t prow = ((size_t)(mi.slot0 + s) * a.n_groups + grp) * WG_ROWS + r;
     const float w = __builtin_amdgcn_exp2f(a.ws_lse[2 * prow] - mx);
     wsum += w;
     xsum += __builtin_amdgcn_exp2f(a.ws_lse[2 * prow + 1] - mxx);
@@ -478,7 +574,7 @@ hipError_t launch_variant(const PrefillArgs& a, dim3 grid, hipStream_t st) {
 }  // namespace
 
 size_t prefill_ws_bytes(const purekv_plan& p) {
-  return (size_t)p.n_slots * p.g.Hq * BQ * (p.g.d + 2) * sizeof(float);
+  return (size_t)p.n_slots * p.g.n_groups * WG_ROWS * (p.g.d + 2) * sizeof(float);
 }
 
 int launch_prefill(const purekv_plan& p, const void* q, const void* k, const void* v, void* out, float* lse,
@@ -490,20 +586,24 @@ int launch_prefill(const purekv_plan& p, const void* q, const void* k, const voi
   a.out = static_cast<uint16_t*>(out);
   a.lse = lse;
   a.ws_o = static_cast<float*>(ws);
-  a.ws_lse = a.ws_o ? a.ws_o + (size_t)p.n_slots * p.g.Hq * BQ * p.g.d : nullptr;
+  a.ws_lse = a.ws_o ? a.ws_o + (size_t)p.n_slots * p.g.n_groups * WG_ROWS * p.g.d : nullptr;
   a.stream = p.d_stream;
   a.units = p.d_units;
   a.queue_begin = p.d_queue_begin;
+  a.queue_unit0 = p.d_queue_unit0;
   a.merges = p.d_merges;
   a.N = p.g.N;
   a.Nv = p.g.Nv;
   a.P = p.g.P;
   a.Hq = p.g.Hq;
   a.Hkv = p.g.Hkv;
+  a.Gs = p.g.Gs;
+  a.R = p.g.R;
+  a.n_groups = p.g.n_groups;
   a.pattern = p.g.pattern;
   a.scale_log2 = p.g.scale * kLog2e;
   const dim3 grid((unsigned)p.n_queues), block(256);
-  const dim3 mgrid((unsigned)(p.merges.size() * p.g.Hq * (BQ / MERGE_ROWS)));
+  const dim3 mgrid((unsigned)(p.merges.size() * p.g.n_groups * 2 * p.g.Gs * p.g.R));
   const bool sparse = p.g.pattern != PUREKV_PATTERN_DENSE;
   if (p.g.d == 128) {
     if (sparse)

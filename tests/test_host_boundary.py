@@ -76,7 +76,7 @@ def test_compute_calls_validate_before_touching_the_gpu():
     assert lib.purekv_kv_append(h, one, one, one, one, 0, 4, None) == pk.EINVAL
     assert lib.purekv_decode_attn(h, one, one, one, 4, 4, one, one, 1 << 20, None) == pk.EINVAL
     assert lib.purekv_workspace_bytes(None, pk.OP_PREFILL, 0, 0, 0) == 0
-    c = (ctypes.c_int64 * 8)()
+    c = (ctypes.c_int64 * 16)()
     assert lib.purekv_plan_counts(None, c) == pk.EINVAL and lib.purekv_plan_counts(h, None) == pk.EINVAL
     assert lib.purekv_plan_qtile_list(h, 99, None, 0) == pk.EINVAL
     assert lib.purekv_plan_queue(h, 100000, None, 0) == pk.EINVAL
@@ -94,41 +94,59 @@ def test_budget_matches_oracle_rule():
 
 
 def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern, n_wg=256):
-    """Tile lists and per-row-block masks against the oracle's boolean mask; slices, units and queues are a partition."""
+    """Tile lists, need bits and block kinds against the oracle's boolean mask; slices, units and queues are a
+    partition of the work."""
     P, n = ph * pw, F * ph * pw + T
     plan = pk.Plan(F, ph, pw, T, hq, hkv, d, pattern, host_only=True, n_workgroups=n_wg)
     c = plan.counts()
-    assert c["N"] == n and c["n_qtiles"] == (n + pk.BQ - 1) // pk.BQ
+    R, gs, n_groups = c["row_blocks"], c["stacked_heads"], c["n_head_groups"]
+    g = hq // hkv
+    assert 1 <= gs * R <= pk.WAVES and g % gs == 0 and n_groups * gs == hq
+    if pattern != 0 and g > 1 and any(g % x == 0 for x in range(2, pk.WAVES + 1)):
+        assert gs > 1      # sparse patterns stack the heads of a KV group
+    bq = R * pk.BLOCK
+    assert c["N"] == n and c["n_qtiles"] == (n + bq - 1) // bq
     n_ktiles = (n + pk.BK - 1) // pk.BK
-    total_pairs = refs = wave_tiles = full_wave_tiles = 0
+    total_pairs = refs = 0
+    by_kind = [0, 0, 0, 0]
     for qt in range(c["n_qtiles"]):
-        rows = np.arange(qt * pk.BQ, min((qt + 1) * pk.BQ, n))
+        rows = np.arange(qt * bq, min((qt + 1) * bq, n))
         mask = orc.st_mask_rows(F, P, T, pattern, rows)
         total_pairs += int(mask.sum())
-        padded = np.zeros((pk.BQ, n_ktiles * pk.BK), dtype=bool)
+        padded = np.zeros((bq, n_ktiles * pk.BK), dtype=bool)
         padded[:rows.shape[0], :n] = mask
-        blocks = padded.reshape(pk.WAVES, 32, n_ktiles, pk.BK)
-        real = (np.arange(pk.BQ) < rows.shape[0]).reshape(pk.WAVES, 32)
-        any_wt = blocks.any(axis=(1, 3))                                   # [wave, tile]
-        # full: every (real row, nominal key) pair allowed; a row block without real rows is never needed
-        all_wt = (blocks | ~real[:, :, None, None]).all(axis=(1, 3)) & real.any(axis=1)[:, None]
+        blocks = padded.reshape(R, pk.BLOCK, n_ktiles, 2, pk.BLOCK)      # [rb, row, tile, kb, key]
+        any_b = blocks.any(axis=(1, 4))                                      # [rb, tile, kb]
         lst = plan.qtile_list(qt)
         refs += len(lst)
-        assert [t for t, _, _ in lst] == np.nonzero(any_wt.any(axis=0))[0].tolist(), (qt, pattern)
-        for t, need, full in lst:
-            want_need = sum(1 << w for w in range(pk.WAVES) if any_wt[w, t])
+        assert [t for t, _, _ in lst] == np.nonzero(any_b.any(axis=(0, 2)))[0].tolist(), (qt, pattern)
+        row_idx = qt * bq + np.arange(bq).reshape(R, pk.BLOCK)               # absolute query rows
+        real = row_idx < n
+        for t, need, kinds in lst:
+            want_need = sum(1 << (2 * rb + kb) for rb in range(R) for kb in range(2) if any_b[rb, t, kb])
             assert need == want_need, (qt, t, pattern)
-            # the plan may flag fewer row blocks full than possible (the mask is then applied element-wise),
-            # never more
-            assert full & ~need == 0
-            for w in range(pk.WAVES):
-                if full >> w & 1:
-                    assert all_wt[w, t], (qt, t, w, pattern)
-            wave_tiles += bin(need).count("1")
-            full_wave_tiles += bin(full).count("1")
-    assert refs == c["n_tile_refs"] and wave_tiles == c["n_wave_tiles"] and full_wave_tiles == c["n_full_wave_tiles"]
+            for rb in range(R):
+                for kb in range(2):
+                    if not any_b[rb, t, kb]:
+                        continue
+                    kind = (kinds >> (4 * rb + 2 * kb)) & 3
+                    by_kind[kind] += 1
+                    blk = blocks[rb, :, t, kb, :][real[rb]]                  # real rows only
+                    i = row_idx[rb][real[rb]][:, None]
+                    j = (t * pk.BK + kb * pk.BLOCK + np.arange(pk.BLOCK))[None, :]
+                    # a cheaper kind is a promise about the mask of the block; the general kind promises nothing
+                    if kind == pk.KIND_FULL:
+                        assert blk.all(), (qt, t, rb, kb, pattern)
+                    elif kind == pk.KIND_CAUSAL:
+                        assert np.array_equal(blk, np.broadcast_to(j <= i, blk.shape)), (qt, t, rb, kb, pattern)
+                    elif kind == pk.KIND_PREV:
+                        assert np.array_equal(blk, np.broadcast_to(j == i - P, blk.shape)), (qt, t, rb, kb, pattern)
+    assert refs == c["n_tile_refs"] and sum(by_kind) == c["n_blocks"]
+    assert by_kind == [c["n_full_blocks"], c["n_causal_blocks"], c["n_prev_blocks"], c["n_general_blocks"]]
+    if pattern == 0:
+        assert by_kind[2] == 0 and by_kind[3] == 0     # the dense kernel variant only knows full and causal
     assert abs(plan.mask_flops() - 4.0 * d * total_pairs * hq) < 1e-3 * max(1.0, plan.mask_flops())
-    assert plan.kept_tile_flops() == 4.0 * 32 * pk.BK * d * wave_tiles * hq
+    assert plan.kept_tile_flops() == 4.0 * pk.BLOCK * pk.BLOCK * d * c["n_blocks"] * hq
     # work items: each query tile's list is covered exactly once, in order; slots are distinct
     begin = np.concatenate([[0], np.cumsum([len(plan.qtile_list(q)) for q in range(c["n_qtiles"])])])
     items = [plan.item(i) for i in range(c["n_items"])]
@@ -151,21 +169,22 @@ def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern, n_wg=256):
         assert pos == begin[qt + 1]
     assert sorted(slots) == list(range(len(slots)))
     assert c["n_split_qtiles"] == sum(1 for p in by_q.values() if len(p) > 1)
-    # queues: every (work item, head) unit runs exactly once
+    # queues: every (work item, head group) unit runs exactly once
     assert 1 <= c["n_workgroups"] <= n_wg
-    units = [u for g in range(c["n_workgroups"]) for u in plan.queue(g)]
-    assert sorted(units) == [(i, h) for i in range(c["n_items"]) for h in range(hq)]
-    loads = [sum(items[i][2] for i, _ in plan.queue(g)) for g in range(c["n_workgroups"])]
+    units = [u for q in range(c["n_workgroups"]) for u in plan.queue(q)]
+    assert sorted(units) == [(i, h0) for i in range(c["n_items"]) for h0 in range(0, hq, gs)]
+    loads = [sum(items[i][2] for i, _ in plan.queue(q)) for q in range(c["n_workgroups"])]
     if len(units) >= 4 * c["n_workgroups"]:
         assert max(loads) <= 1.5 * (sum(loads) / len(loads)) + max(it[2] for it in items)
     plan.close()
 
 
 @pytest.mark.parametrize("pattern", [0, 1, 2, 3])
+@pytest.mark.parametrize("heads", [(4, 2), (7, 1), (3, 3), (12, 2)])
 @pytest.mark.parametrize("shape", [(4, 8, 8, 32), (3, 5, 7, 19), (1, 9, 9, 0), (5, 16, 16, 200), (2, 24, 24, 1)])
-def test_plan_lists_match_oracle_mask_small(shape, pattern):
+def test_plan_lists_match_oracle_mask_small(shape, pattern, heads):
     F, ph, pw, T = shape
-    _check_plan_against_oracle(F, ph, pw, T, 4, 2, 64, pattern, n_wg=16)
+    _check_plan_against_oracle(F, ph, pw, T, heads[0], heads[1], 64, pattern, n_wg=16)
 
 
 @pytest.mark.parametrize("name", ["videollama2_8f", "qwen25vl_32f", "qwen25vl_64f", "qwen25vl_128f_stack"])
