@@ -5,7 +5,9 @@
 #include "plan.h"
 
 #include <algorithm>
+#include <cstddef>
 #include <numeric>
+#include <utility>
 
 namespace purekv {
 
@@ -126,9 +128,21 @@ void build_plan(purekv_plan& p, int n_cu) {
     p.qtile_begin.push_back(static_cast<int32_t>(p.tiles.size()));
   }
 
+  // ---- cost model (in steps of one full tile) ----
+  // A tile of which every row block needs one 32-key half at most skips half of the score product; a unit
+  // switch (write the finished rows, reset the state, first tile without a second product to overlap) costs
+  // about one and a half steps.
+  constexpr double kHalfTileCost = 0.85, kUnitCost = 1.5;
+  std::vector<double> tile_cost(p.tiles.size());
+  for (size_t i = 0; i < p.tiles.size(); ++i) {
+    bool both = false;
+    for (int32_t rb = 0; rb < g.R; ++rb) both |= ((p.tiles[i].need >> (2 * rb)) & 3u) == 3u;
+    tile_cost[i] = both ? 1.0 : kHalfTileCost;
+  }
+
   // ---- work items: cut lists that are long against the average load of one workgroup ----
   const double total_steps = double(p.tiles.size()) * g.n_groups;
-  const int32_t chunk = std::max<int32_t>(8, static_cast<int32_t>(0.8 * total_steps / std::max(1, n_cu) + 0.5));
+  const int32_t chunk = std::max<int32_t>(8, static_cast<int32_t>(0.4 * total_steps / std::max(1, n_cu) + 0.5));
   p.items.clear();
   p.merges.clear();
   p.n_slots = 0;
@@ -151,6 +165,12 @@ void build_plan(purekv_plan& p, int n_cu) {
   }
   std::stable_sort(p.items.begin(), p.items.end(),
                    [](const WorkItem& x, const WorkItem& y) { return x.n_tiles > y.n_tiles; });
+  std::vector<double> item_cost(p.items.size());
+  for (size_t it = 0; it < p.items.size(); ++it) {
+    double c = kUnitCost;
+    for (int32_t t = 0; t < p.items[it].n_tiles; ++t) c += tile_cost[p.items[it].list_begin + t];
+    item_cost[it] = c;
+  }
 
   // ---- deal (item, head group) units onto persistent workgroups: longest first, least-loaded queue ----
   // Workgroup q runs on XCD q % 8 (round-robin dispatch); when the head counts allow it, the units of one
@@ -158,23 +178,83 @@ void build_plan(purekv_plan& p, int n_cu) {
   const int64_t n_units = int64_t(p.items.size()) * g.n_groups;
   p.n_queues = static_cast<int32_t>(std::min<int64_t>(std::max(1, n_cu), std::max<int64_t>(1, n_units)));
   const bool affinity = (p.n_queues % 8 == 0) && (g.Hkv % 8 == 0 || 8 % g.Hkv == 0);
+  auto allowed = [&](int32_t q, int32_t kvh) {
+    if (!affinity) return true;
+    const int32_t x = q % 8;
+    return (g.Hkv >= 8) ? (x == kvh % 8) : (x % g.Hkv == kvh);
+  };
   std::vector<std::vector<int32_t>> queues(p.n_queues);  // flat (item, group) pairs
-  std::vector<int64_t> load(p.n_queues, 0);
+  std::vector<double> load(p.n_queues, 0.0);
   for (size_t it = 0; it < p.items.size(); ++it) {
     for (int32_t grp = 0; grp < g.n_groups; ++grp) {
       const int32_t kvh = grp * g.Gs / g.G;
       int32_t best = -1;
-      for (int32_t q = 0; q < p.n_queues; ++q) {
-        if (affinity) {
-          const int32_t x = q % 8;
-          const bool ok = (g.Hkv >= 8) ? (x == kvh % 8) : (x % g.Hkv == kvh);
-          if (!ok) continue;
-        }
-        if (best < 0 || load[q] < load[best]) best = q;
-      }
+      for (int32_t q = 0; q < p.n_queues; ++q)
+        if (allowed(q, kvh) && (best < 0 || load[q] < load[best])) best = q;
       queues[best].push_back(static_cast<int32_t>(it));
       queues[best].push_back(grp);
-      load[best] += p.items[it].n_tiles + 2;
+      load[best] += item_cost[it];
+    }
+  }
+  // Refinement: while it lowers the larger of the two loads, move a unit from the fullest queue to the emptiest
+  // queue that may run it, or exchange a unit of each.
+  for (int32_t round = 0; round < 8 * p.n_queues; ++round) {
+    const int32_t qa = static_cast<int32_t>(std::max_element(load.begin(), load.end()) - load.begin());
+    double best_gain = 1e-9;
+    int32_t best_q = -1;
+    size_t best_u = 0, best_v = SIZE_MAX;
+    for (size_t u = 0; u + 1 < queues[qa].size(); u += 2) {
+      const double cu = item_cost[queues[qa][u]];
+      const int32_t kvh = queues[qa][u + 1] * g.Gs / g.G;
+      for (int32_t qb = 0; qb < p.n_queues; ++qb) {
+        if (qb == qa || !allowed(qb, kvh)) continue;
+        // move u: new pair maximum = max(load[qa] - cu, load[qb] + cu)
+        double gain = load[qa] - std::max(load[qa] - cu, load[qb] + cu);
+        if (gain > best_gain) {
+          best_gain = gain;
+          best_q = qb;
+          best_u = u;
+          best_v = SIZE_MAX;
+        }
+        for (size_t v = 0; v + 1 < queues[qb].size(); v += 2) {
+          const double cv = item_cost[queues[qb][v]];
+          if (cv >= cu || !allowed(qa, queues[qb][v + 1] * g.Gs / g.G)) continue;
+          gain = load[qa] - std::max(load[qa] - cu + cv, load[qb] + cu - cv);
+          if (gain > best_gain) {
+            best_gain = gain;
+            best_q = qb;
+            best_u = u;
+            best_v = v;
+          }
+        }
+      }
+    }
+    if (best_q < 0) break;
+    const int32_t ui = queues[qa][best_u], ug = queues[qa][best_u + 1];
+    if (best_v == SIZE_MAX) {
+      queues[qa].erase(queues[qa].begin() + best_u, queues[qa].begin() + best_u + 2);
+      queues[best_q].push_back(ui);
+      queues[best_q].push_back(ug);
+      load[qa] -= item_cost[ui];
+      load[best_q] += item_cost[ui];
+    } else {
+      const int32_t vi = queues[best_q][best_v], vg = queues[best_q][best_v + 1];
+      queues[qa][best_u] = vi;
+      queues[qa][best_u + 1] = vg;
+      queues[best_q][best_v] = ui;
+      queues[best_q][best_v + 1] = ug;
+      load[qa] += item_cost[vi] - item_cost[ui];
+      load[best_q] += item_cost[ui] - item_cost[vi];
+    }
+  }
+  // Longest units first within a queue (item indices ascend with decreasing length).
+  for (auto& qv : queues) {
+    std::vector<std::pair<int32_t, int32_t>> pairs;
+    for (size_t u = 0; u + 1 < qv.size(); u += 2) pairs.emplace_back(qv[u], qv[u + 1]);
+    std::stable_sort(pairs.begin(), pairs.end());
+    for (size_t u = 0; u < pairs.size(); ++u) {
+      qv[2 * u] = pairs[u].first;
+      qv[2 * u + 1] = pairs[u].second;
     }
   }
 

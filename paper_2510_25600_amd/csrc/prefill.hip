@@ -36,6 +36,7 @@ namespace {
 constexpr int BK = PUREKV_BK;
 constexpr int WG_ROWS = PUREKV_WAVES * PUREKV_BLOCK;   // rows of one workgroup's partial result
 constexpr float kRescaleGap = 8.0f;
+constexpr int kXTile = 4096;   // bf16 elements of a wavefront's private LDS tile (8 KB)
 
 struct PrefillArgs {
   const uint16_t* q;
@@ -138,6 +139,9 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   uint16_t* const Ks_base = smem;                     // NBUF x [BK][D]
   uint16_t* const Vs_base = smem + NBUF * BK * D;     // NBUF x [BK][D]
+  // One private 8 KB tile per wavefront (32 rows x 256 bytes) through which query rows come in and output rows
+  // go out: global memory sees whole rows (16 lanes x 16 bytes each), the MFMA register layouts see LDS.
+  uint16_t* const Xs_base = smem + 2 * NBUF * BK * D; // PUREKV_WAVES x kXTile
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -203,6 +207,9 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   };
   auto next_buf = [](int b) { return b == NBUF - 1 ? 0 : b + 1; };
   // Barrier between phases; the scheduling fences keep the matrix work of a phase on its side.
+  // Only LDS traffic has to be ordered here (reads of a buffer before the barrier, its refill after it): a bare
+  // barrier after the LDS counter has drained.  __syncthreads() would also wait for every outstanding global
+  // access, i.e. for the K/V loads just issued and for the output stores of a finished unit.
   auto phase_barrier = [&]() {
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
@@ -210,7 +217,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   };
 
   // ---- per-unit state ----
-  int hq = 0, row = 0, rowc = 0, a_i = 0, lo_i = 0, prev_j = -1, self_j = -1;
+  int hq = 0, row0 = 0, rowc = 0, a_i = 0, lo_i = 0, prev_j = -1, self_j = -1;
   int u_nsplits = 1, u_ws_row0 = -1;
   bf16x8 qf[KSTEPS];
   // m: reference maximum (log2 units); lacc: every element holds the sum of the bf16-rounded probabilities of
@@ -221,22 +228,37 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) ones8[i] = (__bf16)1.0f;
 
-  // Unit record {row0, head0, n_splits, ws_row0}: start fetching this wavefront's 32 query rows.  The fragment
-  // registers are free from the last score product of a unit to the first of the next.
+  uint16_t* const Xs = Xs_base + wave * kXTile;
+  constexpr int XQ = 32 * CPR / 64;   // 1 KB pieces of a 32-row bf16 tile
+  // Unit record {row0, head0, n_splits, ws_row0}: start fetching this wavefront's 32 query rows into its private
+  // LDS tile (same swizzled layout as a K tile; rows past the end repeat the last row).
   auto prefetch_q = [&](const u32x4 un) {
     if (active) {
-      const int r = min((int)un[0] + rb * 32 + n, a.N - 1);
-      const uint16_t* qrow = a.q + ((size_t)((int)un[1] + hl) * a.N + r) * D;
+      int ln = lane;   // opaque copy: keeps the address arithmetic inside the unit switch
+      asm volatile("" : "+v"(ln));
+      const char* qhead = reinterpret_cast<const char*>(a.q) + (size_t)((int)un[1] + hl) * a.N * (D * 2);
+      const int r0 = (int)un[0] + rb * 32;
 #pragma unroll
-      for (int s = 0; s < KSTEPS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s + 8 * h);
+      for (int i = 0; i < XQ; ++i) {
+        int r, u;
+        kunswz<D>(i * 64 + ln, r, u);
+        const size_t off = (size_t)min(r0 + r, a.N - 1) * (D * 2) + (size_t)u * 16;
+        __builtin_amdgcn_global_load_lds((GlobalPtr)(qhead + off), (LdsPtr)(Xs + i * 512), 16, 0, 0);
+      }
     }
+  };
+  // Query fragments of the unit that starts: B operand of k-step s = columns 16 s + 8 h .. of row n.
+  auto load_q_frags = [&]() {
+    wait_loads();
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(Xs + kswz<D>(n, 2 * s + h));
   };
   auto begin_unit = [&](const u32x4 un) {
     hq = (int)un[1] + hl;
     u_nsplits = (int)un[2];
     u_ws_row0 = (int)un[3];
-    row = (int)un[0] + rb * 32 + n;
-    rowc = min(row, a.N - 1);
+    row0 = (int)un[0] + rb * 32;
+    rowc = min(row0 + n, a.N - 1);
     // allowed keys of this lane's row: j <= rowc and (j <= a_i or j >= lo_i or j == prev_j or j == self_j)
     const bool sparse_row = ST && a.pattern != 0u && rowc < a.Nv;
     const int frame = sparse_row ? rowc / a.P : 0;
@@ -254,40 +276,80 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
       for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
   };
 
-  // Normalise and write this wavefront's 32 rows of the unit that just finished.
+  // Normalise and write this wavefront's 32 rows of the unit that just finished.  The accumulators hold, per
+  // lane, 4 consecutive columns of ONE row at a time; the rows are assembled in the private LDS tile and leave
+  // as whole 256-byte pieces.
   auto finish_unit = [&]() {
     if (!active) return;
+    // Addresses below depend on the lane only; derived from an opaque copy they are recomputed here instead of
+    // being hoisted out of the tile loop, where they would occupy registers all the time.
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int n = ln & 31, h = ln >> 5;
     const float l_tot = lacc[0];
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     const float lse2 = m + __builtin_amdgcn_logf(l_tot);  // log2 domain; -inf when the slice saw no key
     const float lse2x = LSE ? m + __builtin_amdgcn_logf(lx + other_half(lx)) : lse2;
     if (u_nsplits == 1) {
-      if (row < a.N) {
-        uint16_t* orow = a.out + ((size_t)hq * a.N + row) * D;
-#pragma unroll
-        for (int b = 0; b < DBLK; ++b)
-#pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) {
-            u32x2 w;
-            w[0] = pack_bf16(oacc[b][4 * g4 + 0] * inv, oacc[b][4 * g4 + 1] * inv);
-            w[1] = pack_bf16(oacc[b][4 * g4 + 2] * inv, oacc[b][4 * g4 + 3] * inv);
-            *reinterpret_cast<u32x2*>(orow + 32 * b + 8 * g4 + 4 * h) = w;
-          }
-        if (LSE && h == 0) a.lse[(size_t)hq * a.N + row] = lse2x * kLn2;
-      }
-    } else {
-      const size_t prow = (size_t)u_ws_row0 + wave * 32 + n;
-      float* orow = a.ws_o + prow * D;
 #pragma unroll
       for (int b = 0; b < DBLK; ++b)
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
-          floatx4 w;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) w[r] = oacc[b][4 * g4 + r] * inv;
-          *reinterpret_cast<floatx4*>(orow + 32 * b + 8 * g4 + 4 * h) = w;
+          u32x2 w;
+          w[0] = pack_bf16(oacc[b][4 * g4 + 0] * inv, oacc[b][4 * g4 + 1] * inv);
+          w[1] = pack_bf16(oacc[b][4 * g4 + 2] * inv, oacc[b][4 * g4 + 3] * inv);
+          *reinterpret_cast<u32x2*>(Xs + kswz<D>(n, 4 * b + g4) + 4 * h) = w;   // columns 32 b + 8 g4 + 4 h ..
         }
+      char* ohead = reinterpret_cast<char*>(a.out) + (size_t)hq * a.N * (D * 2);
+      // read the pieces back in batches of four before storing any: the LDS latencies overlap
+#pragma unroll
+      for (int i0 = 0; i0 < XQ; i0 += 4) {
+        u32x4 w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = *reinterpret_cast<const u32x4*>(Xs + ((i0 + i) * 64 + ln) * 8);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          int r, u;
+          kunswz<D>((i0 + i) * 64 + ln, r, u);
+          if (row0 + r < a.N)
+            *reinterpret_cast<u32x4*>(ohead + (size_t)(row0 + r) * (D * 2) + (size_t)u * 16) = w[i];
+        }
+      }
+      if (LSE && h == 0 && row0 + n < a.N) a.lse[(size_t)hq * a.N + row0 + n] = lse2x * kLn2;
+    } else {
+      // fp32 partial result: 64 columns (256 bytes a row) per round through the same tile
+      float* const Xf = reinterpret_cast<float*>(Xs);
+      float* wbase = a.ws_o + ((size_t)u_ws_row0 + wave * 32) * D;
+#pragma unroll
+      for (int rnd = 0; rnd < D / 64; ++rnd) {
+#pragma unroll
+        for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+          for (int g4 = 0; g4 < 4; ++g4) {
+            floatx4 w;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) w[r] = oacc[2 * rnd + bb][4 * g4 + r] * inv;
+            // columns 32 bb + 8 g4 + 4 h .. of the round: 16-byte slot 8 bb + 2 g4 + h of a 256-byte row
+            *reinterpret_cast<floatx4*>(Xf + kswz<128>(n, 8 * bb + 2 * g4 + h) / 2) = w;
+            __builtin_amdgcn_sched_barrier(0);
+          }
+#pragma unroll
+        for (int i0 = 0; i0 < 8; i0 += 4) {
+          floatx4 w[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) w[i] = *reinterpret_cast<const floatx4*>(Xf + ((i0 + i) * 64 + ln) * 4);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            int r, u;
+            kunswz<128>((i0 + i) * 64 + ln, r, u);
+            *reinterpret_cast<floatx4*>(wbase + (size_t)r * D + 64 * rnd + 4 * u) = w[i];
+          }
+        }
+      }
       if (h == 0) {
+        const size_t prow = (size_t)u_ws_row0 + wave * 32 + n;
         a.ws_lse[2 * prow] = lse2;
         a.ws_lse[2 * prow + 1] = lse2x;
       }
@@ -462,12 +524,11 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     const uint32_t kinds = (st0.kinds >> (4 * rb)) & 15u;
     const bool last = (st0.need >> 16) & 1u, first = (st0.need >> 17) & 1u;
 
-    // ---- matrix phase: second product of the previous tile, unit switch, score product of this tile ----
+    // ---- matrix phase: second product of the previous tile, score product of this tile ----
     PHASE_MARK(0);
     if (pv_bits) pv_tile(pv_buf, pf);
     PHASE_MARK(4);
-    if (fin_pending) finish_unit();
-    if (first) begin_unit(un_next);
+    if (first) load_q_frags();   // frees the private tile, which the finished unit's rows leave through
     {
       const uint16_t* Ks = Ks_base + buf * (BK * D);
       if (nb & 1u) qk_half(Ks, sacc[0]);
@@ -478,7 +539,15 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     phase_barrier();
     PHASE_MARK(2);
 
-    // ---- vector phase: start the loads of this wavefront's rows of the coming tiles; softmax ----
+    // ---- vector phase: unit switch, start the loads of this wavefront's rows of the coming tiles, softmax ----
+    // Unit switch (a pending unit always ends where the next one starts).  It sits in the vector phase: its
+    // arithmetic overlaps the other wavefront's MFMAs, and both halves of the workgroup pay for it in the same
+    // pair of phases.
+    if (first) {
+      if (fin_pending) finish_unit();
+      PHASE_MARK(7);
+      begin_unit(un_next);
+    }
     const int b1 = next_buf(buf), b2 = next_buf(b1);
     if (t + 2 < t_end) issue_k(st2, b2);
     if (grp == 0) {
@@ -558,7 +627,8 @@ __global__ __launch_bounds__(256) void merge_kernel(const PrefillArgs a) {
 
 template <int D, bool ST, bool LSE>
 hipError_t launch_one(const PrefillArgs& a, dim3 grid, hipStream_t st) {
-  constexpr unsigned lds_bytes = 6u * BK * D * sizeof(uint16_t);   // 3 K buffers + 3 V buffers
+  // 3 K buffers + 3 V buffers + one private tile per wavefront
+  constexpr unsigned lds_bytes = (6u * BK * D + PUREKV_WAVES * kXTile) * sizeof(uint16_t);
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel<D, ST, LSE>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (attr != hipSuccess) return attr;
