@@ -73,7 +73,7 @@ def main() -> int:
     ap.add_argument("--batched-layers", type=int, default=26, help="layers per batched top-k/compaction launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=28, help="query heads in the oracle's timed sample")
-    ap.add_argument("--only-stage", default=None, choices=STAGES + ["copy_calib"],
+    ap.add_argument("--only-stage", default=None, choices=STAGES + ["copy_calib", "topk_batched", "compact_batched"],
                     help="profiling aid: after one full warm-up step run only this stage --steps times and exit")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -135,9 +135,25 @@ def main() -> int:
         pk.purekv_decode_attn(st, q_new, kc1, vc1, n_keep + 1, out=o_dec)
         mark(8)
 
+    def make_batched(L):
+        """Buffers of L high layers (Eq. 4: every high layer scores with the same C and its own V); distinct data
+        per layer, derived on the device from the generated high layer."""
+        v_all = torch.empty((L, hkv, n, d), dtype=torch.bfloat16, device=dev)
+        k_all = torch.empty_like(v_all)
+        for l in range(L):
+            v_all[l] = v1.roll(l, dims=1)
+            k_all[l] = k1.roll(l, dims=1)
+        idx_all = torch.empty((L, hkv, n_keep), dtype=torch.int32, device=dev)
+        kc_all = torch.empty((L, hkv, n_keep, d), dtype=torch.bfloat16, device=dev)
+        vc_all = torch.empty_like(kc_all)
+        return v_all, k_all, idx_all, kc_all, vc_all
+
     if args.only_stage is not None:
         step()
         torch.cuda.synchronize()
+        if args.only_stage in ("topk_batched", "compact_batched"):
+            v_all, k_all, idx_all, kc_all, vc_all = make_batched(args.batched_layers)
+            pk.purekv_topk_select(st, c, v_all, w, h, idx_out=idx_all)
         if args.only_stage == "copy_calib":
             calib_src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
             calib_dst = torch.empty_like(calib_src)
@@ -153,6 +169,8 @@ def main() -> int:
                                       pk.purekv_decode_attn(st, q_new, kc1, vc1, n_keep + 1, out=o_dec)),
             # plain device copy of a known size (256 MiB read + 256 MiB written): scale for the HBM byte counters
             "copy_calib": lambda: calib_dst.copy_(calib_src),
+            "topk_batched": lambda: pk.purekv_topk_select(st, c, v_all, w, h, idx_out=idx_all),
+            "compact_batched": lambda: pk.purekv_kv_compact(st, k_all, v_all, idx_all, kc=kc_all, vc=vc_all),
         }
         one = stages[args.only_stage]
         for _ in range(args.steps):
@@ -193,14 +211,7 @@ def main() -> int:
 
     # batched over the high layers (Eq. 4: every high layer scores with the same C and its own V)
     L = args.batched_layers
-    v_all = torch.empty((L, hkv, n, d), dtype=torch.bfloat16, device=dev)
-    k_all = torch.empty_like(v_all)
-    for l in range(L):  # distinct data per layer, derived on the device from the two generated layers
-        v_all[l] = v1.roll(l, dims=1)
-        k_all[l] = k1.roll(l, dims=1)
-    idx_all = torch.empty((L, hkv, n_keep), dtype=torch.int32, device=dev)
-    kc_all = torch.empty((L, hkv, n_keep, d), dtype=torch.bfloat16, device=dev)
-    vc_all = torch.empty_like(kc_all)
+    v_all, k_all, idx_all, kc_all, vc_all = make_batched(L)
     topk_b_ms = time_calls(lambda: pk.purekv_topk_select(st, c, v_all, w, h, idx_out=idx_all))
     comp_b_ms = time_calls(lambda: pk.purekv_kv_compact(st, k_all, v_all, idx_all, kc=kc_all, vc=vc_all))
     del v_all, k_all, kc_all, vc_all

@@ -120,6 +120,21 @@ def test_topk_exact_on_given_scores(n_keys, h):
     assert np.array_equal(idx.cpu().numpy(), ref)
 
 
+@pytest.mark.parametrize("n_keys", [8192, 8193, 16384, 20000, 32768, 32769, 50001])
+def test_topk_row_lengths_across_kernel_variants(n_keys):
+    """Row lengths on both sides of every switch between the register-resident variants (8, 16, 32 scores per
+    thread) and the streaming variant of the selection kernel; heavy ties in one head."""
+    w = 8
+    plan = pk.Plan(1, 1, n_keys, w, 2, 2, 64, 0)
+    rng = np.random.default_rng(n_keys)
+    s = rng.random((2, n_keys)).astype(np.float32)
+    s[1] = np.round(s[1] * 16) / 16
+    for h in (1, n_keys // 5, n_keys):
+        idx = pk.purekv_topk_select(plan, torch.from_numpy(s).cuda(), None, w, h)
+        ref = orc.topk_select(s.astype(np.float64), h, n_keys + w, w)
+        assert np.array_equal(idx.cpu().numpy(), ref), (n_keys, h)
+
+
 def test_topk_negative_and_mixed_scores():
     w, n_keys = 8, 3000
     plan = pk.Plan(1, 1, n_keys, w, 2, 2, 64, 0)
