@@ -51,11 +51,13 @@ def profiled_traffic_bytes():
     try:
         total, in_table = 0.0, False
         for line in open(path):
-            in_table = in_table or line.startswith("## HBM-side byte counters")
+            if line.startswith("## "):
+                in_table = line.startswith("## Kernel durations")
             cells = [c.strip() for c in line.split("|")]
-            if in_table and len(cells) >= 5 and (cells[1].startswith("`prefill_kernel<128, true") or cells[1].startswith("`merge_kernel")):
+            if in_table and len(cells) >= 9 and (cells[1].startswith("`prefill_kernel<128, true")
+                                                 or cells[1].startswith("`merge_kernel")):
                 try:
-                    total += float(cells[2]) * 2.0 * 1024 + float(cells[3]) * 1024
+                    total += float(cells[7]) * 2.0 * 1024 + float(cells[8]) * 1024
                 except ValueError:
                     pass
         return int(total) if total > 0 else None
