@@ -40,6 +40,29 @@ __device__ __forceinline__ float other_half(float x) {
   return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
 }
 
+// Row-major bf16 tile of D columns in LDS (K tiles, query tiles): element offset of 16-byte slot `u` of row `r`.  The slot index is XOR-ed with the
+// row so that the 16 lanes the LDS serves together (rows that differ in their low four bits) fall into 16
+// different 16-byte slots of a 256-byte bank period.
+template <int D>
+__device__ __forceinline__ int kswz(int r, int u) {
+  if constexpr (D == 128) {
+    return r * 128 + ((u ^ (r & 15)) * 8);
+  } else {  // 64 elements = 128 bytes: two rows share one 256-byte period
+    return (r >> 1) * 128 + ((((r & 1) * 8 + u) ^ ((r >> 1) & 15)) * 8);
+  }
+}
+// Inverse: 16-byte position p of the tile -> (row, slot) stored there.
+template <int D>
+__device__ __forceinline__ void kunswz(int p, int& r, int& u) {
+  if constexpr (D == 128) {
+    r = p >> 4;
+    u = (p & 15) ^ (r & 15);
+  } else {
+    const int rr = p >> 4, y = (p & 15) ^ (rr & 15);
+    r = 2 * rr + (y >> 3);
+    u = y & 7;
+  }
+}
 // Records a failed HIP call for purekv_strerror and maps it to PUREKV_EHIP.
 int note_hip_error(hipError_t e);
 

@@ -73,29 +73,6 @@ typedef __attribute__((address_space(3))) shortx4* LdsShortx4;
 typedef __attribute__((address_space(3))) void* LdsPtr;
 typedef const __attribute__((address_space(1))) void* GlobalPtr;
 
-// K tile [BK][D] bf16 in LDS: element offset of 16-byte slot `u` of row `r`.  The slot index is XOR-ed with the
-// row so that the 16 lanes the LDS serves together (rows that differ in their low four bits) fall into 16
-// different 16-byte slots of a 256-byte bank period.
-template <int D>
-__device__ __forceinline__ int kswz(int r, int u) {
-  if constexpr (D == 128) {
-    return r * 128 + ((u ^ (r & 15)) * 8);
-  } else {  // 64 elements = 128 bytes: two rows share one 256-byte period
-    return (r >> 1) * 128 + ((((r & 1) * 8 + u) ^ ((r >> 1) & 15)) * 8);
-  }
-}
-// Inverse: 16-byte position p of the tile -> (row, slot) stored there.
-template <int D>
-__device__ __forceinline__ void kunswz(int p, int& r, int& u) {
-  if constexpr (D == 128) {
-    r = p >> 4;
-    u = (p & 15) ^ (r & 15);
-  } else {
-    const int rr = p >> 4, y = (p & 15) ^ (rr & 15);
-    r = 2 * rr + (y >> 3);
-    u = y & 7;
-  }
-}
 // V tile [BK][D] bf16 in LDS, row-major; the transpose read of a 16-lane group touches 4 consecutive rows x 32
 // bytes, two such groups run side by side: XOR-ing the 32-byte pair index with the row's low bits keeps them on
 // distinct banks.
