@@ -71,9 +71,19 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecodeArgs a) {
 
   const uint16_t* kb = a.kc + (size_t)kvh * a.cap * D;
   const uint16_t* vb = a.vc + (size_t)kvh * a.cap * D;
-  for (int j = c0 + grp; j < c1; j += GPB) {
-    const u32x4 kx = *reinterpret_cast<const u32x4*>(kb + (size_t)j * D + sub * 8);
-    const u32x4 vx = *reinterpret_cast<const u32x4*>(vb + (size_t)j * D + sub * 8);
+  // all rows of this group are requested before the first is used (a chunk is at most RPG rows per group)
+  constexpr int RPG = DEC_CHUNK / GPB;
+  u32x4 kxs[RPG], vxs[RPG];
+#pragma unroll
+  for (int r = 0; r < RPG; ++r) {
+    const int j = min(c0 + grp + r * GPB, a.n_cached - 1);
+    kxs[r] = *reinterpret_cast<const u32x4*>(kb + (size_t)j * D + sub * 8);
+    vxs[r] = *reinterpret_cast<const u32x4*>(vb + (size_t)j * D + sub * 8);
+  }
+#pragma unroll
+  for (int r = 0; r < RPG; ++r) {
+    if (c0 + grp + r * GPB >= c1) break;
+    const u32x4 kx = kxs[r], vx = vxs[r];
     float kf[8], vf[8];
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
@@ -142,18 +152,61 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecodeArgs a) {
   }
 }
 
+// One workgroup per query head; thread -> (output element, one of MERGE_PARTS interleaved subsets of the chunks).
+// A thread requests all its chunks' values before it combines them; the subsets are combined through LDS in a
+// fixed order.
+constexpr int MERGE_PARTS = 4;
 template <int D>
-__global__ void decode_merge_kernel(const DecodeArgs a) {
-  const int hq = blockIdx.x, dd = threadIdx.x;
+__global__ __launch_bounds__(D * MERGE_PARTS) void decode_merge_kernel(const DecodeArgs a) {
+  __shared__ float sm[MERGE_PARTS][D], sl[MERGE_PARTS], smax[MERGE_PARTS];
+  const int hq = blockIdx.x, dd = threadIdx.x % D, part = threadIdx.x / D;
+  constexpr int U = 8;
   float mn = -INFINITY;
-  for (int s = 0; s < a.n_splits; ++s) mn = fmaxf(mn, a.ws_ml[((size_t)s * a.Hq + hq) * 2]);
-  float acc = 0.f, ls = 0.f;
-  for (int s = 0; s < a.n_splits; ++s) {
-    const float sc = __builtin_amdgcn_exp2f(a.ws_ml[((size_t)s * a.Hq + hq) * 2] - mn);
-    acc += a.ws_o[((size_t)s * a.Hq + hq) * D + dd] * sc;
-    ls += a.ws_ml[((size_t)s * a.Hq + hq) * 2 + 1] * sc;
+  for (int s0 = part; s0 < a.n_splits; s0 += MERGE_PARTS * U) {
+    float mv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int s = s0 + u * MERGE_PARTS;
+      mv[u] = s < a.n_splits ? a.ws_ml[((size_t)s * a.Hq + hq) * 2] : -INFINITY;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) mn = fmaxf(mn, mv[u]);
   }
-  a.out[(size_t)hq * D + dd] = (uint16_t)f32_to_bf16(acc / ls);
+  if (dd == 0) smax[part] = mn;
+  __syncthreads();
+  mn = smax[0];
+#pragma unroll
+  for (int p2 = 1; p2 < MERGE_PARTS; ++p2) mn = fmaxf(mn, smax[p2]);
+  float acc = 0.f, ls = 0.f;
+  for (int s0 = part; s0 < a.n_splits; s0 += MERGE_PARTS * U) {
+    float mv[U], ov[U], lv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int s = min(s0 + u * MERGE_PARTS, a.n_splits - 1);
+      mv[u] = a.ws_ml[((size_t)s * a.Hq + hq) * 2];
+      lv[u] = a.ws_ml[((size_t)s * a.Hq + hq) * 2 + 1];
+      ov[u] = a.ws_o[((size_t)s * a.Hq + hq) * D + dd];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (s0 + u * MERGE_PARTS < a.n_splits) {
+        const float sc = __builtin_amdgcn_exp2f(mv[u] - mn);
+        acc += ov[u] * sc;
+        ls += lv[u] * sc;
+      }
+    }
+  }
+  sm[part][dd] = acc;
+  if (dd == 0) sl[part] = ls;
+  __syncthreads();
+  if (part == 0) {
+#pragma unroll
+    for (int p2 = 1; p2 < MERGE_PARTS; ++p2) {
+      acc += sm[p2][dd];
+      ls += sl[p2];
+    }
+    a.out[(size_t)hq * D + dd] = (uint16_t)f32_to_bf16(acc / ls);
+  }
 }
 
 }  // namespace
@@ -180,10 +233,10 @@ int launch_decode(const purekv_plan& p, const void* q_new, const void* kc, const
   const dim3 grid((unsigned)a.n_splits, (unsigned)p.g.Hkv, (unsigned)((p.g.G + GT - 1) / GT));
   if (p.g.d == 128) {
     hipLaunchKernelGGL(decode_kernel<128>, grid, dim3(256), 0, st, a);
-    hipLaunchKernelGGL(decode_merge_kernel<128>, dim3((unsigned)p.g.Hq), dim3(128), 0, st, a);
+    hipLaunchKernelGGL(decode_merge_kernel<128>, dim3((unsigned)p.g.Hq), dim3(128 * MERGE_PARTS), 0, st, a);
   } else {
     hipLaunchKernelGGL(decode_kernel<64>, grid, dim3(256), 0, st, a);
-    hipLaunchKernelGGL(decode_merge_kernel<64>, dim3((unsigned)p.g.Hq), dim3(64), 0, st, a);
+    hipLaunchKernelGGL(decode_merge_kernel<64>, dim3((unsigned)p.g.Hq), dim3(64 * MERGE_PARTS), 0, st, a);
   }
   PUREKV_HIP_TRY(hipGetLastError());
   return PUREKV_OK;
