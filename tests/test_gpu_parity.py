@@ -33,6 +33,15 @@ SMALL = {
     # long text tail so that the text rows' key lists are split across work items and merged
     "longtext_2f": small_variant("longtext_2f", n_frames=2, patch_h=16, patch_w=16, n_text=2100, n_q_heads=2,
                                  n_kv_heads=1, head_dim=128),
+    # workgroup shapes of the planner: 7 stacked heads x 1 row block (one wavefront idle), split text rows
+    "heads7_3f": small_variant("heads7_3f", n_frames=3, patch_h=10, patch_w=10, n_text=900, n_q_heads=7,
+                               n_kv_heads=1, head_dim=128),
+    # 3 stacked heads x 2 row blocks (six wavefronts), two KV heads, P = 99 straddles row blocks and key halves
+    "heads3_4f": small_variant("heads3_4f", n_frames=4, patch_h=9, patch_w=11, n_text=45, n_q_heads=6,
+                               n_kv_heads=2, head_dim=64),
+    # 12 query heads per KV head: two groups of 6 stacked heads
+    "heads12_2f": small_variant("heads12_2f", n_frames=2, patch_h=12, patch_w=12, n_text=33, n_q_heads=12,
+                                n_kv_heads=1, head_dim=128),
 }
 
 
