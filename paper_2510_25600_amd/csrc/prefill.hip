@@ -213,13 +213,15 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     if (active) {
       int ln = lane;   // opaque copy: keeps the address arithmetic inside the unit switch
       asm volatile("" : "+v"(ln));
-      const char* qhead = reinterpret_cast<const char*>(a.q) + (size_t)((int)un[1] + hl) * a.N * (D * 2);
       const int r0 = (int)un[0] + rb * 32;
+      // uniform base of the head + 32-bit lane offsets (a head is at most 2^30 bytes); the row is clamped to
+      // the last row of the sequence, also when the whole block lies past it (ragged last query tile)
+      const char* const qhead = reinterpret_cast<const char*>(a.q) + (size_t)((int)un[1] + hl) * a.N * (D * 2);
 #pragma unroll
       for (int i = 0; i < XQ; ++i) {
         int r, u;
         kunswz<D>(i * 64 + ln, r, u);
-        const size_t off = (size_t)min(r0 + r, a.N - 1) * (D * 2) + (size_t)u * 16;
+        const uint32_t off = (uint32_t)min(r0 + r, a.N - 1) * (D * 2u) + (uint32_t)u * 16u;
         __builtin_amdgcn_global_load_lds((GlobalPtr)(qhead + off), (LdsPtr)(Xs + i * 512), 16, 0, 0);
       }
     }
@@ -277,7 +279,9 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
           w[1] = pack_bf16(oacc[b][4 * g4 + 2] * inv, oacc[b][4 * g4 + 3] * inv);
           *reinterpret_cast<u32x2*>(Xs + kswz<D>(n, 4 * b + g4) + 4 * h) = w;   // columns 32 b + 8 g4 + 4 h ..
         }
-      char* ohead = reinterpret_cast<char*>(a.out) + (size_t)hq * a.N * (D * 2);
+      // uniform base of the tile's first row + 32-bit lane offsets (a head is at most 2^30 bytes)
+      char* const otile = reinterpret_cast<char*>(a.out) + ((size_t)hq * a.N + row0) * (D * 2);
+      const int rows_left = a.N - row0;   // rows of the tile that exist
       // read the pieces back in batches of four before storing any: the LDS latencies overlap
 #pragma unroll
       for (int i0 = 0; i0 < XQ; i0 += 4) {
@@ -289,8 +293,8 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
         for (int i = 0; i < 4; ++i) {
           int r, u;
           kunswz<D>((i0 + i) * 64 + ln, r, u);
-          if (row0 + r < a.N)
-            *reinterpret_cast<u32x4*>(ohead + (size_t)(row0 + r) * (D * 2) + (size_t)u * 16) = w[i];
+          const uint32_t off = (uint32_t)r * (D * 2u) + (uint32_t)u * 16u;
+          if (rows_left >= 32 || r < rows_left) *reinterpret_cast<u32x4*>(otile + off) = w[i];
         }
       }
       if (LSE && h == 0 && row0 + n < a.N) a.lse[(size_t)hq * a.N + row0 + n] = lse2x * kLn2;
