@@ -37,6 +37,14 @@ constexpr int BK = PUREKV_BK;
 constexpr int WG_ROWS = PUREKV_WAVES * PUREKV_BLOCK;   // rows of one workgroup's partial result
 constexpr float kRescaleGap = 8.0f;
 constexpr int kXTile = 4096;   // bf16 elements of a wavefront's private LDS tile (8 KB)
+// Operand fragments are read from LDS this many MFMAs ahead of their use.
+#ifndef PUREKV_QK_AHEAD
+#define PUREKV_QK_AHEAD 2
+#endif
+#ifndef PUREKV_PV_AHEAD
+#define PUREKV_PV_AHEAD 2
+#endif
+constexpr int kQkAhead = PUREKV_QK_AHEAD, kPvAhead = PUREKV_PV_AHEAD;
 
 struct PrefillArgs {
   const uint16_t* q;
@@ -56,14 +64,14 @@ struct PrefillArgs {
   uint32_t pattern;
   float scale_log2;  // softmax scale * log2(e)
 #ifdef PUREKV_PHASE_TRACE
-  unsigned long long* trace;  // [grid, 2, 64, 8] cycle stamps of wavefronts 0 and 4, development builds only
+  unsigned long long* trace;  // [grid, 8, 64, 8] cycle stamps per wavefront, development builds only
 #endif
 };
 
 #ifdef PUREKV_PHASE_TRACE
 #define PHASE_MARK(i)                                                                                  \
-  if ((threadIdx.x & 255) == 0 && t - t_begin < 64)                                                    \
-  a.trace[(((size_t)blockIdx.x * 2 + (threadIdx.x >> 8)) * 64 + (t - t_begin)) * 8 + (i)] = __builtin_readcyclecounter()
+  if ((threadIdx.x & 63) == 0 && t - t_begin < 64)                                                     \
+  a.trace[(((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 64 + (t - t_begin)) * 8 + (i)] = __builtin_readcyclecounter()
 #else
 #define PHASE_MARK(i)
 #endif
@@ -183,27 +191,30 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     return s;
   };
   auto next_buf = [](int b) { return b == NBUF - 1 ? 0 : b + 1; };
-  // Barrier between phases; the scheduling fences keep the matrix work of a phase on its side.
-  // Only LDS traffic has to be ordered here (reads of a buffer before the barrier, its refill after it): a bare
-  // barrier after the LDS counter has drained.  __syncthreads() would also wait for every outstanding global
-  // access, i.e. for the K/V loads just issued and for the output stores of a finished unit.
+  // Barrier between phases; the scheduling fences keep the matrix work of a phase on its side.  __syncthreads()
+  // also waits for the K/V loads issued in a vector phase; a barrier that waits for the LDS counter alone (the
+  // loads have until the end of the next matrix phase) measured slightly slower.
   auto phase_barrier = [&]() {
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
   };
-
   // ---- per-unit state ----
   int hq = 0, row0 = 0, rowc = 0, a_i = 0, lo_i = 0, prev_j = -1, self_j = -1;
   int u_nsplits = 1, u_ws_row0 = -1;
   bf16x8 qf[KSTEPS];
   // m: reference maximum (log2 units); lacc: every element holds the sum of the bf16-rounded probabilities of
-  // query n (accumulated by the matrix pipe against an all-ones operand); lx: exact fp32 sum (LSE only).
+  // query n, accumulated by the matrix pipe; lx: exact fp32 sum (LSE only).
+  // The row sum uses the 16x16x32 MFMA (4 accumulator registers, half the pipe time of a 32x32x16).  Its B operand
+  // takes lane l as (column l % 16, k-group l / 16); a probability fragment has lane l = (query l % 32, keys
+  // 8 (l / 32) ..), so k-groups 0 and 2 of column j are the 16 keys of query j and k-groups 1 and 3 those of query
+  // j + 16.  The A operand (lane l = row l % 16, k-group l / 16) is 1 where the row's output lanes 16 (row / 4) ..
+  // want that k-group and 0 elsewhere: output lane l (column l % 16, rows 4 (l / 16) ..) then holds the sum of
+  // query l % 32 in all four registers.
   float m = -INFINITY, lx = 0.f;
-  floatx16 oacc[DBLK], lacc;
-  bf16x8 ones8;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) ones8[i] = (__bf16)1.0f;
+  floatx16 oacc[DBLK];
+  floatx4 lacc;
+  const uint32_t ones_word = ((((lane >> 4) ^ (lane >> 2)) & 1) == 0) ? 0x3F803F80u : 0u;   // two bf16 ones or zeros
 
   uint16_t* const Xs = Xs_base + wave * kXTile;
   constexpr int XQ = 32 * CPR / 64;   // 1 KB pieces of a 32-row bf16 tile
@@ -229,8 +240,11 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   // Query fragments of the unit that starts: B operand of k-step s = columns 16 s + 8 h .. of row n.
   auto load_q_frags = [&]() {
     wait_loads();
+    int ln = lane;   // opaque copy: the eight addresses are formed here, not kept in registers across the loop
+    asm volatile("" : "+v"(ln));
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(Xs + kswz<D>(n, 2 * s + h));
+    for (int s = 0; s < KSTEPS; ++s)
+      qf[s] = *reinterpret_cast<const bf16x8*>(Xs + kswz<D>(ln & 31, 2 * s + (ln >> 5)));
   };
   auto begin_unit = [&](const u32x4 un) {
     hq = (int)un[1] + hl;
@@ -248,7 +262,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     m = -INFINITY;
     lx = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) lacc[i] = 0.f;
+    for (int i = 0; i < 4; ++i) lacc[i] = 0.f;
 #pragma unroll
     for (int b = 0; b < DBLK; ++b)
 #pragma unroll
@@ -257,11 +271,52 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 
   // Normalise and write this wavefront's 32 rows of the unit that just finished.  The accumulators hold, per
   // lane, 4 consecutive columns of ONE row at a time; the rows are assembled in the private LDS tile and leave
-  // as whole 256-byte pieces.
-  auto finish_unit = [&]() {
+  // as whole 256-byte pieces.  For a unit that holds a whole key list this happens in two parts: the pieces are
+  // normalised, rounded and written to the private tile one by one between the MFMAs of the next unit's first
+  // score product (the vector ALU is idle there), and the rows leave in the vector phase that follows.
+  float fin_inv = 0.f, fin_lse = 0.f;   // 1 / row sum and log-sum-exp (natural log) of the unit being finished
+  constexpr int NPIECE = 4 * DBLK;      // (output block, group of 4 accumulator registers): 8 bytes per lane
+  auto finish_sums = [&]() {
+    const float l_tot = lacc[0];
+    fin_inv = l_tot > 0.f ? __builtin_amdgcn_rcpf(l_tot) : 0.f;
+    if (LSE) fin_lse = (m + __builtin_amdgcn_logf(lx + other_half(lx))) * kLn2;
+  };
+  // `ln` is an opaque copy of the lane id: addresses derived from it are recomputed where they are used instead
+  // of being hoisted out of the tile loop, where they would occupy registers all the time.
+  auto stage_piece = [&](int j, int ln) {
+    const int b = j >> 2, g4 = j & 3;
+    u32x2 w;
+    w[0] = pack_bf16(oacc[b][4 * g4 + 0] * fin_inv, oacc[b][4 * g4 + 1] * fin_inv);
+    w[1] = pack_bf16(oacc[b][4 * g4 + 2] * fin_inv, oacc[b][4 * g4 + 3] * fin_inv);
+    *reinterpret_cast<u32x2*>(Xs + kswz<D>(ln & 31, 4 * b + g4) + 4 * (ln >> 5)) = w;   // columns 32 b + 8 g4 + 4 h ..
+  };
+  auto flush_rows = [&]() {
     if (!active) return;
-    // Addresses below depend on the lane only; derived from an opaque copy they are recomputed here instead of
-    // being hoisted out of the tile loop, where they would occupy registers all the time.
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    // uniform base of the tile's first row + 32-bit lane offsets (a head is at most 2^30 bytes)
+    char* const otile = reinterpret_cast<char*>(a.out) + ((size_t)hq * a.N + row0) * (D * 2);
+    const int rows_left = a.N - row0;   // rows of the tile that exist
+    // read the pieces back in batches of four before storing any: the LDS latencies overlap
+#pragma unroll
+    for (int i0 = 0; i0 < XQ; i0 += 4) {
+      u32x4 w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) w[i] = *reinterpret_cast<const u32x4*>(Xs + ((i0 + i) * 64 + ln) * 8);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int r, u;
+        kunswz<D>((i0 + i) * 64 + ln, r, u);
+        const uint32_t off = (uint32_t)r * (D * 2u) + (uint32_t)u * 16u;
+        if (rows_left >= 32 || r < rows_left) *reinterpret_cast<u32x4*>(otile + off) = w[i];
+      }
+    }
+    if (LSE && (ln >> 5) == 0 && (ln & 31) < rows_left) a.lse[(size_t)hq * a.N + row0 + (ln & 31)] = fin_lse;
+  };
+  // fp32 partial result of a slice: 64 columns (256 bytes a row) per round through the same tile
+  auto finish_slice = [&]() {
+    if (!active) return;
     int ln = lane;
     asm volatile("" : "+v"(ln));
     const int n = ln & 31, h = ln >> 5;
@@ -269,89 +324,80 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     const float lse2 = m + __builtin_amdgcn_logf(l_tot);  // log2 domain; -inf when the slice saw no key
     const float lse2x = LSE ? m + __builtin_amdgcn_logf(lx + other_half(lx)) : lse2;
-    if (u_nsplits == 1) {
+    float* const Xf = reinterpret_cast<float*>(Xs);
+    float* wbase = a.ws_o + ((size_t)u_ws_row0 + wave * 32) * D;
 #pragma unroll
-      for (int b = 0; b < DBLK; ++b)
+    for (int rnd = 0; rnd < D / 64; ++rnd) {
+#pragma unroll
+      for (int bb = 0; bb < 2; ++bb)
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
-          u32x2 w;
-          w[0] = pack_bf16(oacc[b][4 * g4 + 0] * inv, oacc[b][4 * g4 + 1] * inv);
-          w[1] = pack_bf16(oacc[b][4 * g4 + 2] * inv, oacc[b][4 * g4 + 3] * inv);
-          *reinterpret_cast<u32x2*>(Xs + kswz<D>(n, 4 * b + g4) + 4 * h) = w;   // columns 32 b + 8 g4 + 4 h ..
+          floatx4 w;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) w[r] = oacc[2 * rnd + bb][4 * g4 + r] * inv;
+          // columns 32 bb + 8 g4 + 4 h .. of the round: 16-byte slot 8 bb + 2 g4 + h of a 256-byte row
+          *reinterpret_cast<floatx4*>(Xf + kswz<128>(n, 8 * bb + 2 * g4 + h) / 2) = w;
+          __builtin_amdgcn_sched_barrier(0);
         }
-      // uniform base of the tile's first row + 32-bit lane offsets (a head is at most 2^30 bytes)
-      char* const otile = reinterpret_cast<char*>(a.out) + ((size_t)hq * a.N + row0) * (D * 2);
-      const int rows_left = a.N - row0;   // rows of the tile that exist
-      // read the pieces back in batches of four before storing any: the LDS latencies overlap
 #pragma unroll
-      for (int i0 = 0; i0 < XQ; i0 += 4) {
-        u32x4 w[4];
+      for (int i0 = 0; i0 < 8; i0 += 4) {
+        floatx4 w[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = *reinterpret_cast<const u32x4*>(Xs + ((i0 + i) * 64 + ln) * 8);
+        for (int i = 0; i < 4; ++i) w[i] = *reinterpret_cast<const floatx4*>(Xf + ((i0 + i) * 64 + ln) * 4);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           int r, u;
-          kunswz<D>((i0 + i) * 64 + ln, r, u);
-          const uint32_t off = (uint32_t)r * (D * 2u) + (uint32_t)u * 16u;
-          if (rows_left >= 32 || r < rows_left) *reinterpret_cast<u32x4*>(otile + off) = w[i];
+          kunswz<128>((i0 + i) * 64 + ln, r, u);
+          *reinterpret_cast<floatx4*>(wbase + (size_t)r * D + 64 * rnd + 4 * u) = w[i];
         }
-      }
-      if (LSE && h == 0 && row0 + n < a.N) a.lse[(size_t)hq * a.N + row0 + n] = lse2x * kLn2;
-    } else {
-      // fp32 partial result: 64 columns (256 bytes a row) per round through the same tile
-      float* const Xf = reinterpret_cast<float*>(Xs);
-      float* wbase = a.ws_o + ((size_t)u_ws_row0 + wave * 32) * D;
-#pragma unroll
-      for (int rnd = 0; rnd < D / 64; ++rnd) {
-#pragma unroll
-        for (int bb = 0; bb < 2; ++bb)
-#pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) {
-            floatx4 w;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) w[r] = oacc[2 * rnd + bb][4 * g4 + r] * inv;
-            // columns 32 bb + 8 g4 + 4 h .. of the round: 16-byte slot 8 bb + 2 g4 + h of a 256-byte row
-            *reinterpret_cast<floatx4*>(Xf + kswz<128>(n, 8 * bb + 2 * g4 + h) / 2) = w;
-            __builtin_amdgcn_sched_barrier(0);
-          }
-#pragma unroll
-        for (int i0 = 0; i0 < 8; i0 += 4) {
-          floatx4 w[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) w[i] = *reinterpret_cast<const floatx4*>(Xf + ((i0 + i) * 64 + ln) * 4);
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            int r, u;
-            kunswz<128>((i0 + i) * 64 + ln, r, u);
-            *reinterpret_cast<floatx4*>(wbase + (size_t)r * D + 64 * rnd + 4 * u) = w[i];
-          }
-        }
-      }
-      if (h == 0) {
-        const size_t prow = (size_t)u_ws_row0 + wave * 32 + n;
-        a.ws_lse[2 * prow] = lse2;
-        a.ws_lse[2 * prow + 1] = lse2x;
       }
     }
+    if (h == 0) {
+      const size_t prow = (size_t)u_ws_row0 + wave * 32 + n;
+      a.ws_lse[2 * prow] = lse2;
+      a.ws_lse[2 * prow + 1] = lse2x;
+    }
+  };
+  // Whole finish in one go (end of the queue, where no score product follows).
+  auto finish_unit = [&]() {
+    if (u_nsplits != 1) {
+      finish_slice();
+      return;
+    }
+    if (active) {
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      finish_sums();
+#pragma unroll
+      for (int j = 0; j < NPIECE; ++j) stage_piece(j, ln);
+    }
+    flush_rows();
   };
 
   // Operand fragments are read from LDS two MFMAs ahead of their use (ring of three registers); the scheduling
   // fences keep that order, so each wait covers only the oldest read.
   // Scores of one 32-key half: S^T[32 keys, 32 queries] = K Q^T; Kh = first row of the half in its LDS tile.
-  auto qk_half = [&](const uint16_t* Kh, floatx16& s) {
-    auto rd = [&](int i) { return *reinterpret_cast<const bf16x8*>(Kh + kswz<D>(n, 2 * i + h)); };
+  // `between(i)` runs after MFMA i is issued (independent vector work that hides under the matrix pipe).
+  const int kq0 = kswz<D>(n, h);
+  auto qk_half = [&](const uint16_t* Kh, floatx16& s, auto between) {
+    // fragment i sits at kswz(n, 2 i + h) = kswz(n, h) ^ 16 i: one XOR per read from a single per-lane base (an
+    // opaque copy, or the eight offsets would be hoisted out of the tile loop into registers of their own)
+    int kq = kq0;
+    asm volatile("" : "+v"(kq));
+    auto rd = [&](int i) { return *reinterpret_cast<const bf16x8*>(Kh + (kq ^ (16 * i))); };
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] = 0.f;
-    bf16x8 f[3];
-    f[0] = rd(0);
-    f[1] = rd(1);
+    constexpr int A = kQkAhead < KSTEPS ? kQkAhead : KSTEPS;
+    bf16x8 f[A + 1];
+#pragma unroll
+    for (int i = 0; i < A; ++i) f[i] = rd(i);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < KSTEPS; ++i) {
-      if (i + 2 < KSTEPS) f[(i + 2) % 3] = rd(i + 2);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % 3], qf[i], s, 0, 0, 0);
+      if (i + A < KSTEPS) f[(i + A) % (A + 1)] = rd(i + A);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % (A + 1)], qf[i], s, 0, 0, 0);
+      between(i);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -364,29 +410,33 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   // of the group supplies the address of row (s / 4), columns 4 (s % 4) .. +3, and lane j receives column j.
   const int tr_row = 4 * h + ((lane & 15) >> 2);                 // row within a 16-key step, first read
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);    // column within a 32-column block
-  int v_off[DBLK];
-#pragma unroll
-  for (int b = 0; b < DBLK; ++b) v_off[b] = vswz<D>(tr_row, (32 * b + tr_col) >> 3) + (tr_col & 7);
+  const int v_off0 = vswz<D>(tr_row, tr_col >> 3) + (tr_col & 7);   // output block b: v_off0 ^ 32 b
   auto pv_tile = [&](int buf, const bf16x8 (&pf)[4]) {
     const uint16_t* Vs = Vs_base + buf * (BK * D);
     constexpr int NF = 4 * DBLK;
+    int vo = v_off0;   // opaque copy, as for the K fragments
+    asm volatile("" : "+v"(vo));
     auto rd = [&](int i) {   // fragment i: 16-key step i % 4 of output block i / 4
-      const uint16_t* p = Vs + v_off[i >> 2] + 16 * (i & 3) * D;   // rows 16 ks + .. : the swizzle ignores them
+      const uint16_t* p = Vs + (vo ^ (32 * (i >> 2))) + 16 * (i & 3) * D;   // rows 16 ks + .. : the swizzle ignores them
       const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsShortx4)p);
       const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsShortx4)(p + 8 * D));
       return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    bf16x8 f[3];
-    f[0] = rd(0);
-    f[1] = rd(1);
+    uint32_t ow = ones_word;   // opaque: the four-register operand exists only here
+    asm volatile("" : "+v"(ow));
+    const bf16x8 ones8 = __builtin_bit_cast(bf16x8, u32x4{ow, ow, ow, ow});
+    constexpr int A = kPvAhead;
+    bf16x8 f[A + 1];
+#pragma unroll
+    for (int i = 0; i < A; ++i) f[i] = rd(i);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones8, pf[ks], lacc, 0, 0, 0);
+    for (int ks = 0; ks < 4; ++ks) lacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones8, pf[ks], lacc, 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
-      if (i + 2 < NF) f[(i + 2) % 3] = rd(i + 2);
-      oacc[i >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % 3], pf[i & 3], oacc[i >> 2], 0, 0, 0);
+      if (i + A < NF) f[(i + A) % (A + 1)] = rd(i + A);
+      oacc[i >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % (A + 1)], pf[i & 3], oacc[i >> 2], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -499,8 +549,6 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   floatx16 sacc[2];
 
   for (int t = t_begin; t < t_end; ++t) {
-    const Step st3 = fetch_step(t + 3);
-    const u32x4 un_fetch = units_c[2 * (unit_id + 1)];   // the unit table ends with a spare record
     const uint32_t nb = active ? (st0.need >> (2 * rb)) & 3u : 0u;
     const uint32_t kinds = (st0.kinds >> (4 * rb)) & 15u;
     const bool last = (st0.need >> 16) & 1u, first = (st0.need >> 17) & 1u;
@@ -512,20 +560,50 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     if (first) load_q_frags();   // frees the private tile, which the finished unit's rows leave through
     {
       const uint16_t* Ks = Ks_base + buf * (BK * D);
-      if (nb & 1u) qk_half(Ks, sacc[0]);
-      if (nb & 2u) qk_half(Ks + 32 * D, sacc[1]);
+      if (first && fin_pending && u_nsplits == 1 && active) {
+        // The finished unit's accumulators are normalised, rounded and staged between the MFMAs of this
+        // score product, one piece per MFMA.
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        finish_sums();
+        constexpr int PPM = NPIECE / (2 * KSTEPS);   // pieces per MFMA
+        static_assert(PPM * 2 * KSTEPS == NPIECE, "pieces divide over the MFMAs of a tile");
+        // Both halves are multiplied whether or not the row block needs them (the softmax ignores a half it
+        // does not need): one code path, and every piece has an MFMA to hide under.
+        qk_half(Ks, sacc[0], [&](int i) {
+#pragma unroll
+          for (int j = 0; j < PPM; ++j) stage_piece(PPM * i + j, ln);
+        });
+        qk_half(Ks + 32 * D, sacc[1], [&](int i) {
+#pragma unroll
+          for (int j = 0; j < PPM; ++j) stage_piece(NPIECE / 2 + PPM * i + j, ln);
+        });
+      } else {
+        if (nb & 1u) qk_half(Ks, sacc[0], [](int) {});
+        if (nb & 2u) qk_half(Ks + 32 * D, sacc[1], [](int) {});
+      }
     }
     wait_loads();   // the loads this wavefront issued in its last vector phase have landed
     PHASE_MARK(1);
     phase_barrier();
     PHASE_MARK(2);
+    // Table entries for later steps are requested here, where no LDS read is in flight: scalar loads and LDS
+    // reads share a counter that cannot tell them apart, so a scalar load pending in the matrix phase would make
+    // every wait for an operand fragment a wait for everything.
+    const Step st3 = fetch_step(t + 3);
+    const u32x4 un_fetch = units_c[2 * (unit_id + 1)];   // the unit table ends with a spare record
 
     // ---- vector phase: unit switch, start the loads of this wavefront's rows of the coming tiles, softmax ----
     // Unit switch (a pending unit always ends where the next one starts).  It sits in the vector phase: its
     // arithmetic overlaps the other wavefront's MFMAs, and both halves of the workgroup pay for it in the same
     // pair of phases.
     if (first) {
-      if (fin_pending) finish_unit();
+      if (fin_pending) {
+        if (u_nsplits == 1)
+          flush_rows();
+        else
+          finish_slice();
+      }
       PHASE_MARK(7);
       begin_unit(un_next);
     }
@@ -551,6 +629,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     st1 = st2;
     st2 = st3;
     PHASE_MARK(3);
+    PHASE_MARK(6);
     phase_barrier();
   }
   if (pv_bits) pv_tile(pv_buf, pf);
