@@ -68,8 +68,8 @@ def profiled_traffic_bytes():
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="qwen25vl_32f")
     ap.add_argument("--ratio", type=float, default=0.2)
     ap.add_argument("--batched-layers", type=int, default=26, help="layers per batched top-k/compaction launch")

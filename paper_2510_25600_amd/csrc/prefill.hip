@@ -18,16 +18,19 @@
 // product applies, so each output row is a true convex combination of V rows.  It comes from the matrix pipe
 // as well: one more MFMA per 16 keys multiplies the probabilities by an all-ones operand.
 //
-// Two-phase schedule.  Wavefronts w and w+4 share a SIMD.  A step of a wavefront is a matrix phase (second
-// product of the previous tile, score product of this tile) and a vector phase (mask, maximum, exponentials,
-// issue of the K/V loads), separated by workgroup barriers.  Wavefronts 4-7 run one phase behind wavefronts
-// 0-3, so on every SIMD one wavefront is in its matrix phase while the other is in its vector phase and the
-// two pipes overlap without relying on instruction scheduling inside a wavefront.
+// Software pipeline inside every wavefront.  One iteration handles the score product of tile j and the second
+// product of tile j-1: the exponentials of tile j-1 sit between the MFMAs of the score product, the running
+// maximum of tile j and the address arithmetic of the next K/V loads between the MFMAs of the second product
+// (scheduling fences pin every MFMA and the vector work behind it).  A wavefront thus keeps the matrix pipe and
+// the vector ALU busy at the same time, the two wavefronts of a SIMD fill each other's gaps, and the workgroup
+// meets at one barrier per tile, where the K/V buffers change hands.  The reference maximum of the online
+// softmax moves lazily; when it does, the accumulators are rescaled at the top of the next iteration, after the
+// second product that was still running in the old units.
 //
-// K and V each rotate through three LDS buffers.  In the vector phase of its step t a leading wavefront starts
-// the loads of its rows of K tile t+2 and V tile t+1, a lagging wavefront (one phase later) those of K tile t+2
-// and V tile t+2: each targets a buffer whose last reader finished at least one barrier earlier, and every load
-// is waited for at the end of the issuing wavefront's next matrix phase, two barriers before its first reader.
+// K and V each rotate through three LDS buffers: iteration j reads K(j) and V(j-1) and starts the loads of K(j+2)
+// and V(j+1), whose buffers were last read in iteration j-1.  Every wavefront waits for its own loads at the top
+// of an iteration, before the barrier; the loads are written as assembly so that these are the only waits (the
+// compiler cannot tell which buffer a load of the builtin form fills and waits for all of them before LDS reads).
 #include "common.h"
 
 namespace purekv {
@@ -69,7 +72,12 @@ struct PrefillArgs {
 };
 
 #ifdef PUREKV_PHASE_TRACE
-#define PHASE_MARK(i)                                                                                  \
+#ifdef PUREKV_TRACE_ENDS_ONLY
+#define PHASE_MARK(i) if ((i) == 0 || (i) == 7) PHASE_MARK_(i)
+#else
+#define PHASE_MARK(i) PHASE_MARK_(i)
+#endif
+#define PHASE_MARK_(i)                                                                                  \
   if ((threadIdx.x & 63) == 0 && t - t_begin < 64)                                                     \
   a.trace[(((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 64 + (t - t_begin)) * 8 + (i)] = __builtin_readcyclecounter()
 #else
@@ -80,6 +88,16 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) shortx4* LdsShortx4;
 typedef __attribute__((address_space(3))) void* LdsPtr;
 typedef const __attribute__((address_space(1))) void* GlobalPtr;
+
+// 16 bytes per lane from global memory straight into LDS: lane l's piece lands at lds_base + 16 l, its source is
+// base + off (a 32-bit byte offset per lane).  Written as assembly so that every wait for these loads is the
+// kernel's own: the compiler does not know which LDS buffer a load of its builtin form targets and would wait
+// for ALL outstanding ones, the loads just issued for later tiles included, before any LDS read.
+// lds_base must be wave-uniform.
+__device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t off, const void* lds_ptr) {
+  const uint32_t lds_base = (uint32_t)(size_t)(LdsPtr)lds_ptr;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(off), "s"(base) : "memory");
+}
 
 // V tile [BK][D] bf16 in LDS, row-major; the transpose read of a 16-lane group touches 4 consecutive rows x 32
 // bytes, two such groups run side by side: XOR-ing the 32-byte pair index with the row's low bits keeps them on
@@ -130,12 +148,18 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int grp = wave >> 2;            // 0: leading wavefronts, 1: the ones that run one phase behind
   const int n = lane & 31, h = lane >> 5;
   const int rb = wave / a.Gs, hl = wave - rb * a.Gs;   // row block and stacked head of this wavefront
   const bool active = wave < a.Gs * a.R;
   const int t_begin = a.queue_begin[blockIdx.x], t_end = a.queue_begin[blockIdx.x + 1];
   if (t_begin >= t_end) return;
+#ifdef PUREKV_PHASE_TRACE
+  // development builds: shader-clock and constant-rate (100 MHz) time stamps at both ends of the workgroup
+  if (threadIdx.x == 0) {
+    a.trace[((size_t)blockIdx.x * 8 * 64 + 63) * 8 + 0] = __builtin_readcyclecounter();
+    a.trace[((size_t)blockIdx.x * 8 * 64 + 63) * 8 + 1] = __builtin_amdgcn_s_memrealtime();
+  }
+#endif
 
   // ---- load maps (per-thread constants) ----
   // Load i of this wavefront fills 16-byte positions (NLD*wave + i)*64 + lane of a tile: 1 KB of LDS, contiguous
@@ -162,8 +186,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const uint32_t off = s.kv_off + (uint32_t)min(k_row[i], rv) * (D * 2u) + k_col[i];
-      __builtin_amdgcn_global_load_lds((GlobalPtr)(k_bytes + off),
-                                       (LdsPtr)(Ks_base + buf * (BK * D) + (NLD * wave + i) * 512), 16, 0, 0);
+      load_to_lds_16(k_bytes, off, Ks_base + buf * (BK * D) + (NLD * wave + i) * 512);
     }
   };
   auto issue_v = [&](const Step& s, int buf) {
@@ -171,8 +194,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const uint32_t off = s.kv_off + (uint32_t)min(v_row[i], rv) * (D * 2u) + v_col[i];
-      __builtin_amdgcn_global_load_lds((GlobalPtr)(v_bytes + off),
-                                       (LdsPtr)(Vs_base + buf * (BK * D) + (NLD * wave + i) * 512), 16, 0, 0);
+      load_to_lds_16(v_bytes, off, Vs_base + buf * (BK * D) + (NLD * wave + i) * 512);
     }
   };
   // All loads of this wavefront have written LDS (vmcnt == 0; the other counters are left alone).
@@ -191,14 +213,6 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     return s;
   };
   auto next_buf = [](int b) { return b == NBUF - 1 ? 0 : b + 1; };
-  // Barrier between phases; the scheduling fences keep the matrix work of a phase on its side.  __syncthreads()
-  // also waits for the K/V loads issued in a vector phase; a barrier that waits for the LDS counter alone (the
-  // loads have until the end of the next matrix phase) measured slightly slower.
-  auto phase_barrier = [&]() {
-    __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();
-    __builtin_amdgcn_sched_barrier(0);
-  };
   // ---- per-unit state ----
   int hq = 0, row0 = 0, rowc = 0, a_i = 0, lo_i = 0, prev_j = -1, self_j = -1;
   int u_nsplits = 1, u_ws_row0 = -1;
@@ -233,7 +247,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
         int r, u;
         kunswz<D>(i * 64 + ln, r, u);
         const uint32_t off = (uint32_t)min(r0 + r, a.N - 1) * (D * 2u) + (uint32_t)u * 16u;
-        __builtin_amdgcn_global_load_lds((GlobalPtr)(qhead + off), (LdsPtr)(Xs + i * 512), 16, 0, 0);
+        load_to_lds_16(qhead, off, Xs + i * 512);
       }
     }
   };
@@ -246,40 +260,17 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     for (int s = 0; s < KSTEPS; ++s)
       qf[s] = *reinterpret_cast<const bf16x8*>(Xs + kswz<D>(ln & 31, 2 * s + (ln >> 5)));
   };
-  auto begin_unit = [&](const u32x4 un) {
-    hq = (int)un[1] + hl;
-    u_nsplits = (int)un[2];
-    u_ws_row0 = (int)un[3];
-    row0 = (int)un[0] + rb * 32;
-    rowc = min(row0 + n, a.N - 1);
-    // allowed keys of this lane's row: j <= rowc and (j <= a_i or j >= lo_i or j == prev_j or j == self_j)
-    const bool sparse_row = ST && a.pattern != 0u && rowc < a.Nv;
-    const int frame = sparse_row ? rowc / a.P : 0;
-    a_i = sparse_row ? min(rowc, a.P - 1) : rowc;
-    lo_i = sparse_row ? ((a.pattern & 1u) ? frame * a.P : rowc + 1) : 0;
-    prev_j = (sparse_row && (a.pattern & 2u) && frame >= 1) ? rowc - a.P : -1;
-    self_j = (sparse_row && (a.pattern & 2u)) ? rowc : -1;
-    m = -INFINITY;
-    lx = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) lacc[i] = 0.f;
-#pragma unroll
-    for (int b = 0; b < DBLK; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
-  };
-
   // Normalise and write this wavefront's 32 rows of the unit that just finished.  The accumulators hold, per
   // lane, 4 consecutive columns of ONE row at a time; the rows are assembled in the private LDS tile and leave
-  // as whole 256-byte pieces.  For a unit that holds a whole key list this happens in two parts: the pieces are
-  // normalised, rounded and written to the private tile one by one between the MFMAs of the next unit's first
-  // score product (the vector ALU is idle there), and the rows leave in the vector phase that follows.
+  // as whole 256-byte pieces (a version that stored 8-byte pieces per lane straight from the accumulator layout
+  // produced 1024 partial-line writes per wavefront and cost several thousand cycles per unit).
   float fin_inv = 0.f, fin_lse = 0.f;   // 1 / row sum and log-sum-exp (natural log) of the unit being finished
+  float m_fin = -INFINITY;              // its reference maximum
   constexpr int NPIECE = 4 * DBLK;      // (output block, group of 4 accumulator registers): 8 bytes per lane
   auto finish_sums = [&]() {
     const float l_tot = lacc[0];
     fin_inv = l_tot > 0.f ? __builtin_amdgcn_rcpf(l_tot) : 0.f;
-    if (LSE) fin_lse = (m + __builtin_amdgcn_logf(lx + other_half(lx))) * kLn2;
+    if (LSE) fin_lse = (m_fin + __builtin_amdgcn_logf(lx + other_half(lx))) * kLn2;
   };
   // `ln` is an opaque copy of the lane id: addresses derived from it are recomputed where they are used instead
   // of being hoisted out of the tile loop, where they would occupy registers all the time.
@@ -322,8 +313,8 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     const int n = ln & 31, h = ln >> 5;
     const float l_tot = lacc[0];
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    const float lse2 = m + __builtin_amdgcn_logf(l_tot);  // log2 domain; -inf when the slice saw no key
-    const float lse2x = LSE ? m + __builtin_amdgcn_logf(lx + other_half(lx)) : lse2;
+    const float lse2 = m_fin + __builtin_amdgcn_logf(l_tot);  // log2 domain; -inf when the slice saw no key
+    const float lse2x = LSE ? m_fin + __builtin_amdgcn_logf(lx + other_half(lx)) : lse2;
     float* const Xf = reinterpret_cast<float*>(Xs);
     float* wbase = a.ws_o + ((size_t)u_ws_row0 + wave * 32) * D;
 #pragma unroll
@@ -359,7 +350,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
       a.ws_lse[2 * prow + 1] = lse2x;
     }
   };
-  // Whole finish in one go (end of the queue, where no score product follows).
+  // Finish of a unit that holds a whole key list: normalise, round, stage, store.
   auto finish_unit = [&]() {
     if (u_nsplits != 1) {
       finish_slice();
@@ -375,8 +366,8 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     flush_rows();
   };
 
-  // Operand fragments are read from LDS two MFMAs ahead of their use (ring of three registers); the scheduling
-  // fences keep that order, so each wait covers only the oldest read.
+  // Operand fragments are read from LDS a few MFMAs ahead of their use (register ring); the scheduling fences
+  // keep that order, so each wait covers only the oldest read.
   // Scores of one 32-key half: S^T[32 keys, 32 queries] = K Q^T; Kh = first row of the half in its LDS tile.
   // `between(i)` runs after MFMA i is issued (independent vector work that hides under the matrix pipe).
   const int kq0 = kswz<D>(n, h);
@@ -384,7 +375,6 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     // fragment i sits at kswz(n, 2 i + h) = kswz(n, h) ^ 16 i: one XOR per read from a single per-lane base (an
     // opaque copy, or the eight offsets would be hoisted out of the tile loop into registers of their own)
     int kq = kq0;
-    asm volatile("" : "+v"(kq));
     auto rd = [&](int i) { return *reinterpret_cast<const bf16x8*>(Kh + (kq ^ (16 * i))); };
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] = 0.f;
@@ -411,7 +401,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   const int tr_row = 4 * h + ((lane & 15) >> 2);                 // row within a 16-key step, first read
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);    // column within a 32-column block
   const int v_off0 = vswz<D>(tr_row, tr_col >> 3) + (tr_col & 7);   // output block b: v_off0 ^ 32 b
-  auto pv_tile = [&](int buf, const bf16x8 (&pf)[4]) {
+  auto pv_tile = [&](int buf, const bf16x8 (&pf)[4], auto between) {
     const uint16_t* Vs = Vs_base + buf * (BK * D);
     constexpr int NF = 4 * DBLK;
     int vo = v_off0;   // opaque copy, as for the K fragments
@@ -437,6 +427,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     for (int i = 0; i < NF; ++i) {
       if (i + A < NF) f[(i + A) % (A + 1)] = rd(i + A);
       oacc[i >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % (A + 1)], pf[i & 3], oacc[i >> 2], 0, 0, 0);
+      between(i);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -463,178 +454,249 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
       }
     }
   };
-  auto max_block = [&](const floatx16& s, float mt) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) mt = fmaxf(mt, s[i]);
-    return mt;
+  // ---- software pipeline inside every wavefront ----
+  // Iteration j: the score product of tile j with the exponentials of tile j-1 between its MFMAs, then the second
+  // product of tile j-1 with the running maximum of tile j between its MFMAs.  A wavefront keeps its own matrix
+  // pipe and vector ALU busy at the same time, and the two wavefronts of a SIMD fill each other's gaps; the
+  // workgroup meets once per tile, where the K/V buffers change hands.
+  // K tile x and V tile x live in ring buffer (x - t_begin) % 3.  Iteration j reads K(j) and V(j-1) and starts the
+  // loads of K(j+2) and V(j+1): their buffers were last read in iteration j-1, which every wavefront has left when
+  // it passes the barrier at the top of iteration j.
+  floatx16 S[2][2];   // scores of two consecutive tiles, two 32-key halves each
+  bf16x8 pf[4];       // probabilities of the tile whose second product comes next
+  float alpha = 1.f;  // pending rescale of the accumulators (the reference maximum moved)
+  bool resc = false;
+  int q_hq = 0, q_row0 = 0, q_nsplits = 1, q_ws_row0 = -1;   // unit of the tile on the score side
+  auto begin_qk_unit = [&](const u32x4 un) {
+    q_hq = (int)un[1] + hl;
+    q_nsplits = (int)un[2];
+    q_ws_row0 = (int)un[3];
+    q_row0 = (int)un[0] + rb * 32;
+    rowc = min(q_row0 + n, a.N - 1);
+    const bool sparse_row = ST && a.pattern != 0u && rowc < a.Nv;
+    const int frame = sparse_row ? rowc / a.P : 0;
+    a_i = sparse_row ? min(rowc, a.P - 1) : rowc;
+    lo_i = sparse_row ? ((a.pattern & 1u) ? frame * a.P : rowc + 1) : 0;
+    prev_j = (sparse_row && (a.pattern & 2u) && frame >= 1) ? rowc - a.P : -1;
+    self_j = (sparse_row && (a.pattern & 2u)) ? rowc : -1;
   };
-  // Probabilities of one block -> two bf16 B-operand fragments (16 keys each).
-  auto exp_block = [&](const floatx16& s, float neg_m, bf16x8& p0, bf16x8& p1) {
+  auto adopt_unit = [&]() {   // the second-product side moves on to the unit of the score side
+    hq = q_hq;
+    row0 = q_row0;
+    u_nsplits = q_nsplits;
+    u_ws_row0 = q_ws_row0;
+    lx = 0.f;
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      u32x4 pk;
+    for (int i = 0; i < 4; ++i) lacc[i] = 0.f;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * half + 2 * w], a.scale_log2, neg_m));
-        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * half + 2 * w + 1], a.scale_log2, neg_m));
-        if (LSE) lx += e0 + e1;
-        pk[w] = pack_bf16(e0, e1);
-      }
-      if (half == 0)
-        p0 = __builtin_bit_cast(bf16x8, pk);
-      else
-        p1 = __builtin_bit_cast(bf16x8, pk);
-    }
+    for (int b = 0; b < DBLK; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
   };
-  // Mask, running maximum, exponentials of the needed halves (bits nb) of one tile; pf[ks] covers keys
-  // 16*ks .. 16*ks+15 of the tile.
-  auto softmax_tile = [&](floatx16 (&sacc)[2], bf16x8 (&pf)[4], uint32_t nb, uint32_t kinds, int k0) {
-    float mt = -INFINITY;
-    if (nb & 1u) {
-      mask_block(sacc[0], kinds & 3u, k0);
-      mt = max_block(sacc[0], mt);
-    }
-    if (nb & 2u) {
-      mask_block(sacc[1], (kinds >> 2) & 3u, k0 + 32);
-      mt = max_block(sacc[1], mt);
-    }
+  auto fill_ninf = [&](floatx16& x) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) x[i] = -INFINITY;
+  };
+  // Slice i of 16: probabilities of elements 2 w, 2 w + 1 (w = i % 8) of half i / 8 -> one word of pf.
+  auto exp_slice = [&](const floatx16 (&Sp)[2], float neg_m, int i) {
+    const int hf = i >> 3, w = i & 7;
+    // The multiply-adds are volatile: the whole slice stays where it is called (between two MFMAs) instead of
+    // being collected ahead of the product.
+    float y0, y1;
+    asm volatile("v_fma_f32 %0, %2, %3, %4\n\tv_fma_f32 %1, %5, %3, %4"
+                 : "=&v"(y0), "=&v"(y1)
+                 : "v"(Sp[hf][2 * w]), "s"(a.scale_log2), "v"(neg_m), "v"(Sp[hf][2 * w + 1]));
+    const float e0 = __builtin_amdgcn_exp2f(y0);
+    const float e1 = __builtin_amdgcn_exp2f(y1);
+    if (LSE) lx += e0 + e1;
+    u32x4 pk = __builtin_bit_cast(u32x4, pf[2 * hf + (w >> 2)]);
+    pk[w & 3] = pack_bf16(e0, e1);
+    pf[2 * hf + (w >> 2)] = __builtin_bit_cast(bf16x8, pk);
+  };
+  auto max_slice = [&](const floatx16 (&Sn)[2], float& mt, int i) {
+    const int hf = i >> 3, w = i & 7;
+    mt = fmaxf(fmaxf(mt, Sn[hf][2 * w]), Sn[hf][2 * w + 1]);
+  };
+  // New reference maximum after a tile whose (masked) maximum is mt; `first`: the tile starts a unit.
+  auto update_reference = [&](float mt, bool first) {
     mt = fmaxf(mt, other_half(mt)) * a.scale_log2;
-    // The reference maximum m only moves when a tile exceeds it by more than kRescaleGap (log2 units):
-    // probabilities then stay below 2^kRescaleGap, exact in fp32/bf16 range, and the accumulators are
-    // rescaled rarely.  The final normalisation divides the same factor out again.
+    m_fin = m;
+    if (first) m = -INFINITY;
+    // The reference only moves when a tile exceeds it by more than kRescaleGap (log2 units): probabilities stay
+    // below 2^kRescaleGap and the accumulators are rescaled rarely (before the next second product).
     if (__any(mt > m + kRescaleGap)) {
       const float m_new = (mt > m + kRescaleGap) ? mt : m;
       const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m - m_ref);
+      alpha = __builtin_amdgcn_exp2f(m - m_ref);
+      resc = !first;   // a unit that starts has nothing accumulated yet
+      m = m_new;
+    }
+  };
+
+  Step e_prev = fetch_step(t_begin), e_cur = fetch_step(t_begin + 1), e_n1 = fetch_step(t_begin + 2),
+       e_n2 = fetch_step(t_begin + 3);
+  int unit_id = a.queue_unit0[blockIdx.x];
+  u32x4 un_next = units_c[2 * unit_id];   // the first entry of a queue always starts a unit
+  bool q_pref = false;
+  // Query rows of the next unit: requested one tile before the current unit's last one when it has that many
+  // (x: index of the tile on the score side, ex / ex1: its entry and the next one), and never before the rows of
+  // a unit finished in the same iteration have left the private tile.
+  auto maybe_prefetch_q = [&](int x, const Step& ex, const Step& ex1, const u32x4 un_rec) {
+    if (q_pref || x >= t_end) return;
+    const bool lastc = (ex.need >> 16) & 1u;
+    const bool lastn = x + 1 < t_end && ((ex1.need >> 16) & 1u);
+    const int s_next = lastc ? x + 1 : x + 2;   // first entry of the next unit
+    if ((lastc || lastn) && s_next < t_end) {
+      un_next = un_rec;
+      __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): every read of the private tile has returned
+      prefetch_q(un_next);
+      q_pref = true;
+    }
+  };
+  prefetch_q(un_next);
+  issue_k(e_prev, 0);
+  issue_v(e_prev, 0);
+  if (t_begin + 1 < t_end) {
+    issue_k(e_cur, 1);
+    issue_v(e_cur, 1);
+  }
+  if (t_begin + 2 < t_end) issue_k(e_n1, 2);
+  load_q_frags();
+  begin_qk_unit(un_next);
+  adopt_unit();
+  maybe_prefetch_q(t_begin, e_prev, e_cur, units_c[2 * (unit_id + 1)]);
+  __syncthreads();
+  // scores and reference maximum of the first tile
+  if (active) {
+    const uint32_t nb = (e_prev.need >> (2 * rb)) & 3u, kinds = (e_prev.kinds >> (4 * rb)) & 15u;
+    if (nb & 1u) {
+      qk_half(Ks_base, S[0][0], [](int) {});
+      mask_block(S[0][0], kinds & 3u, e_prev.k0);
+    } else {
+      fill_ninf(S[0][0]);
+    }
+    if (nb & 2u) {
+      qk_half(Ks_base + 32 * D, S[0][1], [](int) {});
+      mask_block(S[0][1], (kinds >> 2) & 3u, e_prev.k0 + 32);
+    } else {
+      fill_ninf(S[0][1]);
+    }
+    float mt = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) max_slice(S[0], mt, i);
+    update_reference(mt, true);
+  }
+
+  int bj = 1;   // ring buffer of tile j
+  // One iteration; Sn receives the scores of tile j, Sp holds those of tile j-1.
+  auto iteration = [&](int j, floatx16 (&Sn)[2], floatx16 (&Sp)[2]) {
+    const bool have = j < t_end;
+    const uint32_t nb = (have && active) ? (e_cur.need >> (2 * rb)) & 3u : 0u;
+    const uint32_t kinds = (e_cur.kinds >> (4 * rb)) & 15u;
+    const bool first = have && ((e_cur.need >> 17) & 1u);
+    const bool lastp = (e_prev.need >> 16) & 1u;   // the unit of tile j-1 ends with it
+    const int b_next = next_buf(bj), b_prev = next_buf(b_next);
+    [[maybe_unused]] const int t = j - 1;   // index for the development trace
+    PHASE_MARK(0);
+    if (resc) {
       lacc[0] *= alpha;   // only element 0 is read back
       if (LSE) lx *= alpha;
 #pragma unroll
       for (int b = 0; b < DBLK; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
-      m = m_new;
+      resc = false;
     }
-    const float neg_m = (m == -INFINITY) ? 0.f : -m;
-    const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
-    if (nb & 1u)
-      exp_block(sacc[0], neg_m, pf[0], pf[1]);
-    else
-      pf[0] = pf[1] = zero8;
-    if (nb & 2u)
-      exp_block(sacc[1], neg_m, pf[2], pf[3]);
-    else
-      pf[2] = pf[3] = zero8;
-  };
-
-  // ---- pipeline fill: K tiles 0 and 1 and V tile 0 complete in LDS, the lagging wavefronts' rows of V tile 1 ----
-  Step st0 = fetch_step(t_begin), st1 = fetch_step(t_begin + 1), st2 = fetch_step(t_begin + 2);
-  int unit_id = a.queue_unit0[blockIdx.x];
-  u32x4 un_next = units_c[2 * unit_id];   // the first entry of a queue always starts a unit
-  prefetch_q(un_next);
-  issue_k(st0, 0);
-  issue_v(st0, 0);
-  if (t_begin + 1 < t_end) {
-    issue_k(st1, 1);
-    if (grp == 1) issue_v(st1, 1);
-  }
-  wait_loads();
-  __syncthreads();
-  if (grp == 1) phase_barrier();   // run one phase behind wavefronts 0-3
-
-  int buf = 0;                     // LDS buffer of tile t
-  int pv_buf = 0;
-  uint32_t pv_bits = 0;            // halves of the previous tile whose probabilities wait for the second product
-  bool fin_pending = false;
-  bf16x8 pf[4];
-  floatx16 sacc[2];
-
-  for (int t = t_begin; t < t_end; ++t) {
-    const uint32_t nb = active ? (st0.need >> (2 * rb)) & 3u : 0u;
-    const uint32_t kinds = (st0.kinds >> (4 * rb)) & 15u;
-    const bool last = (st0.need >> 16) & 1u, first = (st0.need >> 17) & 1u;
-
-    // ---- matrix phase: second product of the previous tile, score product of this tile ----
-    PHASE_MARK(0);
-    if (pv_bits) pv_tile(pv_buf, pf);
-    PHASE_MARK(4);
-    if (first) load_q_frags();   // frees the private tile, which the finished unit's rows leave through
-    {
-      const uint16_t* Ks = Ks_base + buf * (BK * D);
-      if (first && fin_pending && u_nsplits == 1 && active) {
-        // The finished unit's accumulators are normalised, rounded and staged between the MFMAs of this
-        // score product, one piece per MFMA.
-        int ln = lane;
-        asm volatile("" : "+v"(ln));
-        finish_sums();
-        constexpr int PPM = NPIECE / (2 * KSTEPS);   // pieces per MFMA
-        static_assert(PPM * 2 * KSTEPS == NPIECE, "pieces divide over the MFMAs of a tile");
-        // Both halves are multiplied whether or not the row block needs them (the softmax ignores a half it
-        // does not need): one code path, and every piece has an MFMA to hide under.
-        qk_half(Ks, sacc[0], [&](int i) {
+    const float neg_m = (m == -INFINITY) ? 0.f : -m;   // m: reference after tile j-1, until this tile's maximum is in
+    if (first) {
+      load_q_frags();   // frees the private tile, which the finished unit's rows leave through
+      ++unit_id;
+      q_pref = false;
+      begin_qk_unit(un_next);
+    }
+    // Table entries for later tiles are requested before the barrier, which then also covers their latency:
+    // scalar loads and LDS reads share a counter that cannot tell them apart, so a scalar load still pending
+    // during a product would turn every wait for an operand fragment into a wait for everything.
+    const Step e_f = fetch_step(j + 3);
+    const u32x4 un_fetch = units_c[2 * (unit_id + 1)];   // the unit table ends with a spare record
+    wait_loads();
+    PHASE_MARK(1);
+    __syncthreads();
+    PHASE_MARK(2);
+    // The loads of K(j+2) and V(j+1) are started between the MFMAs of the second product below (their address
+    // arithmetic hides there); a wavefront without rows of its own starts them here.
+    if (!active) {
+      if (j + 2 < t_end) issue_k(e_n2, b_prev);
+      if (j + 1 < t_end) issue_v(e_n1, b_next);
+    }
+    PHASE_MARK(3);
+    if (active) {
+      // ---- score product of tile j, exponentials of tile j-1 ----
+      constexpr int SPM = 8 / KSTEPS;   // slices per MFMA
+      const uint16_t* Ks = Ks_base + bj * (BK * D);
+      if (nb & 1u) {
+        qk_half(Ks, Sn[0], [&](int i) {
 #pragma unroll
-          for (int j = 0; j < PPM; ++j) stage_piece(PPM * i + j, ln);
-        });
-        qk_half(Ks + 32 * D, sacc[1], [&](int i) {
-#pragma unroll
-          for (int j = 0; j < PPM; ++j) stage_piece(NPIECE / 2 + PPM * i + j, ln);
+          for (int q = 0; q < SPM; ++q) exp_slice(Sp, neg_m, SPM * i + q);
         });
       } else {
-        if (nb & 1u) qk_half(Ks, sacc[0], [](int) {});
-        if (nb & 2u) qk_half(Ks + 32 * D, sacc[1], [](int) {});
+        fill_ninf(Sn[0]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) exp_slice(Sp, neg_m, i);
       }
-    }
-    wait_loads();   // the loads this wavefront issued in its last vector phase have landed
-    PHASE_MARK(1);
-    phase_barrier();
-    PHASE_MARK(2);
-    // Table entries for later steps are requested here, where no LDS read is in flight: scalar loads and LDS
-    // reads share a counter that cannot tell them apart, so a scalar load pending in the matrix phase would make
-    // every wait for an operand fragment a wait for everything.
-    const Step st3 = fetch_step(t + 3);
-    const u32x4 un_fetch = units_c[2 * (unit_id + 1)];   // the unit table ends with a spare record
-
-    // ---- vector phase: unit switch, start the loads of this wavefront's rows of the coming tiles, softmax ----
-    // Unit switch (a pending unit always ends where the next one starts).  It sits in the vector phase: its
-    // arithmetic overlaps the other wavefront's MFMAs, and both halves of the workgroup pay for it in the same
-    // pair of phases.
-    if (first) {
-      if (fin_pending) {
+      if (nb & 2u) {
+        qk_half(Ks + 32 * D, Sn[1], [&](int i) {
+#pragma unroll
+          for (int q = 0; q < SPM; ++q) exp_slice(Sp, neg_m, 8 + SPM * i + q);
+        });
+      } else {
+        fill_ninf(Sn[1]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) exp_slice(Sp, neg_m, 8 + i);
+      }
+      PHASE_MARK(4);
+      // ---- second product of tile j-1, running maximum of tile j ----
+      if (nb & 1u) mask_block(Sn[0], kinds & 3u, e_cur.k0);
+      if (nb & 2u) mask_block(Sn[1], (kinds >> 2) & 3u, e_cur.k0 + 32);
+      float mt = -INFINITY;
+      constexpr int MPM = 16 / (4 * DBLK);   // maximum slices per MFMA
+      pv_tile(b_prev, pf, [&](int i) {
+#pragma unroll
+        for (int q = 0; q < MPM; ++q) max_slice(Sn, mt, MPM * i + q);
+        if (i == 1 && j + 2 < t_end) issue_k(e_n2, b_prev);
+        if (i == 3 && j + 1 < t_end) issue_v(e_n1, b_next);
+      });
+      update_reference(mt, first);
+      PHASE_MARK(5);
+      if (lastp) {
         if (u_nsplits == 1)
-          flush_rows();
+          finish_unit();
         else
           finish_slice();
+        adopt_unit();
       }
-      PHASE_MARK(7);
-      begin_unit(un_next);
     }
-    const int b1 = next_buf(buf), b2 = next_buf(b1);
-    if (t + 2 < t_end) issue_k(st2, b2);
-    if (grp == 0) {
-      if (t + 1 < t_end) issue_v(st1, b1);
-    } else {
-      if (t + 2 < t_end) issue_v(st2, b2);
-    }
-    if (last && t + 1 < t_end) {   // the next entry starts a unit: its query rows travel while this one is finished
-      un_next = un_fetch;
-      ++unit_id;
-      prefetch_q(un_next);
-    }
-    PHASE_MARK(5);
-    if (nb) softmax_tile(sacc, pf, nb, kinds, st0.k0);
-    pv_bits = nb;
-    pv_buf = buf;
-    fin_pending = last;
-    buf = b1;
-    st0 = st1;
-    st1 = st2;
-    st2 = st3;
-    PHASE_MARK(3);
     PHASE_MARK(6);
-    phase_barrier();
+    maybe_prefetch_q(j, e_cur, e_n1, un_fetch);
+    PHASE_MARK(7);
+    bj = b_next;
+    e_prev = e_cur;
+    e_cur = e_n1;
+    e_n1 = e_n2;
+    e_n2 = e_f;
+  };
+  for (int j = t_begin + 1;; j += 2) {
+    iteration(j, S[1], S[0]);
+    if (j == t_end) break;
+    iteration(j + 1, S[0], S[1]);
+    if (j + 1 == t_end) break;
   }
-  if (pv_bits) pv_tile(pv_buf, pf);
-  if (fin_pending) finish_unit();
-  if (grp == 0) phase_barrier();   // matches the extra barrier the lagging wavefronts took at the start
+#ifdef PUREKV_PHASE_TRACE
+  if (threadIdx.x == 0) {
+    a.trace[((size_t)blockIdx.x * 8 * 64 + 63) * 8 + 2] = __builtin_readcyclecounter();
+    a.trace[((size_t)blockIdx.x * 8 * 64 + 63) * 8 + 3] = __builtin_amdgcn_s_memrealtime();
+  }
+#endif
 }
 
 // Combines the partial results of a query tile whose key list was cut into slices.  One workgroup
