@@ -71,6 +71,10 @@ struct PrefillArgs {
 #endif
 };
 
+// Development builds only (PUREKV_PHASE_TRACE): cycle stamps at eight points of an iteration, or at its two ends
+// (PUREKV_TRACE_ENDS_ONLY).  A stamp is a counter read plus a global store; the store is one more access the
+// wait at the top of the next iteration covers, so stamped iterations run several hundred cycles longer each
+// than unstamped ones: good for comparing segments, not for absolute times.
 #ifdef PUREKV_PHASE_TRACE
 #ifdef PUREKV_TRACE_ENDS_ONLY
 #define PHASE_MARK(i) if ((i) == 0 || (i) == 7) PHASE_MARK_(i)
@@ -87,7 +91,6 @@ struct PrefillArgs {
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) shortx4* LdsShortx4;
 typedef __attribute__((address_space(3))) void* LdsPtr;
-typedef const __attribute__((address_space(1))) void* GlobalPtr;
 
 // 16 bytes per lane from global memory straight into LDS: lane l's piece lands at lds_base + 16 l, its source is
 // base + off (a 32-bit byte offset per lane).  Written as assembly so that every wait for these loads is the
