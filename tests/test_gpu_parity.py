@@ -42,6 +42,17 @@ SMALL = {
     # 12 query heads per KV head: two groups of 6 stacked heads
     "heads12_2f": small_variant("heads12_2f", n_frames=2, patch_h=12, patch_w=12, n_text=33, n_q_heads=12,
                                 n_kv_heads=1, head_dim=128),
+    # More units than workgroups, so that queues hold several units and every unit switch (output of the finished
+    # unit, query prefetch, state reset) is compared exhaustively, not on sampled rows as in the full-size tests:
+    # 7 stacked heads x 1 row block, P = 272 straddles key tiles (91 query tiles x 6 head groups: up to three units a queue)
+    "manyunits_g7": small_variant("manyunits_g7", n_frames=10, patch_h=16, patch_w=17, n_text=190, n_q_heads=42,
+                                  n_kv_heads=6, head_dim=128),
+    # 2 stacked heads x 4 row blocks (18 query tiles x 16 head groups), d = 64
+    "manyunits_g2": small_variant("manyunits_g2", n_frames=7, patch_h=15, patch_w=20, n_text=120, n_q_heads=32,
+                                  n_kv_heads=16, head_dim=64),
+    # one head x 8 row blocks (5 query tiles x 64 heads), d = 64
+    "manyunits_g1": small_variant("manyunits_g1", n_frames=4, patch_h=16, patch_w=16, n_text=100, n_q_heads=64,
+                                  n_kv_heads=64, head_dim=64),
 }
 
 
@@ -64,6 +75,9 @@ def test_prefill_matches_oracle(name, pattern):
     assert np.abs(f64_of(lse) - ref_lse).max() < 2e-3
     if name == "longtext_2f":
         assert plan.counts()["n_split_qtiles"] > 0  # the merge path ran
+    if name.startswith("manyunits"):
+        c = plan.counts()
+        assert max(len(plan.queue(g)) for g in range(c["n_workgroups"])) >= 2  # some queue switches units
 
 
 def test_prefill_is_deterministic_and_output_buffer_reuse():
