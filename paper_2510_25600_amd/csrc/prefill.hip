@@ -72,11 +72,13 @@ struct PrefillArgs {
 };
 
 // Development builds only (PUREKV_PHASE_TRACE): cycle stamps at eight points of an iteration, or at its two ends
-// (PUREKV_TRACE_ENDS_ONLY).  A stamp is a counter read plus a global store; the store is one more access the
+// (PUREKV_TRACE_ENDS_ONLY), or only at the two ends of a workgroup (PUREKV_TRACE_WORKGROUP_ONLY).  A stamp is a counter read plus a global store; the store is one more access the
 // wait at the top of the next iteration covers, so stamped iterations run several hundred cycles longer each
 // than unstamped ones: good for comparing segments, not for absolute times.
 #ifdef PUREKV_PHASE_TRACE
-#ifdef PUREKV_TRACE_ENDS_ONLY
+#if defined(PUREKV_TRACE_WORKGROUP_ONLY)   // only the stamps at both ends of a workgroup
+#define PHASE_MARK(i)
+#elif defined(PUREKV_TRACE_ENDS_ONLY)
 #define PHASE_MARK(i) if ((i) == 0 || (i) == 7) PHASE_MARK_(i)
 #else
 #define PHASE_MARK(i) PHASE_MARK_(i)
