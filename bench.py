@@ -75,7 +75,7 @@ def main() -> int:
     ap.add_argument("--batched-layers", type=int, default=26, help="layers per batched top-k/compaction launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=28, help="query heads in the oracle's timed sample")
-    ap.add_argument("--only-stage", default=None, choices=STAGES + ["copy_calib", "topk_batched", "compact_batched"],
+    ap.add_argument("--only-stage", default=None, choices=STAGES + ["copy_calib", "topk_batched", "compact_batched", "mfma_calib"],
                     help="profiling aid: after one full warm-up step run only this stage --steps times and exit")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -150,6 +150,30 @@ def main() -> int:
         vc_all = torch.empty_like(kc_all)
         return v_all, k_all, idx_all, kc_all, vc_all
 
+    def mfma_calib(mix, random_operands, iters=40000):
+        """One warm launch (≈ 20 ms: long enough for the clock to settle), then one event-timed launch of the
+        board-calibration loop.  Returns (TFLOP/s, shader clock in GHz seen by wavefront 0)."""
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        pk.purekv_calib_mfma(st, mix, random_operands, iters)
+        torch.cuda.synchronize()
+        a.record()
+        flops, ticks = pk.purekv_calib_mfma(st, mix, random_operands, iters)
+        b.record()
+        torch.cuda.synchronize()
+        cyc, ref = (int(x) for x in ticks.tolist())
+        return flops / (a.elapsed_time(b) * 1e-3) / 1e12, cyc / max(ref, 1) / 10.0
+
+    if args.only_stage == "mfma_calib":
+        step()
+        torch.cuda.synchronize()
+        names = ["MFMA only", "MFMA + 1 KB LDS fragment read", "MFMA + LDS read + 2 fma + 2 exp + 1 convert"]
+        for rnd in (False, True):
+            for mix, name in enumerate(names):
+                tf, ghz = mfma_calib(mix, rnd)
+                print(f"{name:46s} {'random' if rnd else 'constant':8s} operands: {tf:7.1f} TFLOP/s at {ghz:.2f} GHz",
+                      flush=True)
+        return 0
+
     if args.only_stage is not None:
         step()
         torch.cuda.synchronize()
@@ -218,6 +242,9 @@ def main() -> int:
     comp_b_ms = time_calls(lambda: pk.purekv_kv_compact(st, k_all, v_all, idx_all, kc=kc_all, vc=vc_all))
     del v_all, k_all, kc_all, vc_all
 
+    # what the board sustains for the bare matrix instruction, constant and random operands (power limit)
+    calib_const, calib_rand = mfma_calib(0, False), mfma_calib(0, True)
+
     kept_flops, mask_flops = st.kept_tile_flops(), st.mask_flops()
     dense_kept = dense.kept_tile_flops()
     st_call_ms = stage_ms["st_prefill"]           # prefill kernel + merge, events inside the timed steps
@@ -268,6 +295,11 @@ def main() -> int:
             "bound": "mfma", "achieved": round(st_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(st_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": profiled_traffic_bytes(),
             "algorithmic_flops_per_launch": kept_flops, "launch_ms": round(st_call_ms, 4),
+            "mfma_loop_measured": {
+                "what": "register-resident v_mfma_f32_32x32x16_bf16 loop, 256 workgroups x 8 wavefronts, ~20 ms",
+                "constant_operands_tflops": round(calib_const[0], 1), "constant_operands_ghz": round(calib_const[1], 2),
+                "random_operands_tflops": round(calib_rand[0], 1), "random_operands_ghz": round(calib_rand[1], 2),
+            },
         },
         "context": "paper: 5.0x KV compression, 3.16x prefill speed-up, whole model on 1x A100 40GB (not comparable)",
     }

@@ -193,6 +193,24 @@ PUREKV_API int32_t purekv_budget(int32_t n, int32_t w, double ratio);
 PUREKV_API double purekv_plan_kept_tile_flops(const purekv_plan_t* plan);
 PUREKV_API double purekv_plan_mask_flops(const purekv_plan_t* plan);
 
+/*
+ * Board calibration (not a step of the paper's method; it exists so that the prefill kernel's rate can be read
+ * against what the board sustains).  Launches, on the plan's grid of persistent workgroups (one per compute unit,
+ * eight wavefronts each), a register-resident loop of the bf16 32x32x16 matrix instruction the prefill kernel uses:
+ *   mix 0: the matrix instruction alone;  mix 1: each one takes an operand from a fresh 1 KB LDS fragment read;
+ *   mix 2: mix 1 plus the vector work of one softmax slot (2 multiply-adds, 2 exponentials, 1 bf16 convert).
+ * random_operands != 0 fills the operands with pseudo-random bf16 values, 0 with constants: the board's power
+ * limit, and with it the clock, depends on how many operand bits change.  `iters` (1 .. 2^20) outer iterations of
+ * 16 matrix instructions per wavefront; purekv_calib_mfma_flops gives the launch's flop count.
+ *   sink  fp32 device [512 * counts[6]] (counts from purekv_plan_counts): written, values meaningless.
+ *   ticks uint64 device [2]: elapsed shader cycles of wavefront 0 and the same span on the 100 MHz counter.
+ * Asynchronous on `stream`, allocates nothing; the caller times it with events.  EINVAL for a host-only plan, null
+ * pointers or arguments out of range.
+ */
+PUREKV_API int purekv_calib_mfma(const purekv_plan_t* plan, int mix, int random_operands, int32_t iters, float* sink,
+                                 uint64_t* ticks, void* stream);
+PUREKV_API double purekv_calib_mfma_flops(const purekv_plan_t* plan, int32_t iters);
+
 /* Static description of a status code; for PUREKV_EHIP the text of the last HIP error seen by this
  * thread is appended. */
 PUREKV_API const char* purekv_strerror(int status);

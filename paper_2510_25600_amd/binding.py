@@ -62,6 +62,8 @@ def _load() -> ctypes.CDLL:
         "purekv_budget": (c_int32, [c_int32, c_int32, c_double]),
         "purekv_plan_kept_tile_flops": (c_double, [P]),
         "purekv_plan_mask_flops": (c_double, [P]),
+        "purekv_calib_mfma": (c_int, [P, c_int, c_int, c_int32, P, P, P]),
+        "purekv_calib_mfma_flops": (c_double, [P, c_int32]),
         "purekv_strerror": (c_char_p, [c_int]),
     }
     for name, (res, args) in sig.items():
@@ -77,7 +79,7 @@ EXPORTS = (
     "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_workspace_bytes", "purekv_st_spattn_prefill",
     "purekv_lowlayer_importance", "purekv_topk_select", "purekv_kv_compact", "purekv_kv_append",
     "purekv_decode_attn", "purekv_budget", "purekv_plan_kept_tile_flops", "purekv_plan_mask_flops",
-    "purekv_strerror",
+    "purekv_calib_mfma", "purekv_calib_mfma_flops", "purekv_strerror",
 )
 
 
@@ -294,3 +296,18 @@ def purekv_decode_attn(plan: Plan, q_new: torch.Tensor, kc: torch.Tensor, vc: to
     _check(_lib.purekv_decode_attn(plan.handle, q_new.data_ptr(), kc.data_ptr(), vc.data_ptr(), n_cached, cap,
                                    out.data_ptr(), _ptr(ws), nb, _stream()), "purekv_decode_attn")
     return out
+
+
+def purekv_calib_mfma(plan: Plan, mix: int, random_operands: bool, iters: int,
+                      sink: Optional[torch.Tensor] = None, ticks: Optional[torch.Tensor] = None):
+    """Launches the board-calibration loop once on the current stream (asynchronous).  Returns (flops of the launch,
+    ticks): ticks is an int64 device tensor [2], shader cycles and 100 MHz ticks of wavefront 0, valid once the
+    stream has been synchronised.  Time the call with events around it."""
+    dev = torch.device("cuda", torch.cuda.current_device())
+    if sink is None:
+        sink = torch.empty(512 * plan.counts()["n_workgroups"], dtype=torch.float32, device=dev)
+    if ticks is None:
+        ticks = torch.zeros(2, dtype=torch.int64, device=dev)
+    _check(_lib.purekv_calib_mfma(plan.handle, mix, int(bool(random_operands)), iters, sink.data_ptr(),
+                                  ticks.data_ptr(), _stream()), "purekv_calib_mfma")
+    return float(_lib.purekv_calib_mfma_flops(plan.handle, iters)), ticks

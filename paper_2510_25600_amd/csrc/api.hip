@@ -246,6 +246,17 @@ int purekv_decode_attn(const purekv_plan_t* p, const void* q_new, const void* kc
   return launch_decode(*p, q_new, kc, vc, n_cached, cap, out, ws, static_cast<hipStream_t>(stream));
 }
 
+int purekv_calib_mfma(const purekv_plan_t* p, int mix, int random_operands, int32_t iters, float* sink, uint64_t* ticks,
+                      void* stream) {
+  if (!launchable(p) || sink == nullptr || ticks == nullptr) return PUREKV_EINVAL;
+  if (mix < 0 || mix > 2 || iters < 1 || iters > (1 << 20)) return PUREKV_EINVAL;
+  return launch_calib_mfma(*p, mix, random_operands != 0, iters, sink, ticks, static_cast<hipStream_t>(stream));
+}
+
+double purekv_calib_mfma_flops(const purekv_plan_t* p, int32_t iters) {
+  return (p == nullptr || iters < 1) ? 0.0 : calib_mfma_flops(*p, iters);
+}
+
 int32_t purekv_budget(int32_t n, int32_t w, double ratio) {
   const double kept = std::floor(ratio * (double)n);
   const int64_t h = (int64_t)kept - w;

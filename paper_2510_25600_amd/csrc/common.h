@@ -86,6 +86,10 @@ int launch_append(const purekv_plan& p, const void* k_new, const void* v_new, vo
 int launch_decode(const purekv_plan& p, const void* q_new, const void* kc, const void* vc, int32_t n_cached,
                   int32_t cap, void* out, void* ws, hipStream_t st);
 
+int launch_calib_mfma(const purekv_plan& p, int mix, int random_operands, int32_t iters, float* sink, uint64_t* ticks,
+                      hipStream_t st);
+double calib_mfma_flops(const purekv_plan& p, int32_t iters);
+
 size_t prefill_ws_bytes(const purekv_plan& p);
 size_t topk_ws_bytes(const purekv_plan& p, int32_t n_layers, int32_t w);
 size_t decode_ws_bytes(const purekv_plan& p, int32_t cap);

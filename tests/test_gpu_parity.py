@@ -290,7 +290,28 @@ def test_gpu_argument_errors():
     assert lib.purekv_kv_append(plan.handle, P(k), P(v), P(k), P(v), 57, 57, None) == pk.EINVAL
     assert lib.purekv_decode_attn(plan.handle, P(q), P(k), P(v), 0, 57, P(q), P(c), 1 << 20, None) == pk.EINVAL
     assert lib.purekv_decode_attn(plan.handle, P(q), P(k), P(v), 57, 57, P(q), None, 0, None) == pk.EWORKSPACE
+    assert lib.purekv_calib_mfma(plan.handle, 3, 0, 10, P(c), P(c), None) == pk.EINVAL
+    assert lib.purekv_calib_mfma(plan.handle, 0, 0, 0, P(c), P(c), None) == pk.EINVAL
+    assert lib.purekv_calib_mfma(plan.handle, 0, 0, 10, None, P(c), None) == pk.EINVAL
     long = pk.Plan.for_workload(SMALL["longtext_2f"], 3)
     assert long.workspace_bytes(pk.OP_PREFILL) > 0
     assert lib.purekv_st_spattn_prefill(long.handle, P(q), P(k), P(v), P(q), None, None, 0, None) == pk.EWORKSPACE
     torch.cuda.synchronize()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("mix", [0, 1, 2])
+def test_calibration_loop_runs_and_reports_its_clock(mix):
+    """The board-calibration loop is not part of the method: it has to run on the plan's grid, write every sink
+    element with a finite value and report a plausible shader clock."""
+    plan = _plan(WORKLOADS["tiny_4f"], 3)
+    n_wg = plan.counts()["n_workgroups"]
+    sink = torch.full((512 * n_wg,), float("nan"), dtype=torch.float32, device="cuda")
+    for rnd in (False, True):
+        flops, ticks = pk.purekv_calib_mfma(plan, mix, rnd, 200, sink=sink)
+        torch.cuda.synchronize()
+        assert flops == 2.0 * 32 * 32 * 16 * 16 * 200 * 8 * n_wg
+        assert bool(torch.isfinite(sink).all())
+        cyc, ref = ticks.tolist()
+        assert cyc >= 200 * 16 * 32 and ref > 0          # an MFMA of this shape holds the pipe 32 cycles
+        assert 0.05 < cyc / ref / 10.0 < 3.0             # GHz
