@@ -133,8 +133,7 @@ def main() -> int:
         mark(6)
         pk.purekv_kv_compact(st, k1, v1, idx1[0], cap=cap, kc=kc1, vc=vc1)
         mark(7)
-        pk.purekv_kv_append(st, k_new, v_new, kc1, vc1, n_keep)
-        pk.purekv_decode_attn(st, q_new, kc1, vc1, n_keep + 1, out=o_dec)
+        pk.purekv_decode_step(st, q_new, k_new, v_new, kc1, vc1, n_keep, out=o_dec)
         mark(8)
 
     def make_batched(L):
@@ -191,8 +190,7 @@ def main() -> int:
             "st_prefill": lambda: pk.purekv_st_spattn_prefill(st, q1, k1, v1, out=out1),
             "topk_high": lambda: pk.purekv_topk_select(st, c, v1, w, h, idx_out=idx1),
             "compact_high": lambda: pk.purekv_kv_compact(st, k1, v1, idx1[0], cap=cap, kc=kc1, vc=vc1),
-            "append_decode": lambda: (pk.purekv_kv_append(st, k_new, v_new, kc1, vc1, n_keep),
-                                      pk.purekv_decode_attn(st, q_new, kc1, vc1, n_keep + 1, out=o_dec)),
+            "append_decode": lambda: pk.purekv_decode_step(st, q_new, k_new, v_new, kc1, vc1, n_keep, out=o_dec),
             # plain device copy of a known size (256 MiB read + 256 MiB written): scale for the HBM byte counters
             "copy_calib": lambda: calib_dst.copy_(calib_src),
             "topk_batched": lambda: pk.purekv_topk_select(st, c, v_all, w, h, idx_out=idx_all),

@@ -185,6 +185,18 @@ PUREKV_API int purekv_kv_append(const purekv_plan_t* plan, const void* k_new, co
 PUREKV_API int purekv_decode_attn(const purekv_plan_t* plan, const void* q_new, const void* kc, const void* vc,
                        int32_t n_cached, int32_t cap, void* out, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * One decode step in one launch (the decode stage of the paper's inference-speed table, per generated token):
+ * stores k_new, v_new [Hkv, d] as row n_cached of kc, vc (as purekv_kv_append does) and attends q_new over rows
+ * 0 .. n_cached inclusive (as purekv_decode_attn with n_cached + 1 does).  0 <= n_cached < cap.
+ * Both decode calls keep per-plan arrival counters on the device: calls that share a plan must not overlap on the
+ * GPU (calls on one stream never do).
+ */
+PUREKV_API int purekv_decode_step(const purekv_plan_t* plan, const void* q_new, const void* k_new, const void* v_new,
+                                  void* kc, void* vc, int32_t n_cached, int32_t cap, void* out, void* ws,
+                                  size_t ws_bytes, void* stream);
+
+
 /* h = max(0, floor(ratio * n) - w): the keep budget counts the recent window (20 % budget = 5.0x). */
 PUREKV_API int32_t purekv_budget(int32_t n, int32_t w, double ratio);
 

@@ -59,6 +59,7 @@ def _load() -> ctypes.CDLL:
         "purekv_kv_compact": (c_int, [P, P, P, c_int64, c_int32, P, c_int32, P, P, c_int32, P]),
         "purekv_kv_append": (c_int, [P, P, P, P, P, c_int32, c_int32, P]),
         "purekv_decode_attn": (c_int, [P, P, P, P, c_int32, c_int32, P, P, c_size_t, P]),
+        "purekv_decode_step": (c_int, [P, P, P, P, P, P, c_int32, c_int32, P, P, c_size_t, P]),
         "purekv_budget": (c_int32, [c_int32, c_int32, c_double]),
         "purekv_plan_kept_tile_flops": (c_double, [P]),
         "purekv_plan_mask_flops": (c_double, [P]),
@@ -78,7 +79,7 @@ EXPORTS = (
     "purekv_plan_create", "purekv_plan_create_host", "purekv_plan_destroy", "purekv_plan_counts",
     "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_workspace_bytes", "purekv_st_spattn_prefill",
     "purekv_lowlayer_importance", "purekv_topk_select", "purekv_kv_compact", "purekv_kv_append",
-    "purekv_decode_attn", "purekv_budget", "purekv_plan_kept_tile_flops", "purekv_plan_mask_flops",
+    "purekv_decode_attn", "purekv_decode_step", "purekv_budget", "purekv_plan_kept_tile_flops", "purekv_plan_mask_flops",
     "purekv_calib_mfma", "purekv_calib_mfma_flops", "purekv_strerror",
 )
 
@@ -295,6 +296,22 @@ def purekv_decode_attn(plan: Plan, q_new: torch.Tensor, kc: torch.Tensor, vc: to
     ws = plan._workspace(OP_DECODE, nb, q_new.device)
     _check(_lib.purekv_decode_attn(plan.handle, q_new.data_ptr(), kc.data_ptr(), vc.data_ptr(), n_cached, cap,
                                    out.data_ptr(), _ptr(ws), nb, _stream()), "purekv_decode_attn")
+    return out
+
+
+def purekv_decode_step(plan: Plan, q_new: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, kc: torch.Tensor,
+                       vc: torch.Tensor, n_cached: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Appends k_new, v_new as row n_cached of kc, vc and attends q_new over rows 0 .. n_cached, in one launch."""
+    for t, name in ((q_new, "q_new"), (k_new, "k_new"), (v_new, "v_new"), (kc, "kc"), (vc, "vc")):
+        _dev_bf16(t, name)
+    cap = kc.shape[-2]
+    if out is None:
+        out = torch.empty_like(q_new)
+    nb = plan.workspace_bytes(OP_DECODE, cap=cap)
+    ws = plan._workspace(OP_DECODE, nb, q_new.device)
+    _check(_lib.purekv_decode_step(plan.handle, q_new.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), kc.data_ptr(),
+                                   vc.data_ptr(), n_cached, cap, out.data_ptr(), _ptr(ws), nb, _stream()),
+           "purekv_decode_step")
     return out
 
 

@@ -88,6 +88,9 @@ int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* s
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_queue_begin), qb ? qb : 16);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_queue_unit0), qb ? qb : 16);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_merges), mb ? mb : 16);
+  const size_t cb = (size_t)decode_counter_count(*p) * sizeof(int32_t);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_counters), cb);
+  if (e == hipSuccess) e = hipMemsetAsync(p->d_counters, 0, cb, st);
   if (e == hipSuccess && sb) e = hipMemcpyAsync(p->d_stream, p->stream.data(), sb, hipMemcpyHostToDevice, st);
   if (e == hipSuccess && ub) e = hipMemcpyAsync(p->d_units, p->units.data(), ub, hipMemcpyHostToDevice, st);
   if (e == hipSuccess && qb) e = hipMemcpyAsync(p->d_queue_begin, p->queue_begin.data(), qb, hipMemcpyHostToDevice, st);
@@ -110,6 +113,7 @@ int purekv_plan_destroy(purekv_plan_t* p) {
   if (p->d_queue_begin) (void)hipFree(p->d_queue_begin);
   if (p->d_queue_unit0) (void)hipFree(p->d_queue_unit0);
   if (p->d_merges) (void)hipFree(p->d_merges);
+  if (p->d_counters) (void)hipFree(p->d_counters);
   delete p;
   return PUREKV_OK;
 }
@@ -243,7 +247,18 @@ int purekv_decode_attn(const purekv_plan_t* p, const void* q_new, const void* kc
   if (!launchable(p) || q_new == nullptr || kc == nullptr || vc == nullptr || out == nullptr) return PUREKV_EINVAL;
   if (n_cached < 1 || n_cached > cap) return PUREKV_EINVAL;
   if (ws == nullptr || ws_bytes < decode_ws_bytes(*p, cap)) return PUREKV_EWORKSPACE;
-  return launch_decode(*p, q_new, kc, vc, n_cached, cap, out, ws, static_cast<hipStream_t>(stream));
+  return launch_decode(*p, q_new, nullptr, nullptr, const_cast<void*>(kc), const_cast<void*>(vc), n_cached, cap, out, ws,
+                       static_cast<hipStream_t>(stream));
+}
+
+int purekv_decode_step(const purekv_plan_t* p, const void* q_new, const void* k_new, const void* v_new, void* kc,
+                       void* vc, int32_t n_cached, int32_t cap, void* out, void* ws, size_t ws_bytes, void* stream) {
+  if (!launchable(p) || q_new == nullptr || k_new == nullptr || v_new == nullptr || kc == nullptr || vc == nullptr ||
+      out == nullptr)
+    return PUREKV_EINVAL;
+  if (n_cached < 0 || n_cached >= cap) return PUREKV_EINVAL;
+  if (ws == nullptr || ws_bytes < decode_ws_bytes(*p, cap)) return PUREKV_EWORKSPACE;
+  return launch_decode(*p, q_new, k_new, v_new, kc, vc, n_cached + 1, cap, out, ws, static_cast<hipStream_t>(stream));
 }
 
 int purekv_calib_mfma(const purekv_plan_t* p, int mix, int random_operands, int32_t iters, float* sink, uint64_t* ticks,

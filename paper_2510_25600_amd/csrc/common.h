@@ -83,8 +83,10 @@ int launch_compact(const purekv_plan& p, const void* k, const void* v, int64_t k
                    const int32_t* idx, int32_t n_keep, void* kc, void* vc, int32_t cap, hipStream_t st);
 int launch_append(const purekv_plan& p, const void* k_new, const void* v_new, void* kc, void* vc, int32_t n_cached,
                   int32_t cap, hipStream_t st);
-int launch_decode(const purekv_plan& p, const void* q_new, const void* kc, const void* vc, int32_t n_cached,
-                  int32_t cap, void* out, void* ws, hipStream_t st);
+// k_new, v_new null: attention only; else row n_cached - 1 comes from them and is stored into kc, vc
+int launch_decode(const purekv_plan& p, const void* q_new, const void* k_new, const void* v_new, void* kc, void* vc,
+                  int32_t n_cached, int32_t cap, void* out, void* ws, hipStream_t st);
+int decode_counter_count(const purekv_plan& p);
 
 int launch_calib_mfma(const purekv_plan& p, int mix, int random_operands, int32_t iters, float* sink, uint64_t* ticks,
                       hipStream_t st);

@@ -98,6 +98,7 @@ struct purekv_plan {
   int32_t* d_queue_begin = nullptr;
   int32_t* d_queue_unit0 = nullptr;        // [n_queues + 1] first unit of each queue
   purekv::MergeItem* d_merges = nullptr;
+  int32_t* d_counters = nullptr;           // arrival counters of the decode kernel, zero between calls
   int device = -1;
   int n_cu = 256;
 };

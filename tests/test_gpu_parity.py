@@ -222,7 +222,8 @@ def test_compaction_bit_exact_and_append(name):
 
 
 @pytest.mark.parametrize("hq,hkv,d,n_cached", [(2, 1, 64, 57), (28, 4, 128, 1690), (32, 8, 128, 948), (12, 1, 128, 5),
-                                               (4, 4, 64, 1), (9, 3, 128, 333)])
+                                               (4, 4, 64, 1), (9, 3, 128, 333), (40, 2, 128, 300), (34, 2, 64, 129),
+                                               (28, 4, 128, 128), (28, 4, 128, 6800), (4, 1, 64, 17000), (6, 2, 128, 33000)])
 def test_decode_matches_oracle(hq, hkv, d, n_cached):
     rng = np.random.default_rng(n_cached)
     from workloads import f32_to_bf16_bits
@@ -235,6 +236,35 @@ def test_decode_matches_oracle(hq, hkv, d, n_cached):
     torch.cuda.synchronize()
     ref = orc.decode_attention(F64(q), F64(kc)[:, :n_cached], F64(vc)[:, :n_cached])
     check_attention(f64_of(out), ref, "decode")
+
+
+@pytest.mark.parametrize("hq,hkv,d,n0,steps", [(28, 4, 128, 1689, 3), (40, 2, 64, 126, 5), (8, 8, 128, 0, 3),
+                                               (12, 3, 128, 255, 3)])
+def test_decode_step_appends_and_attends(hq, hkv, d, n0, steps):
+    """The fused step = append + attention: the cache must equal the one the separate append call builds, bit for
+    bit, the output must match the oracle on the grown cache, and consecutive calls (the arrival counters reset
+    themselves) must keep doing so, also across a 256-key chunk boundary."""
+    from workloads import f32_to_bf16_bits
+    rng = np.random.default_rng(1000 * hq + n0)
+    bits = lambda *shape: f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))  # noqa: E731
+    cap = n0 + steps + 2
+    kc_h, vc_h = bits(hkv, cap, d), bits(hkv, cap, d)
+    kc, vc = to_dev(kc_h), to_dev(vc_h)           # fused path
+    kc2, vc2 = to_dev(kc_h), to_dev(vc_h)         # separate append + attention
+    plan = pk.Plan(1, 4, 4, 4, hq, hkv, d, 3)
+    for t in range(steps):
+        q, kn, vn = bits(hq, d), bits(hkv, d), bits(hkv, d)
+        n = n0 + t
+        out = pk.purekv_decode_step(plan, to_dev(q), to_dev(kn), to_dev(vn), kc, vc, n)
+        pk.purekv_kv_append(plan, to_dev(kn), to_dev(vn), kc2, vc2, n)
+        out2 = pk.purekv_decode_attn(plan, to_dev(q), kc2, vc2, n + 1)
+        torch.cuda.synchronize()
+        kc_h[:, n], vc_h[:, n] = kn, vn
+        assert np.array_equal(bits_of(kc)[:, :n + 1], kc_h[:, :n + 1]) and np.array_equal(bits_of(kc), bits_of(kc2))
+        assert np.array_equal(bits_of(vc)[:, :n + 1], vc_h[:, :n + 1]) and np.array_equal(bits_of(vc), bits_of(vc2))
+        assert np.array_equal(bits_of(out), bits_of(out2))   # same kernel, same order of operations
+        ref = orc.decode_attention(F64(q), F64(kc_h)[:, :n + 1], F64(vc_h)[:, :n + 1])
+        check_attention(f64_of(out), ref, f"decode step {t}")
 
 
 def test_tiny_config_end_to_end_chain():
@@ -290,6 +320,9 @@ def test_gpu_argument_errors():
     assert lib.purekv_kv_append(plan.handle, P(k), P(v), P(k), P(v), 57, 57, None) == pk.EINVAL
     assert lib.purekv_decode_attn(plan.handle, P(q), P(k), P(v), 0, 57, P(q), P(c), 1 << 20, None) == pk.EINVAL
     assert lib.purekv_decode_attn(plan.handle, P(q), P(k), P(v), 57, 57, P(q), None, 0, None) == pk.EWORKSPACE
+    assert lib.purekv_decode_step(plan.handle, P(q), P(k), P(v), P(k), P(v), 57, 57, P(q), P(c), 1 << 20, None) == pk.EINVAL
+    assert lib.purekv_decode_step(plan.handle, P(q), None, P(v), P(k), P(v), 5, 57, P(q), P(c), 1 << 20, None) == pk.EINVAL
+    assert lib.purekv_decode_step(plan.handle, P(q), P(k), P(v), P(k), P(v), 5, 57, P(q), None, 0, None) == pk.EWORKSPACE
     assert lib.purekv_calib_mfma(plan.handle, 3, 0, 10, P(c), P(c), None) == pk.EINVAL
     assert lib.purekv_calib_mfma(plan.handle, 0, 0, 0, P(c), P(c), None) == pk.EINVAL
     assert lib.purekv_calib_mfma(plan.handle, 0, 0, 10, None, P(c), None) == pk.EINVAL

@@ -75,6 +75,7 @@ def test_compute_calls_validate_before_touching_the_gpu():
     assert lib.purekv_kv_compact(h, one, one, 0, 1, one, 4, one, one, 4, None) == pk.EINVAL
     assert lib.purekv_kv_append(h, one, one, one, one, 0, 4, None) == pk.EINVAL
     assert lib.purekv_decode_attn(h, one, one, one, 4, 4, one, one, 1 << 20, None) == pk.EINVAL
+    assert lib.purekv_decode_step(h, one, one, one, one, one, 3, 4, one, one, 1 << 20, None) == pk.EINVAL
     assert lib.purekv_calib_mfma(h, 0, 0, 10, one, one, None) == pk.EINVAL
     assert lib.purekv_calib_mfma_flops(None, 10) == 0.0
     assert lib.purekv_calib_mfma_flops(h, 10) == 2.0 * 32 * 32 * 16 * 16 * 10 * 8 * plan.counts()["n_workgroups"]
