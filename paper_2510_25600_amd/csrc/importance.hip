@@ -4,9 +4,11 @@
 // MFMA A operand for the whole kernel) and walks every window row of every query head of the group in
 // blocks of 32 rows.  The workgroup has two such sets of four wavefronts: set 0 takes the even blocks, set 1 the
 // odd ones (two wavefronts per SIMD hide each other's LDS and MFMA latencies), and their sums are added at the
-// end in a fixed order.  The four wavefronts of a set need the same query rows: a block of 32 rows is fetched
-// once per set with whole-row loads (16 lanes x 16 bytes), parked in LDS (double-buffered, one barrier per
-// block; the block after the next is in flight in registers) and read from there as the MFMA B operand.
+// end in a fixed order.  The four wavefronts of a set need the same query rows: a block of 32 rows (and its 32
+// log-sum-exp values) goes from global memory straight into a ring of six LDS slots per set
+// (global_load_lds: no staging registers), five blocks ahead of its use -- an iteration is a few hundred
+// nanoseconds, an L2 hit about as long, so a shallow prefetch leaves every iteration waiting for its rows --
+// with one barrier per block, and is read from LDS as the MFMA B operand.
 // Scores are formed transposed (keys x queries) so a lane owns one query row of the
 // block: it needs one log-sum-exp value and turns its 16 scores into probabilities exp(s - lse) in
 // fp32.  Every lane keeps 16 running sums (one per key it sees); only at the very end are the 32 lanes
@@ -25,17 +27,60 @@ struct ImportanceArgs {
   int32_t N, Nv, P, Hq, G, w;
   uint32_t pattern;
   float scale_log2;
+#ifdef PUREKV_IMPORTANCE_TRACE
+  unsigned long long* trace;   // development aid: [workgroup][8] = 4 x (shader cycles, 100 MHz ticks) of thread 0
+#endif
 };
 
-template <int D>
+#ifdef PUREKV_IMPORTANCE_TRACE
+#define IMP_STAMP(i)                                                                       \
+  do {                                                                                     \
+    if (threadIdx.x == 0) {                                                                \
+      a.trace[(blockIdx.x + gridDim.x * blockIdx.y) * 8 + 2 * (i)] = __builtin_readcyclecounter();       \
+      a.trace[(blockIdx.x + gridDim.x * blockIdx.y) * 8 + 2 * (i) + 1] = __builtin_amdgcn_s_memrealtime(); \
+    }                                                                                      \
+  } while (0)
+#define IMP_TICK(i)                                                  \
+  do {                                                               \
+    const unsigned long long now__ = __builtin_readcyclecounter();   \
+    tick_sum[i] += now__ - tick_last;                                \
+    tick_last = now__;                                               \
+  } while (0)
+#else
+#define IMP_STAMP(i) do {} while (0)
+#define IMP_TICK(i) do {} while (0)
+#endif
+
+typedef __attribute__((address_space(3))) void* LdsPtr;
+
+// Global memory straight into LDS, 16 or 4 bytes per lane: lane l's piece lands at lds_ptr + 16 l (4 l), its source is
+// base + off.  Assembly, so that the waits for these loads are the kernel's own (the compiler would wait for every
+// outstanding one before any LDS read).  base and lds_ptr must be wave-uniform.
+__device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t off, const void* lds_ptr) {
+  const uint32_t lds_base = (uint32_t)(size_t)(LdsPtr)lds_ptr;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(off), "s"(base) : "memory");
+}
+__device__ __forceinline__ void load_to_lds_4(const void* base, uint32_t off, const void* lds_ptr) {
+  const uint32_t lds_base = (uint32_t)(size_t)(LdsPtr)lds_ptr;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_base), "v"(off), "s"(base) : "memory");
+}
+
+// MASK = false: every window row sees every non-recent key (text rows, or the dense pattern).
+template <int D, bool MASK>
 __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a) {
   constexpr int KSTEPS = D / 16;
   constexpr int CPR = D / 8;            // 16-byte chunks per row
   constexpr int NLD = 32 * CPR / 256;   // 16-byte loads per thread and block of 32 query rows
-  __shared__ __attribute__((aligned(16))) uint16_t Qs_all[2][2][32 * D];   // [set][buffer]
-  __shared__ float part[4][16][64];                                        // set 1's sums, per wavefront
-  const int set = threadIdx.x >> 8;
-  const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;      // within the set
+  constexpr int NB = 6;                 // ring of query blocks per set: NB - 1 blocks are in flight or in use
+  constexpr int LPB = NLD + 1;          // loads per thread and block (query pieces + one log-sum-exp word)
+  constexpr int WAIT_BLOCK = ((NB - 2) * LPB & 15) | (((NB - 2) * LPB >> 4) << 14) | 0x0F70;   // vmcnt((NB-2) LPB)
+  static_assert((NB - 2) * LPB < 64, "vmcnt has six bits");
+  __shared__ __attribute__((aligned(16))) uint16_t Qs_all[2][NB][32 * D];   // [set][slot]
+  __shared__ float lse_all[2][NB][4][64];                                   // [set][slot][wavefront]: own copy each
+  __shared__ float part[4][16][64];                                         // set 1's sums, per wavefront
+  const int set = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);
+  const int tid = threadIdx.x & 255, lane = tid & 63;                       // within the set
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   uint16_t (*Qs)[32 * D] = Qs_all[set];
   const int n = lane & 31, h = lane >> 5;
   const int kvh = blockIdx.y;
@@ -43,6 +88,10 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
   const int jw = blockIdx.x * 128 + wave * 32;  // first key of this wavefront
   const int row0 = a.N - a.w;             // first window row
 
+  IMP_STAMP(0);
+#ifdef PUREKV_IMPORTANCE_TRACE
+  unsigned long long tick_sum[5] = {0, 0, 0, 0, 0}, tick_last = __builtin_readcyclecounter();
+#endif
   bf16x8 kf[KSTEPS];
   {
     const int j = min(jw + n, a.N - 1);
@@ -50,9 +99,6 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) kf[s] = *reinterpret_cast<const bf16x8*>(kr + 16 * s + 8 * h);
   }
-
-  // Window rows that are text (or any row under the dense pattern) see every non-recent key: no mask.
-  const bool need_mask = a.pattern != 0u && row0 < a.Nv;
 
   float acc[16];
 #pragma unroll
@@ -66,77 +112,116 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
   int st_row[NLD], st_col[NLD];
 #pragma unroll
   for (int i = 0; i < NLD; ++i) kunswz<D>(i * 256 + tid, st_row[i], st_col[i]);
-  u32x4 qreg[NLD];
-  float lse_reg = 0.f;   // this lane's row of the block in flight
-  auto load_block = [&](int b) {
-    const int bc = min(b, n_blocks - 1);   // past the end: re-read the last block (never used)
+  // Starts the loads of block b into ring slot `slot`: LPB loads per thread, always (a block past the end
+  // repeats the last one and is never used), so that the count of loads in flight is the same in every iteration.
+  auto issue_block = [&](int b, int slot) {
+    const int bc = min(b, n_blocks - 1);
     const int g = bc / n_qblocks, qb = bc - g * n_qblocks;
     const size_t hrow = (size_t)(kvh * a.G + g) * a.N;
+    const uint16_t* qhead = a.q + hrow * D;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int r = min(row0 + qb * 32 + st_row[i], a.N - 1);
-      qreg[i] = *reinterpret_cast<const u32x4*>(a.q + (hrow + r) * D + st_col[i] * 8);
+      load_to_lds_16(qhead, (uint32_t)(r * D + st_col[i] * 8) * 2u, &Qs[slot][(i * 256 + wave * 64) * 8]);
     }
-    lse_reg = a.lse[hrow + min(row0 + qb * 32 + n, a.N - 1)];
-  };
-  auto store_block = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) *reinterpret_cast<u32x4*>(&Qs[buf][(i * 256 + tid) * 8]) = qreg[i];
+    load_to_lds_4(a.lse + hrow, (uint32_t)min(row0 + qb * 32 + n, a.N - 1) * 4u, &lse_all[set][slot][wave][0]);
   };
 
-  load_block(set);
-  store_block(0);
-  float lse_cur = lse_reg;
-  load_block(2 + set);
-  for (int it = 0; it < n_iter; ++it) {
+#pragma unroll 1
+  for (int s = 0; s < NB - 1; ++s) issue_block(2 * s + set, s);
+  // Software pipeline inside the wavefront: the eight MFMAs of block `it` are issued with the exponentials of block
+  // it - 1 between them (two scores per MFMA), so the matrix pipe and the vector ALU overlap although the barrier
+  // keeps all eight wavefronts in step.  State of the block whose scores wait for their exponentials:
+  struct Pending {
+    float neg_lse2;   // minus the log-sum-exp of the lane's row in log2 units; -inf when the row does not exist
+    int rowc;     // the lane's row (clamped) and what the mask needs of it
+    int own0, prev;
+    bool ok, video;
+  };
+  const float scale_v = a.scale_log2;
+  auto exp_step = [&](const floatx16& S, const Pending& pd, int i) {
+    // volatile: the multiply-add stays between the MFMAs where it is written (plain arithmetic is collected ahead
+    // of the product by the compiler, and the wavefronts of a SIMD then take turns instead of overlapping)
+    float x;
+    asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(x) : "v"(S[i]), "v"(scale_v), "v"(pd.neg_lse2));
+    const float p = __builtin_amdgcn_exp2f(x);
+    if constexpr (!MASK) {
+      acc[i] += p;
+    } else {
+      const int j = jw + 8 * (i >> 2) + 4 * h + (i & 3);
+      bool ok = pd.ok && j <= pd.rowc;
+      bool allowed = j < a.P;
+      if (a.pattern & 1u) allowed |= (j >= pd.own0);
+      if (a.pattern & 2u) allowed |= (j == pd.prev) | (j == pd.rowc);
+      ok &= !pd.video || (allowed && j < a.Nv);
+      acc[i] += ok ? p : 0.f;
+    }
+  };
+  int slot = 0;
+  // One pipeline stage: block `it` (if it exists for this set) is multiplied into Sn while Sp's exponentials run.
+  auto stage = [&](int it, floatx16& Sn, Pending& pn, const floatx16& Sp, const Pending& pp, bool have_prev) {
     const int b = 2 * it + set;
-    __syncthreads();   // block b is in Qs[it & 1]; nobody reads Qs[(it + 1) & 1] any more
-    store_block((it + 1) & 1);
-    const float lse_next = lse_reg;
-    load_block(b + 4);
-
+    IMP_TICK(0);
+    __builtin_amdgcn_s_waitcnt(WAIT_BLOCK);   // this thread's pieces of block b have landed
+    IMP_TICK(1);
+    __syncthreads();                          // everybody's have; nobody reads the slot of block b - 2 any more
+    IMP_TICK(2);
+    issue_block(b + 2 * (NB - 1), slot == 0 ? NB - 1 : slot - 1);
+    IMP_TICK(3);
     const int bc = min(b, n_blocks - 1);
-    const int g = bc / n_qblocks, qb = bc - g * n_qblocks;
+    const int qb = bc % n_qblocks;
     const int row = row0 + qb * 32 + n;
-    const bool row_ok = row < a.N && b < n_blocks;   // an odd block count leaves set 1 one idle round
-    const int rowc = min(row, a.N - 1);
-    const uint16_t* Qb = Qs[it & 1];
+    pn.ok = row < a.N && b < n_blocks;   // an odd block count leaves set 1 one idle round
+    pn.rowc = min(row, a.N - 1);
+    pn.neg_lse2 = pn.ok ? lse_all[set][slot][wave][lane] * -kLog2e : -INFINITY;
+    if constexpr (MASK) {
+      pn.video = pn.rowc < a.Nv;
+      const int frame = pn.video ? pn.rowc / a.P : 0;
+      pn.own0 = frame * a.P;
+      pn.prev = frame >= 1 ? pn.rowc - a.P : -1;
+    }
+    const uint16_t* Qb = Qs[slot];
     bf16x8 qf[KSTEPS];
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(Qb + kswz<D>(n, 2 * s + h));
-    floatx16 sacc;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+    for (int i = 0; i < 16; ++i) Sn[i] = 0.f;
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], sacc, 0, 0, 0);
-    const float lse2 = lse_cur * kLog2e;
-    if (!need_mask) {
+    for (int s = 0; s < KSTEPS; ++s) {
+      Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], Sn, 0, 0, 0);
+      if (have_prev) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float p = __builtin_amdgcn_exp2f(sacc[i] * a.scale_log2 - lse2);
-        acc[i] += row_ok ? p : 0.f;
+        for (int i = s * (16 / KSTEPS); i < (s + 1) * (16 / KSTEPS); ++i) exp_step(Sp, pp, i);
       }
-    } else {
-      const bool video = rowc < a.Nv;
-      const int frame = video ? rowc / a.P : 0;
-      const int own0 = frame * a.P;
-      const int prev = (frame >= 1) ? rowc - a.P : -1;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int j = jw + 8 * (i >> 2) + 4 * h + (i & 3);
-        bool ok = row_ok && j <= rowc;
-        if (video) {
-          bool allowed = j < a.P;
-          if (a.pattern & 1u) allowed |= (j >= own0);
-          if (a.pattern & 2u) allowed |= (j == prev) | (j == rowc);
-          ok &= allowed && j < a.Nv;
-        }
-        const float p = __builtin_amdgcn_exp2f(sacc[i] * a.scale_log2 - lse2);
-        acc[i] += ok ? p : 0.f;
-      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    lse_cur = lse_next;
+    slot = slot == NB - 1 ? 0 : slot + 1;
+    IMP_TICK(4);
+  };
+  floatx16 S0, S1;
+  Pending p0, p1;
+  stage(0, S0, p0, S1, p1, false);
+  IMP_STAMP(1);
+  int it = 1;
+  for (; it + 1 < n_iter; it += 2) {
+    stage(it, S1, p1, S0, p0, true);
+    stage(it + 1, S0, p0, S1, p1, true);
   }
+  if (it < n_iter) {
+    stage(it, S1, p1, S0, p0, true);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) exp_step(S1, p1, i);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) exp_step(S0, p0, i);
+  }
+  IMP_STAMP(2);
+#ifdef PUREKV_IMPORTANCE_TRACE
+  if ((threadIdx.x & 63) == 0 && blockIdx.x == 5 && blockIdx.y == 1)
+    for (int i = 0; i < 5; ++i) a.trace[256 * 8 + (threadIdx.x >> 6) * 8 + i] = tick_sum[i];
+#endif
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // the loads started past the end have landed before LDS is reused or freed
 
   // set 0 adds set 1's sums (same wavefront index, same lane: same keys and query slots), then
   // sum over the 32 query slots (lanes with equal h hold the same keys).
@@ -158,6 +243,7 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
     x += __shfl_xor(x, 16, 64);
     acc[i] = x;
   }
+  IMP_STAMP(3);
   if (n == 0) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -168,6 +254,10 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
 }
 
 }  // namespace
+
+#ifdef PUREKV_IMPORTANCE_TRACE
+unsigned long long* g_importance_trace = nullptr;
+#endif
 
 int launch_importance(const purekv_plan& p, const void* q, const void* k, const float* lse, int32_t w,
                       float* c_out, hipStream_t st) {
@@ -186,11 +276,18 @@ int launch_importance(const purekv_plan& p, const void* q, const void* k, const 
   a.w = w;
   a.pattern = p.g.pattern;
   a.scale_log2 = p.g.scale * kLog2e;
+#ifdef PUREKV_IMPORTANCE_TRACE
+  a.trace = g_importance_trace;
+#endif
   const dim3 grid((unsigned)((n_keys + 127) / 128), (unsigned)p.g.Hkv), block(512);
-  if (p.g.d == 128)
-    hipLaunchKernelGGL(importance_kernel<128>, grid, block, 0, st, a);
-  else
-    hipLaunchKernelGGL(importance_kernel<64>, grid, block, 0, st, a);
+  const bool mask = p.g.pattern != 0u && p.g.N - w < p.g.Nv;   // some window row is a video row under a sparse pattern
+  if (p.g.d == 128) {
+    if (mask) hipLaunchKernelGGL((importance_kernel<128, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((importance_kernel<128, false>), grid, block, 0, st, a);
+  } else {
+    if (mask) hipLaunchKernelGGL((importance_kernel<64, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((importance_kernel<64, false>), grid, block, 0, st, a);
+  }
   PUREKV_HIP_TRY(hipGetLastError());
   return PUREKV_OK;
 }
