@@ -112,42 +112,63 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
   int st_row[NLD], st_col[NLD];
 #pragma unroll
   for (int i = 0; i < NLD; ++i) kunswz<D>(i * 256 + tid, st_row[i], st_col[i]);
-  // Starts the loads of block b into ring slot `slot`: LPB loads per thread, always (a block past the end
-  // repeats the last one and is never used), so that the count of loads in flight is the same in every iteration.
-  auto issue_block = [&](int b, int slot) {
-    const int bc = min(b, n_blocks - 1);
-    const int g = bc / n_qblocks, qb = bc - g * n_qblocks;
-    const size_t hrow = (size_t)(kvh * a.G + g) * a.N;
+  // Starts the loads of the next block of this set into ring slot `slot`: LPB loads per thread, always (past the
+  // end the last block is repeated and never used), so that the count of loads in flight is the same in every
+  // iteration.  The set's blocks advance by two: (head, row block) are kept as counters.
+  int is_g = 0, is_qb = set;   // block the next call loads
+  auto normalise = [&](int& g, int& qb) {
+    while (qb >= n_qblocks) qb -= n_qblocks, ++g;
+    if (g >= a.G) g = a.G - 1, qb = n_qblocks - 1;
+  };
+  normalise(is_g, is_qb);
+  auto issue_next = [&](int slot) {
+    const size_t hrow = (size_t)(kvh * a.G + is_g) * a.N;
     const uint16_t* qhead = a.q + hrow * D;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const int r = min(row0 + qb * 32 + st_row[i], a.N - 1);
+      const int r = min(row0 + is_qb * 32 + st_row[i], a.N - 1);
       load_to_lds_16(qhead, (uint32_t)(r * D + st_col[i] * 8) * 2u, &Qs[slot][(i * 256 + wave * 64) * 8]);
     }
-    load_to_lds_4(a.lse + hrow, (uint32_t)min(row0 + qb * 32 + n, a.N - 1) * 4u, &lse_all[set][slot][wave][0]);
+    load_to_lds_4(a.lse + hrow, (uint32_t)min(row0 + is_qb * 32 + n, a.N - 1) * 4u, &lse_all[set][slot][wave][0]);
+    is_qb += 2;
+    normalise(is_g, is_qb);
   };
 
 #pragma unroll 1
-  for (int s = 0; s < NB - 1; ++s) issue_block(2 * s + set, s);
-  // Software pipeline inside the wavefront: the eight MFMAs of block `it` are issued with the exponentials of block
-  // it - 1 between them (two scores per MFMA), so the matrix pipe and the vector ALU overlap although the barrier
-  // keeps all eight wavefronts in step.  State of the block whose scores wait for their exponentials:
-  struct Pending {
-    float neg_lse2;   // minus the log-sum-exp of the lane's row in log2 units; -inf when the row does not exist
-    int rowc;     // the lane's row (clamped) and what the mask needs of it
+  for (int s = 0; s < NB - 1; ++s) issue_next(s);
+
+  // Software pipeline inside the wavefront, one stage per block: the eight MFMAs of block `it`, whose query
+  // fragments were read from LDS during the previous stage, with, between them, the exponentials of block it - 1
+  // (two scores per MFMA), the LDS reads of block it + 1's fragments and the start of the loads of block
+  // it + NB - 1.  The matrix pipe, the vector ALU and LDS overlap although the one barrier per stage keeps all
+  // eight wavefronts in step.
+  struct Pending {   // what the exponentials of a block need besides its scores
+    float neg_lse2;  // minus the log-sum-exp of the lane's row in log2 units; -inf when the row does not exist
+    int rowc;        // the lane's row (clamped) and what the mask needs of it
     int own0, prev;
     bool ok, video;
   };
+  struct Block {     // a block ready for its MFMAs
+    bf16x8 qf[KSTEPS];
+    Pending pd;
+  };
   const float scale_v = a.scale_log2;
   auto exp_step = [&](const floatx16& S, const Pending& pd, int i) {
-    // volatile: the multiply-add stays between the MFMAs where it is written (plain arithmetic is collected ahead
-    // of the product by the compiler, and the wavefronts of a SIMD then take turns instead of overlapping)
-    float x;
-    asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(x) : "v"(S[i]), "v"(scale_v), "v"(pd.neg_lse2));
-    const float p = __builtin_amdgcn_exp2f(x);
+    // Assembly, volatile: the three instructions of a score stay between the MFMAs where they are written (plain
+    // arithmetic is collected ahead of or behind the products by the compiler, and the wavefronts of a SIMD then
+    // take turns instead of overlapping).  The s_nop is the wait state a vector instruction needs before it reads
+    // the result of a transcendental one.
+    float p;
     if constexpr (!MASK) {
-      acc[i] += p;
+      asm volatile("v_fma_f32 %0, %2, %3, %4\n\tv_exp_f32 %0, %0\n\ts_nop 0\n\tv_add_f32 %1, %1, %0"
+                   : "=&v"(p), "+v"(acc[i])
+                   : "v"(S[i]), "v"(scale_v), "v"(pd.neg_lse2));
     } else {
+      asm volatile("v_fma_f32 %0, %1, %2, %3\n\tv_exp_f32 %0, %0\n\ts_nop 0"
+                   : "=v"(p)
+                   : "v"(S[i]), "v"(scale_v), "v"(pd.neg_lse2));
+    }
+    if constexpr (MASK) {
       const int j = jw + 8 * (i >> 2) + 4 * h + (i & 3);
       bool ok = pd.ok && j <= pd.rowc;
       bool allowed = j < a.P;
@@ -157,64 +178,77 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
       acc[i] += ok ? p : 0.f;
     }
   };
-  int slot = 0;
-  // One pipeline stage: block `it` (if it exists for this set) is multiplied into Sn while Sp's exponentials run.
-  auto stage = [&](int it, floatx16& Sn, Pending& pn, const floatx16& Sp, const Pending& pp, bool have_prev) {
-    const int b = 2 * it + set;
-    IMP_TICK(0);
-    __builtin_amdgcn_s_waitcnt(WAIT_BLOCK);   // this thread's pieces of block b have landed
-    IMP_TICK(1);
-    __syncthreads();                          // everybody's have; nobody reads the slot of block b - 2 any more
-    IMP_TICK(2);
-    issue_block(b + 2 * (NB - 1), slot == 0 ? NB - 1 : slot - 1);
-    IMP_TICK(3);
-    const int bc = min(b, n_blocks - 1);
-    const int qb = bc % n_qblocks;
-    const int row = row0 + qb * 32 + n;
-    pn.ok = row < a.N && b < n_blocks;   // an odd block count leaves set 1 one idle round
-    pn.rowc = min(row, a.N - 1);
-    pn.neg_lse2 = pn.ok ? lse_all[set][slot][wave][lane] * -kLog2e : -INFINITY;
+  int rd_slot = 0, rd_g = 0, rd_qb = set, rd_b = set;   // block the next read_pending / read_frag calls fetch
+  normalise(rd_g, rd_qb);
+  auto read_pending = [&](Pending& pd) {
+    const int row = row0 + rd_qb * 32 + n;
+    pd.ok = row < a.N && rd_b < n_blocks;   // an odd block count leaves set 1 one idle round
+    pd.rowc = min(row, a.N - 1);
+    const float lse_row = lse_all[set][rd_slot][wave][lane];   // read unconditionally: no branch, no early wait
+    pd.neg_lse2 = pd.ok ? lse_row * -kLog2e : -INFINITY;
     if constexpr (MASK) {
-      pn.video = pn.rowc < a.Nv;
-      const int frame = pn.video ? pn.rowc / a.P : 0;
-      pn.own0 = frame * a.P;
-      pn.prev = frame >= 1 ? pn.rowc - a.P : -1;
+      pd.video = pd.rowc < a.Nv;
+      const int frame = pd.video ? pd.rowc / a.P : 0;
+      pd.own0 = frame * a.P;
+      pd.prev = frame >= 1 ? pd.rowc - a.P : -1;
     }
-    const uint16_t* Qb = Qs[slot];
-    bf16x8 qf[KSTEPS];
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(Qb + kswz<D>(n, 2 * s + h));
+  };
+  auto read_frag = [&](Block& blk, int s) {
+    blk.qf[s] = *reinterpret_cast<const bf16x8*>(Qs[rd_slot] + kswz<D>(n, 2 * s + h));
+  };
+  auto advance_read = [&]() {
+    rd_slot = rd_slot == NB - 1 ? 0 : rd_slot + 1;
+    rd_b += 2;
+    rd_qb += 2;
+    normalise(rd_g, rd_qb);
+  };
+  // One stage: cur's MFMAs into Sn; Sp's exponentials; nxt <- fragments of the following block.
+  constexpr int WAIT_NEXT = ((NB - 3) * LPB & 15) | (((NB - 3) * LPB >> 4) << 14) | 0x0F70;   // vmcnt((NB-3) LPB)
+  // nxt still holds the pending data of the block before cur (the one Sp belongs to) on entry.
+  auto stage = [&](const Block& cur, Block& nxt, floatx16& Sn, const floatx16& Sp, bool have_prev) {
+    const Pending pp = nxt.pd;
+    __builtin_amdgcn_s_waitcnt(WAIT_NEXT);   // this thread's pieces of the following block have landed
+    __syncthreads();   // everybody's have; the slot of the previous block (read a stage ago) is free
 #pragma unroll
     for (int i = 0; i < 16; ++i) Sn[i] = 0.f;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) {
-      Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], Sn, 0, 0, 0);
+      Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], cur.qf[s], Sn, 0, 0, 0);
+      read_frag(nxt, s);
+      if (s == 0) read_pending(nxt.pd);
+      if (s == 1) issue_next(rd_slot < 2 ? rd_slot + NB - 2 : rd_slot - 2);   // the slot read a stage ago
       if (have_prev) {
 #pragma unroll
         for (int i = s * (16 / KSTEPS); i < (s + 1) * (16 / KSTEPS); ++i) exp_step(Sp, pp, i);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    slot = slot == NB - 1 ? 0 : slot + 1;
-    IMP_TICK(4);
+    advance_read();
   };
+  Block A, B;
   floatx16 S0, S1;
-  Pending p0, p1;
-  stage(0, S0, p0, S1, p1, false);
+  // block 0 of this set: wait for it alone, read it
+  __builtin_amdgcn_s_waitcnt(WAIT_BLOCK);
+  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < KSTEPS; ++s) read_frag(A, s);
+  read_pending(A.pd);
+  advance_read();
   IMP_STAMP(1);
+  stage(A, B, S0, S1, false);
   int it = 1;
   for (; it + 1 < n_iter; it += 2) {
-    stage(it, S1, p1, S0, p0, true);
-    stage(it + 1, S0, p0, S1, p1, true);
+    stage(B, A, S1, S0, true);
+    stage(A, B, S0, S1, true);
   }
   if (it < n_iter) {
-    stage(it, S1, p1, S0, p0, true);
+    stage(B, A, S1, S0, true);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) exp_step(S1, p1, i);
+    for (int i = 0; i < 16; ++i) exp_step(S1, B.pd, i);
   } else {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) exp_step(S0, p0, i);
+    for (int i = 0; i < 16; ++i) exp_step(S0, A.pd, i);
   }
   IMP_STAMP(2);
 #ifdef PUREKV_IMPORTANCE_TRACE
