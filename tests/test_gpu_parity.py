@@ -53,6 +53,16 @@ SMALL = {
     # one head x 8 row blocks (5 query tiles x 64 heads), d = 64
     "manyunits_g1": small_variant("manyunits_g1", n_frames=4, patch_h=16, patch_w=16, n_text=100, n_q_heads=64,
                                   n_kv_heads=64, head_dim=64),
+    # degenerate shapes: a single frame (first frame = own frame, no previous one), one patch per frame (every
+    # video key is its frame's only key), a single token, and a lone video token in front of a text
+    "oneframe_1f": small_variant("oneframe_1f", n_frames=1, patch_h=6, patch_w=6, n_text=10, n_q_heads=4,
+                                 n_kv_heads=2, head_dim=128),
+    "onepatch_9f": small_variant("onepatch_9f", n_frames=9, patch_h=1, patch_w=1, n_text=3, n_q_heads=2,
+                                 n_kv_heads=1, head_dim=64),
+    "single_token": small_variant("single_token", n_frames=1, patch_h=1, patch_w=1, n_text=0, n_q_heads=3,
+                                  n_kv_heads=3, head_dim=128),
+    "mostly_text": small_variant("mostly_text", n_frames=1, patch_h=1, patch_w=1, n_text=200, n_q_heads=8,
+                                 n_kv_heads=1, head_dim=64),
 }
 
 
@@ -106,6 +116,8 @@ def test_prefill_custom_scale():
     ("tiny_4f", 0, 32), ("tiny_4f", 3, 32), ("tiny_4f", 3, 100), ("tiny_4f", 2, 200), ("tiny_4f", 0, 288),
     ("ragged_3f", 3, 19), ("ragged_3f", 1, 50), ("straddle_3f", 3, 70), ("straddle_3f", 0, 700),
     ("notext_5f", 3, 33), ("longtext_2f", 0, 2100),
+    ("oneframe_1f", 3, 10), ("oneframe_1f", 3, 30), ("oneframe_1f", 2, 46), ("onepatch_9f", 3, 5), ("onepatch_9f", 1, 12),
+    ("single_token", 3, 1), ("mostly_text", 3, 64), ("mostly_text", 3, 201), ("heads7_3f", 3, 900), ("heads3_4f", 2, 150),
 ])
 def test_importance_matches_oracle(name, pattern, w):
     wl = SMALL[name]

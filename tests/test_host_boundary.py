@@ -185,7 +185,8 @@ def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern, n_wg=256):
 
 @pytest.mark.parametrize("pattern", [0, 1, 2, 3])
 @pytest.mark.parametrize("heads", [(4, 2), (7, 1), (3, 3), (12, 2)])
-@pytest.mark.parametrize("shape", [(4, 8, 8, 32), (3, 5, 7, 19), (1, 9, 9, 0), (5, 16, 16, 200), (2, 24, 24, 1)])
+@pytest.mark.parametrize("shape", [(4, 8, 8, 32), (3, 5, 7, 19), (1, 9, 9, 0), (5, 16, 16, 200), (2, 24, 24, 1),
+                                   (9, 1, 1, 3), (1, 1, 1, 0), (1, 1, 1, 200), (1, 6, 6, 10)])
 def test_plan_lists_match_oracle_mask_small(shape, pattern, heads):
     F, ph, pw, T = shape
     _check_plan_against_oracle(F, ph, pw, T, heads[0], heads[1], 64, pattern, n_wg=16)
