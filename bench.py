@@ -217,6 +217,19 @@ def main() -> int:
     stage_ms = {name: float(np.mean([events[s][i].elapsed_time(events[s][i + 1]) for s in range(args.steps)]))
                 for i, name in enumerate(STAGES)}
 
+    # ---- the same step recorded once in a HIP graph and replayed (no events inside): launch gaps removed ----
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(10):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / args.steps
+
     # ---- back-to-back launches of single stages (no other kernel in between): per-call durations ----
     def time_calls(fn, reps=30):
         for _ in range(3):
@@ -259,6 +272,7 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_graph_replay": round(ms_per_step_graph, 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

@@ -1,0 +1,81 @@
+"""The whole path captured in a HIP graph: every entry point is asynchronous on the caller's stream, allocates
+nothing and clears nothing with memset nodes, so one layer pair (dense low layer with importance, selection and
+compaction; ST-SpAttn high layer with selection, compaction and a decode step) can be recorded once and replayed.
+Each replay, on new input contents and with eager work and synchronisations in between, must reproduce the eager
+results bit for bit (all kernels are deterministic)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_25600_amd as pk
+from workloads import generate
+from workloads.synth import small_variant
+
+from gpu_util import bits_of, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def test_captured_step_replays_bit_exactly():
+    # 7 stacked heads, text rows split into slices (the merge kernel runs), decode spans several chunks
+    wl = small_variant("graph_3f", n_frames=3, patch_h=10, patch_w=10, n_text=900, n_q_heads=7, n_kv_heads=1,
+                       head_dim=128)
+    n, w, d, hq, hkv = wl.n_tokens, 64, wl.head_dim, wl.n_q_heads, wl.n_kv_heads
+    h = pk.purekv_budget(n, w, 0.5)
+    n_keep, cap = h + w, h + w + 1
+    dense, st = pk.Plan.for_workload(wl, pk.PATTERN_DENSE), pk.Plan.for_workload(wl, pk.PATTERN_ST)
+    assert st.counts()["n_split_qtiles"] > 0
+
+    def inputs(seed):
+        lo, hi = generate(wl, seed=seed, decode_steps=1), generate(wl, seed=seed + 100, decode_steps=1)
+        return [to_dev(x) for x in (lo.q, lo.k, lo.v, hi.q, hi.k, hi.v, hi.q_new[0], hi.k_new[0], hi.v_new[0])]
+
+    static = inputs(1)
+    q0, k0, v0, q1, k1, v1, qn, kn, vn = static
+    dev = q0.device
+    out0, out1 = torch.empty_like(q0), torch.empty_like(q1)
+    lse = torch.empty((hq, n), dtype=torch.float32, device=dev)
+    c = torch.empty((hkv, n - w), dtype=torch.float32, device=dev)
+    idx0 = torch.empty((1, hkv, n_keep), dtype=torch.int32, device=dev)
+    idx1 = torch.empty_like(idx0)
+    kc0 = torch.zeros((hkv, cap, d), dtype=torch.bfloat16, device=dev)
+    vc0, kc1, vc1 = torch.zeros_like(kc0), torch.zeros_like(kc0), torch.zeros_like(kc0)
+    o_dec = torch.empty((hq, d), dtype=torch.bfloat16, device=dev)
+    outputs = [out0, lse, c, idx0, kc0, vc0, out1, idx1, kc1, vc1, o_dec]
+
+    def step():
+        pk.purekv_st_spattn_prefill(dense, q0, k0, v0, out=out0, lse=lse)
+        pk.purekv_lowlayer_importance(dense, q0, k0, lse, w, c_out=c)
+        pk.purekv_topk_select(dense, c, v0, w, h, idx_out=idx0)
+        pk.purekv_kv_compact(dense, k0, v0, idx0[0], cap=cap, kc=kc0, vc=vc0)
+        pk.purekv_st_spattn_prefill(st, q1, k1, v1, out=out1)
+        pk.purekv_topk_select(st, c, v1, w, h, idx_out=idx1)
+        pk.purekv_kv_compact(st, k1, v1, idx1[0], cap=cap, kc=kc1, vc=vc1)
+        pk.purekv_decode_step(st, qn, kn, vn, kc1, vc1, n_keep, out=o_dec)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.view(torch.int16).cpu().numpy().copy() if t.dtype == torch.bfloat16 else t.cpu().numpy().copy()
+                for t in outputs]
+
+    step()   # eager warm-up: workspaces exist, kernel attributes are set
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+
+    for rnd, seed in enumerate((1, 2, 3, 2)):
+        for dst, src in zip(static, inputs(seed)):
+            dst.copy_(src)
+        step()
+        want = snapshot()
+        for t in outputs:   # nothing of the eager run may survive into the comparison
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        names = ["out0", "lse", "c", "idx0", "kc0", "vc0", "out1", "idx1", "kc1", "vc1", "o_dec"]
+        for name, a, b in zip(names, got, want):
+            assert np.array_equal(a, b), f"replay {rnd} (seed {seed}): {name} differs from the eager run"
+    assert np.array_equal(bits_of(kc1)[:, n_keep], bits_of(kn))   # the decode step's append is part of the graph
