@@ -228,6 +228,8 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
   };
   Block A, B;
   floatx16 S0, S1;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) S1[i] = 0.f;   // passed to the first stage, which reads nothing of it
   // block 0 of this set: wait for it alone, read it
   __builtin_amdgcn_s_waitcnt(WAIT_BLOCK);
   __syncthreads();
