@@ -75,6 +75,12 @@ def main() -> int:
     ap.add_argument("--batched-layers", type=int, default=26, help="layers per batched top-k/compaction launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=28, help="query heads in the oracle's timed sample")
+    ap.add_argument("--stack", action="store_true",
+                    help="time the whole layer stack of the workload (purekv_stack_layer per layer, then one batched "
+                         "selection and compaction) instead of the one-layer-pair step; prints its own JSON line")
+    ap.add_argument("--stack-layers", type=int, default=0, help="layers of the --stack run (default: the workload's)")
+    ap.add_argument("--stack-dense", type=int, default=0, help="dense low layers of the --stack run (default: the "
+                    "workload's, else 1); the last of them estimates the importance")
     ap.add_argument("--only-stage", default=None, choices=STAGES + ["copy_calib", "topk_batched", "compact_batched", "mfma_calib"],
                     help="profiling aid: after one full warm-up step run only this stage --steps times and exit")
     args = ap.parse_args()
@@ -135,6 +141,59 @@ def main() -> int:
         mark(7)
         pk.purekv_decode_step(st, q_new, k_new, v_new, kc1, vc1, n_keep, out=o_dec)
         mark(8)
+
+    if args.stack:
+        L = args.stack_layers or max(wl.n_layers, 2)
+        st_layer = max(1, min(args.stack_dense or wl.n_dense_layers or 1, L))
+        clie = st_layer - 1
+        stack = pk.Stack(L, clie, st_layer, w, h)
+        # per-layer data derived on the device from the two generated layers (rolled along the head axis)
+        k_all = torch.empty((L, hkv, n, d), dtype=torch.bfloat16, device=dev)
+        v_all, q_all = torch.empty_like(k_all), torch.empty((L, hq, n, d), dtype=torch.bfloat16, device=dev)
+        for l in range(L):
+            src_q, src_k, src_v = (q0, k0, v0) if l < st_layer else (q1, k1, v1)
+            q_all[l], k_all[l], v_all[l] = src_q.roll(l, dims=0), src_k.roll(l, dims=0), src_v.roll(l, dims=0)
+        out = torch.empty_like(q0)   # consumed by the rest of the model layer by layer: one buffer
+        c_all = torch.empty((clie + 1, hkv, n - w), dtype=torch.float32, device=dev)
+        idx_all = torch.empty((L, hkv, n_keep), dtype=torch.int32, device=dev)
+        kc_all = torch.empty((L, hkv, n_keep, d), dtype=torch.bfloat16, device=dev)
+        vc_all = torch.empty_like(kc_all)
+
+        def run_stack():
+            for l in range(L):
+                pk.purekv_stack_layer(dense, st, stack, l, q_all[l], k_all[l], v_all[l], out, lse, c_all)
+            pk.purekv_stack_select_compact(dense, st, stack, c_all, k_all, v_all, idx_all, kc_all, vc_all)
+
+        reps = max(3, min(args.steps, 20))
+        for _ in range(2):
+            run_stack()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            run_stack()
+        torch.cuda.synchronize()
+        ms_eager = (time.perf_counter() - t0) * 1e3 / reps
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run_stack()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_graph = (time.perf_counter() - t0) * 1e3 / reps
+        flops = st_layer * dense.kept_tile_flops() + (L - st_layer) * st.kept_tile_flops()
+        print(json.dumps({
+            "metric": "layer_stack_prefill_select_compact_ms", "value": round(ms_graph, 3), "unit": "ms",
+            "higher_is_better": False, "n_gpus": 1, "steps": reps, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"{wl.name}: {n} tokens, {hq}q/{hkv}kv heads, d={d}; {L} layers, dense below layer "
+                                   f"{st_layer}, C from layer {clie}, keep ratio {args.ratio} (h={h}, w={w})"},
+            "ms_eager": round(ms_eager, 3), "ms_one_graph_launch": round(ms_graph, 3),
+            "prefill_tokens_per_s": round(n / (ms_graph * 1e-3), 1),
+            "kept_tile_tflops_whole_stack": round(flops / (ms_graph * 1e-3) / 1e12, 1),
+        }))
+        return 0
 
     def make_batched(L):
         """Buffers of L high layers (Eq. 4: every high layer scores with the same C and its own V); distinct data

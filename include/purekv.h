@@ -197,6 +197,42 @@ PUREKV_API int purekv_decode_step(const purekv_plan_t* plan, const void* q_new, 
                                   size_t ws_bytes, void* stream);
 
 
+/*
+ * Layer stack (Sec. 3.1 and the layer-index study of the hyperparameter analysis, Sec. 4.5): which layer runs which attention and whose
+ * importance estimate drives whose selection.
+ *   layers 0 .. st_layer-1 run dense causal attention (Eq. 1), layers st_layer .. n_layers-1 ST-SpAttn (Sec. 3.2);
+ *   layers 0 .. clie_layer also emit their recent-window column sums C (Eq. 2): a layer below clie_layer is
+ *   selected with its own C (Eq. 3), layer clie_layer and every later layer with C of layer clie_layer and
+ *   its own V (cross-layer importance estimation, Eq. 4).  0 <= clie_layer < st_layer <= n_layers: the estimating
+ *   layer computes attention scores, so it lies below the first sparse layer.
+ * purekv_stack_layer runs one layer's prefill (and importance, where the layer emits C) as the model reaches it;
+ * purekv_stack_select_compact then selects and compacts all layers at once: one launch per layer below
+ * clie_layer, ONE batched selection for the n_layers - clie_layer layers that share C, ONE compaction for all.
+ *   q, k, v, out: that layer's tensors, as for purekv_st_spattn_prefill.   st_plan may be NULL when st_layer ==
+ *   n_layers; both plans must describe the same tensor shape (dense_plan with the dense pattern).
+ *   lse   fp32 [Hq, N]: scratch, needed (and overwritten) by layers <= clie_layer, else may be NULL.
+ *   c_all fp32 [clie_layer + 1, Hkv, N - w]: layer l <= clie_layer writes block l.
+ *   k_all, v_all: bf16, layer l at + l * kv_layer_stride elements, each [Hkv, N, d].
+ *   idx_all int32 [n_layers, Hkv, h + w];  kc_all, vc_all bf16 [n_layers, Hkv, cap, d], cap >= h + w.
+ *   ws: at least purekv_stack_workspace_bytes() bytes serve every call of the stack.
+ */
+typedef struct {
+  int32_t n_layers;   /* L >= 1                                                            */
+  int32_t clie_layer; /* layer whose C is shared by itself and all later layers            */
+  int32_t st_layer;   /* first ST-SpAttn layer (== n_layers: every layer dense)            */
+  int32_t w, h;       /* recent window and top-h budget, as for purekv_topk_select         */
+} purekv_stack_t;
+PUREKV_API size_t purekv_stack_workspace_bytes(const purekv_plan_t* dense_plan, const purekv_plan_t* st_plan,
+                                               const purekv_stack_t* stack);
+PUREKV_API int purekv_stack_layer(const purekv_plan_t* dense_plan, const purekv_plan_t* st_plan,
+                                  const purekv_stack_t* stack, int32_t layer, const void* q, const void* k,
+                                  const void* v, void* out, float* lse, float* c_all, void* ws, size_t ws_bytes,
+                                  void* stream);
+PUREKV_API int purekv_stack_select_compact(const purekv_plan_t* dense_plan, const purekv_stack_t* stack,
+                                           const float* c_all, const void* k_all, const void* v_all,
+                                           int64_t kv_layer_stride, int32_t* idx_all, void* kc_all, void* vc_all,
+                                           int32_t cap, void* ws, size_t ws_bytes, void* stream);
+
 /* h = max(0, floor(ratio * n) - w): the keep budget counts the recent window (20 % budget = 5.0x). */
 PUREKV_API int32_t purekv_budget(int32_t n, int32_t w, double ratio);
 

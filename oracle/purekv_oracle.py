@@ -169,6 +169,19 @@ def topk_select(s: np.ndarray, h: int, n: int, w: int) -> np.ndarray:
     return idx
 
 
+def stack_pattern(layer: int, st_layer: int, sparse_pattern: int = 3) -> int:
+    """Attention pattern of a layer of the stack: dense below the first ST-SpAttn layer (Sec. 3.1: the lower layers
+    compute attention scores), the sparse pattern from there on (Sec. 3.2; layer-index study of Sec. 4.5)."""
+    return 0 if layer < st_layer else sparse_pattern
+
+
+def stack_selection(c_layers, v_layers, clie_layer: int, h: int, n: int, w: int):
+    """Kept indices of every layer of a stack.  A layer below the estimating layer has column sums of its own and is
+    scored with them (Eq. 3); the estimating layer and every later one are scored with the estimating layer's column
+    sums and their own V (Eq. 4).  c_layers[l] is only read for l <= clie_layer."""
+    return [topk_select(vnorm_scores(c_layers[min(l, clie_layer)], v), h, n, w) for l, v in enumerate(v_layers)]
+
+
 def compact(k_bits: np.ndarray, v_bits: np.ndarray, idx: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """Kc[kv, r, :] = K[kv, idx[kv, r], :] on raw bit patterns; V likewise."""
     hkv = k_bits.shape[0]

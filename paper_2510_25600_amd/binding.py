@@ -60,6 +60,9 @@ def _load() -> ctypes.CDLL:
         "purekv_kv_append": (c_int, [P, P, P, P, P, c_int32, c_int32, P]),
         "purekv_decode_attn": (c_int, [P, P, P, P, c_int32, c_int32, P, P, c_size_t, P]),
         "purekv_decode_step": (c_int, [P, P, P, P, P, P, c_int32, c_int32, P, P, c_size_t, P]),
+        "purekv_stack_workspace_bytes": (c_size_t, [P, P, P]),
+        "purekv_stack_layer": (c_int, [P, P, P, c_int32, P, P, P, P, P, P, P, c_size_t, P]),
+        "purekv_stack_select_compact": (c_int, [P, P, P, P, P, c_int64, P, P, P, c_int32, P, c_size_t, P]),
         "purekv_budget": (c_int32, [c_int32, c_int32, c_double]),
         "purekv_plan_kept_tile_flops": (c_double, [P]),
         "purekv_plan_mask_flops": (c_double, [P]),
@@ -79,7 +82,8 @@ EXPORTS = (
     "purekv_plan_create", "purekv_plan_create_host", "purekv_plan_destroy", "purekv_plan_counts",
     "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_workspace_bytes", "purekv_st_spattn_prefill",
     "purekv_lowlayer_importance", "purekv_topk_select", "purekv_kv_compact", "purekv_kv_append",
-    "purekv_decode_attn", "purekv_decode_step", "purekv_budget", "purekv_plan_kept_tile_flops", "purekv_plan_mask_flops",
+    "purekv_decode_attn", "purekv_decode_step", "purekv_stack_workspace_bytes", "purekv_stack_layer",
+    "purekv_stack_select_compact", "purekv_budget", "purekv_plan_kept_tile_flops", "purekv_plan_mask_flops",
     "purekv_calib_mfma", "purekv_calib_mfma_flops", "purekv_strerror",
 )
 
@@ -313,6 +317,38 @@ def purekv_decode_step(plan: Plan, q_new: torch.Tensor, k_new: torch.Tensor, v_n
                                    vc.data_ptr(), n_cached, cap, out.data_ptr(), _ptr(ws), nb, _stream()),
            "purekv_decode_step")
     return out
+
+
+class Stack(ctypes.Structure):
+    """purekv_stack_t: which layer runs which attention and whose C drives whose selection."""
+    _fields_ = [("n_layers", c_int32), ("clie_layer", c_int32), ("st_layer", c_int32), ("w", c_int32), ("h", c_int32)]
+
+
+def _stack_ws(dense: Plan, st: Optional[Plan], stack: Stack, device) -> tuple:
+    nb = int(_lib.purekv_stack_workspace_bytes(dense.handle, st.handle if st is not None else None, byref(stack)))
+    return nb, dense._workspace(-1, nb, device)
+
+
+def purekv_stack_layer(dense: Plan, st: Optional[Plan], stack: Stack, layer: int, q: torch.Tensor, k: torch.Tensor,
+                       v: torch.Tensor, out: torch.Tensor, lse: Optional[torch.Tensor], c_all: Optional[torch.Tensor]):
+    """One layer of the stack's prefill (plus importance on the layers that emit C)."""
+    _dev_bf16(q, "q"), _dev_bf16(k, "k"), _dev_bf16(v, "v"), _dev_bf16(out, "out")
+    nb, ws = _stack_ws(dense, st, stack, q.device)
+    _check(_lib.purekv_stack_layer(dense.handle, st.handle if st is not None else None, byref(stack), layer,
+                                   q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), _ptr(lse), _ptr(c_all),
+                                   _ptr(ws), nb, _stream()), "purekv_stack_layer")
+    return out
+
+
+def purekv_stack_select_compact(dense: Plan, st: Optional[Plan], stack: Stack, c_all: torch.Tensor, k_all: torch.Tensor,
+                                v_all: torch.Tensor, idx_all: torch.Tensor, kc_all: torch.Tensor, vc_all: torch.Tensor):
+    """Selection and compaction of all layers of the stack; k_all, v_all [L, Hkv, N, d], kc_all, vc_all [L, Hkv, cap, d]."""
+    _dev_bf16(k_all, "k_all"), _dev_bf16(v_all, "v_all"), _dev_bf16(kc_all, "kc_all"), _dev_bf16(vc_all, "vc_all")
+    nb, ws = _stack_ws(dense, st, stack, k_all.device)
+    _check(_lib.purekv_stack_select_compact(dense.handle, byref(stack), _ptr(c_all), k_all.data_ptr(), v_all.data_ptr(),
+                                            k_all.stride(0), idx_all.data_ptr(), kc_all.data_ptr(), vc_all.data_ptr(),
+                                            kc_all.shape[-2], _ptr(ws), nb, _stream()), "purekv_stack_select_compact")
+    return idx_all, kc_all, vc_all
 
 
 def purekv_calib_mfma(plan: Plan, mix: int, random_operands: bool, iters: int,

@@ -1,4 +1,5 @@
 // C-ABI entry points: argument validation (host only, before any GPU call), plan life cycle, dispatch.
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -259,6 +260,83 @@ int purekv_decode_step(const purekv_plan_t* p, const void* q_new, const void* k_
   if (n_cached < 0 || n_cached >= cap) return PUREKV_EINVAL;
   if (ws == nullptr || ws_bytes < decode_ws_bytes(*p, cap)) return PUREKV_EWORKSPACE;
   return launch_decode(*p, q_new, k_new, v_new, kc, vc, n_cached + 1, cap, out, ws, static_cast<hipStream_t>(stream));
+}
+
+// ---- layer stack: which layer runs which attention, which C drives which layer's selection ----
+static int check_stack(const purekv_plan_t* dense, const purekv_plan_t* st, const purekv_stack_t* s) {
+  if (!launchable(dense) || s == nullptr) return PUREKV_EINVAL;
+  if (s->n_layers < 1 || s->clie_layer < 0 || s->clie_layer >= s->st_layer || s->st_layer > s->n_layers)
+    return PUREKV_EINVAL;
+  const Geometry& a = dense->g;
+  if (a.pattern != PUREKV_PATTERN_DENSE) return PUREKV_EINVAL;
+  if (s->w < 1 || s->w > a.N || s->h < 0 || s->h > a.N - s->w) return PUREKV_EINVAL;
+  if (s->st_layer < s->n_layers) {   // a sparse plan is needed and must describe the same tensors
+    if (!launchable(st)) return PUREKV_EINVAL;
+    const Geometry& b = st->g;
+    if (a.N != b.N || a.Nv != b.Nv || a.P != b.P || a.Hq != b.Hq || a.Hkv != b.Hkv || a.d != b.d || a.scale != b.scale ||
+        dense->device != st->device)
+      return PUREKV_EINVAL;
+  }
+  return PUREKV_OK;
+}
+
+size_t purekv_stack_workspace_bytes(const purekv_plan_t* dense, const purekv_plan_t* st, const purekv_stack_t* s) {
+  if (check_stack(dense, st, s) != PUREKV_OK) return 0;
+  size_t need = std::max(prefill_ws_bytes(*dense), topk_ws_bytes(*dense, s->n_layers - s->clie_layer, s->w));
+  if (s->st_layer < s->n_layers) need = std::max(need, prefill_ws_bytes(*st));
+  return need;
+}
+
+int purekv_stack_layer(const purekv_plan_t* dense, const purekv_plan_t* st, const purekv_stack_t* s, int32_t layer,
+                       const void* q, const void* k, const void* v, void* out, float* lse, float* c_all, void* ws,
+                       size_t ws_bytes, void* stream) {
+  const int rc = check_stack(dense, st, s);
+  if (rc != PUREKV_OK) return rc;
+  if (layer < 0 || layer >= s->n_layers || q == nullptr || k == nullptr || v == nullptr || out == nullptr)
+    return PUREKV_EINVAL;
+  const bool sparse = layer >= s->st_layer, emits_c = layer <= s->clie_layer;
+  const purekv_plan_t* p = sparse ? st : dense;
+  const int n_keys = p->g.N - s->w;
+  if (emits_c && (lse == nullptr || (c_all == nullptr && n_keys > 0))) return PUREKV_EINVAL;
+  const size_t need = prefill_ws_bytes(*p);
+  if (need > 0 && (ws == nullptr || ws_bytes < need)) return PUREKV_EWORKSPACE;
+  hipStream_t sm = static_cast<hipStream_t>(stream);
+  const int rp = launch_prefill(*p, q, k, v, out, emits_c ? lse : nullptr, ws, sm);
+  if (rp != PUREKV_OK || !emits_c) return rp;
+  return launch_importance(*p, q, k, lse, s->w, c_all + (size_t)layer * p->g.Hkv * n_keys, sm);
+}
+
+int purekv_stack_select_compact(const purekv_plan_t* dense, const purekv_stack_t* s, const float* c_all, const void* k_all,
+                                const void* v_all, int64_t kv_layer_stride, int32_t* idx_all, void* kc_all, void* vc_all,
+                                int32_t cap, void* ws, size_t ws_bytes, void* stream) {
+  if (!launchable(dense) || s == nullptr) return PUREKV_EINVAL;
+  if (s->n_layers < 1 || s->clie_layer < 0 || s->clie_layer >= s->st_layer || s->st_layer > s->n_layers)
+    return PUREKV_EINVAL;
+  const Geometry& g = dense->g;
+  if (s->w < 1 || s->w > g.N || s->h < 0 || s->h > g.N - s->w) return PUREKV_EINVAL;
+  const int n_keys = g.N - s->w, n_keep = s->h + s->w, L = s->n_layers, n_shared = L - s->clie_layer;
+  if (k_all == nullptr || v_all == nullptr || idx_all == nullptr || kc_all == nullptr || vc_all == nullptr)
+    return PUREKV_EINVAL;
+  if (c_all == nullptr && n_keys > 0) return PUREKV_EINVAL;
+  if (cap < n_keep) return PUREKV_EINVAL;
+  if (L > 1 && kv_layer_stride < (int64_t)g.Hkv * g.N * g.d) return PUREKV_EINVAL;
+  const size_t need = topk_ws_bytes(*dense, n_shared, s->w);
+  if (need > 0 && (ws == nullptr || ws_bytes < need)) return PUREKV_EWORKSPACE;
+  hipStream_t sm = static_cast<hipStream_t>(stream);
+  const uint16_t* vb = static_cast<const uint16_t*>(v_all);
+  const size_t c_stride = (size_t)g.Hkv * n_keys, idx_stride = (size_t)g.Hkv * n_keep;
+  // layers below the estimating one have attention scores of their own (Eq. 3) ...
+  for (int l = 0; l < s->clie_layer; ++l) {
+    const int rc = launch_topk(*dense, c_all + l * c_stride, vb + (size_t)l * kv_layer_stride, 0, 1, s->w, s->h,
+                               idx_all + l * idx_stride, nullptr, ws, sm);
+    if (rc != PUREKV_OK) return rc;
+  }
+  // ... it and every later layer share its C, each with its own V (Eq. 4): one batched call
+  const int rc = launch_topk(*dense, c_all + (size_t)s->clie_layer * c_stride, vb + (size_t)s->clie_layer * kv_layer_stride,
+                             kv_layer_stride, n_shared, s->w, s->h, idx_all + (size_t)s->clie_layer * idx_stride, nullptr,
+                             ws, sm);
+  if (rc != PUREKV_OK) return rc;
+  return launch_compact(*dense, k_all, v_all, kv_layer_stride, L, idx_all, n_keep, kc_all, vc_all, cap, sm);
 }
 
 int purekv_calib_mfma(const purekv_plan_t* p, int mix, int random_operands, int32_t iters, float* sink, uint64_t* ticks,

@@ -6,6 +6,8 @@ compacted K/V bit-exact given the indices.
 """
 import math
 
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -335,6 +337,20 @@ def test_gpu_argument_errors():
     assert lib.purekv_decode_step(plan.handle, P(q), P(k), P(v), P(k), P(v), 57, 57, P(q), P(c), 1 << 20, None) == pk.EINVAL
     assert lib.purekv_decode_step(plan.handle, P(q), None, P(v), P(k), P(v), 5, 57, P(q), P(c), 1 << 20, None) == pk.EINVAL
     assert lib.purekv_decode_step(plan.handle, P(q), P(k), P(v), P(k), P(v), 5, 57, P(q), None, 0, None) == pk.EWORKSPACE
+    dense_plan = _plan(wl, 0)
+    for bad in (pk.Stack(0, 0, 1, 32, 25), pk.Stack(4, 2, 2, 32, 25), pk.Stack(4, 1, 5, 32, 25), pk.Stack(4, 1, 2, 0, 25),
+                pk.Stack(4, 1, 2, 32, 257)):
+        assert lib.purekv_stack_layer(dense_plan.handle, plan.handle, ctypes.byref(bad), 0, P(q), P(k), P(v), P(q), P(c),
+                                      P(c), None, 0, None) == pk.EINVAL
+    good = pk.Stack(4, 1, 2, 32, 25)
+    args = (P(q), P(k), P(v), P(q), P(c), P(c), None, 0, None)
+    assert lib.purekv_stack_layer(plan.handle, plan.handle, ctypes.byref(good), 0, *args) == pk.EINVAL   # not dense
+    assert lib.purekv_stack_layer(dense_plan.handle, None, ctypes.byref(good), 3, *args) == pk.EINVAL    # needs ST plan
+    assert lib.purekv_stack_layer(dense_plan.handle, plan.handle, ctypes.byref(good), 4, *args) == pk.EINVAL
+    assert lib.purekv_stack_layer(dense_plan.handle, plan.handle, ctypes.byref(good), 0, P(q), P(k), P(v), P(q), None,
+                                  P(c), None, 0, None) == pk.EINVAL   # a layer that emits C needs the LSE scratch
+    assert lib.purekv_stack_select_compact(dense_plan.handle, ctypes.byref(good), P(c), P(k), P(v), 0, P(idx), P(k), P(v),
+                                           57, None, 0, None) == pk.EINVAL   # four layers need a layer stride
     assert lib.purekv_calib_mfma(plan.handle, 3, 0, 10, P(c), P(c), None) == pk.EINVAL
     assert lib.purekv_calib_mfma(plan.handle, 0, 0, 0, P(c), P(c), None) == pk.EINVAL
     assert lib.purekv_calib_mfma(plan.handle, 0, 0, 10, None, P(c), None) == pk.EINVAL
@@ -360,3 +376,50 @@ def test_calibration_loop_runs_and_reports_its_clock(mix):
         cyc, ref = ticks.tolist()
         assert cyc >= 200 * 16 * 32 and ref > 0          # an MFMA of this shape holds the pipe 32 cycles
         assert 0.05 < cyc / ref / 10.0 < 3.0             # GHz
+
+
+@pytest.mark.parametrize("clie,st_layer,layers", [(1, 3, 5), (0, 1, 3), (2, 3, 3)])
+def test_layer_stack_matches_oracle(clie, st_layer, layers):
+    """Layer stack: dense layers below st_layer, ST-SpAttn from there on; layers <= clie emit column sums, a
+    layer below clie is selected with its own, the rest with layer clie's and their own V; one batched
+    selection and one compaction for the whole stack.  Every layer has data of its own (seed = 40 + layer)."""
+    wl = SMALL["straddle_3f"]
+    n, w, hkv, d = wl.n_tokens, wl.window, wl.n_kv_heads, wl.head_dim
+    h = orc.budget(n, w, 0.3)
+    data = [generate(wl, seed=40 + l) for l in range(layers)]
+    dense, st = _plan(wl, 0), _plan(wl, 3)
+    stack = pk.Stack(layers, clie, st_layer, w, h)
+    k_all = torch.stack([to_dev(x.k) for x in data])
+    v_all = torch.stack([to_dev(x.v) for x in data])
+    lse = torch.empty((wl.n_q_heads, n), dtype=torch.float32, device="cuda")
+    c_all = torch.full((clie + 1, hkv, n - w), float("nan"), dtype=torch.float32, device="cuda")
+    outs = []
+    for l, x in enumerate(data):
+        q = to_dev(x.q)
+        outs.append(pk.purekv_stack_layer(dense, st if st_layer < layers else None, stack, l, q, k_all[l], v_all[l],
+                                          torch.empty_like(q), lse, c_all))
+    cap = h + w + 2
+    idx_all = torch.empty((layers, hkv, h + w), dtype=torch.int32, device="cuda")
+    kc_all = torch.zeros((layers, hkv, cap, d), dtype=torch.bfloat16, device="cuda")
+    vc_all = torch.zeros_like(kc_all)
+    pk.purekv_stack_select_compact(dense, st, stack, c_all, k_all, v_all, idx_all, kc_all, vc_all)
+    torch.cuda.synchronize()
+
+    c_ref = []
+    for l, x in enumerate(data):
+        qf, kf, vf = F64(x.q), F64(x.k), F64(x.v)
+        pattern = orc.stack_pattern(l, st_layer)
+        ref, _ = orc.masked_attention(qf, kf, vf, wl.n_frames, wl.patches, wl.n_text, pattern)
+        check_attention(f64_of(outs[l]), ref, f"stack layer {l} pattern {pattern}")
+        if l <= clie:
+            c_ref.append(orc.window_column_sums(qf, kf, wl.n_frames, wl.patches, wl.n_text, 0, w))
+            got = f64_of(c_all[l])
+            assert np.all(np.abs(got - c_ref[l]) <= IMPORTANCE_REL * np.maximum(np.abs(c_ref[l]), 1e-12))
+    idx_ref = orc.stack_selection(c_ref, [F64(x.v) for x in data], clie, h, n, w)
+    for l, x in enumerate(data):
+        s_ref = orc.vnorm_scores(c_ref[min(l, clie)], F64(x.v))
+        got = idx_all[l].cpu().numpy()
+        check_kept_sets(got, idx_ref[l], s_ref, h)
+        kr, vr = orc.compact(x.k, x.v, got)   # compaction is a bit copy of what the GPU selected
+        assert np.array_equal(bits_of(kc_all[l])[:, :h + w], kr) and np.array_equal(bits_of(vc_all[l])[:, :h + w], vr)
+        assert not bits_of(kc_all[l])[:, h + w:].any()

@@ -79,6 +79,12 @@ def test_compute_calls_validate_before_touching_the_gpu():
     assert lib.purekv_calib_mfma(h, 0, 0, 10, one, one, None) == pk.EINVAL
     assert lib.purekv_calib_mfma_flops(None, 10) == 0.0
     assert lib.purekv_calib_mfma_flops(h, 10) == 2.0 * 32 * 32 * 16 * 16 * 10 * 8 * plan.counts()["n_workgroups"]
+    stack = pk.Stack(4, 1, 2, 8, 4)
+    assert lib.purekv_stack_layer(h, h, ctypes.byref(stack), 0, one, one, one, one, one, one, one, 1 << 20, None) == pk.EINVAL
+    assert lib.purekv_stack_select_compact(h, ctypes.byref(stack), one, one, one, 0, one, one, one, 16, one, 1 << 20,
+                                           None) == pk.EINVAL
+    assert lib.purekv_stack_workspace_bytes(h, h, ctypes.byref(stack)) == 0
+    assert lib.purekv_stack_workspace_bytes(None, None, None) == 0
     assert lib.purekv_workspace_bytes(None, pk.OP_PREFILL, 0, 0, 0) == 0
     c = (ctypes.c_int64 * 16)()
     assert lib.purekv_plan_counts(None, c) == pk.EINVAL and lib.purekv_plan_counts(h, None) == pk.EINVAL

@@ -313,3 +313,29 @@ def test_compaction_roundtrip_and_decode_equals_masked_full_attention():
         s[torch.from_numpy(~kept)] = -math.inf
         ref = (torch.softmax(s, 0).numpy() @ vfull)
         assert np.abs(o[hq] - ref).max() < 1e-12
+
+
+def test_stack_selection_shares_the_estimating_layers_column_sums():
+    """Layer stack: a layer below the estimating layer is selected with its own column sums, the estimating
+    layer and every later one with the estimating layer's.  Pinned by construction: every layer gets a C that
+    puts all its mass on a set of keys of its own, and the same all-ones V, so the kept set names the C that
+    was used; a V that zeroes one key in one layer only must drop that key there and nowhere else."""
+    n, w, h, hkv, d, layers, clie = 40, 4, 5, 2, 8, 5, 2
+    rng = np.random.default_rng(9)
+    hot = [np.sort(rng.choice(n - w, size=h, replace=False)) for _ in range(layers)]
+    c_layers = []
+    for l in range(layers):
+        c = np.full((hkv, n - w), 1e-3)
+        c[:, hot[l]] = 1.0 + np.arange(h)
+        c_layers.append(c)
+    v_layers = [np.ones((hkv, n, d)) for _ in range(layers)]
+    idx = orc.stack_selection(c_layers, v_layers, clie, h, n, w)
+    for l in range(layers):
+        want = hot[min(l, clie)]
+        for kv in range(hkv):
+            assert np.array_equal(idx[l][kv, :h], want) and np.array_equal(idx[l][kv, h:], np.arange(n - w, n))
+    # Eq. 4 weighs the shared C with the layer's OWN V
+    v_layers[4][:, hot[clie][0], :] = 0.0
+    idx2 = orc.stack_selection(c_layers, v_layers, clie, h, n, w)
+    assert hot[clie][0] not in idx2[4][0, :h] and np.array_equal(idx2[3], idx[3])
+    assert [orc.stack_pattern(l, 3) for l in range(5)] == [0, 0, 0, 3, 3] and orc.stack_pattern(4, 5) == 0
