@@ -40,15 +40,8 @@ struct ImportanceArgs {
       a.trace[(blockIdx.x + gridDim.x * blockIdx.y) * 8 + 2 * (i) + 1] = __builtin_amdgcn_s_memrealtime(); \
     }                                                                                      \
   } while (0)
-#define IMP_TICK(i)                                                  \
-  do {                                                               \
-    const unsigned long long now__ = __builtin_readcyclecounter();   \
-    tick_sum[i] += now__ - tick_last;                                \
-    tick_last = now__;                                               \
-  } while (0)
 #else
 #define IMP_STAMP(i) do {} while (0)
-#define IMP_TICK(i) do {} while (0)
 #endif
 
 typedef __attribute__((address_space(3))) void* LdsPtr;
@@ -89,9 +82,6 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
   const int row0 = a.N - a.w;             // first window row
 
   IMP_STAMP(0);
-#ifdef PUREKV_IMPORTANCE_TRACE
-  unsigned long long tick_sum[5] = {0, 0, 0, 0, 0}, tick_last = __builtin_readcyclecounter();
-#endif
   bf16x8 kf[KSTEPS];
   {
     const int j = min(jw + n, a.N - 1);
@@ -253,10 +243,6 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
     for (int i = 0; i < 16; ++i) exp_step(S0, A.pd, i);
   }
   IMP_STAMP(2);
-#ifdef PUREKV_IMPORTANCE_TRACE
-  if ((threadIdx.x & 63) == 0 && blockIdx.x == 5 && blockIdx.y == 1)
-    for (int i = 0; i < 5; ++i) a.trace[256 * 8 + (threadIdx.x >> 6) * 8 + i] = tick_sum[i];
-#endif
   __builtin_amdgcn_s_waitcnt(0x0F70);   // the loads started past the end have landed before LDS is reused or freed
 
   // set 0 adds set 1's sums (same wavefront index, same lane: same keys and query slots), then
