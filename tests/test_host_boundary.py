@@ -209,3 +209,13 @@ def test_dense_plan_benchmark_shape():
     wl = WORKLOADS["qwen25vl_32f"]
     _check_plan_against_oracle(wl.n_frames, wl.patch_h, wl.patch_w, wl.n_text, wl.n_q_heads, wl.n_kv_heads,
                                wl.head_dim, 0)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: the bench says so and exits before touching torch or the GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
