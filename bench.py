@@ -221,6 +221,19 @@ def main() -> int:
         cyc, ref = (int(x) for x in ticks.tolist())
         return flops / (a.elapsed_time(b) * 1e-3) / 1e12, cyc / max(ref, 1) / 10.0
 
+    def step_calib(rows, iters=12000):
+        """Tile-step skeleton (see purekv_calib_tile_step): one warm launch, one timed.  (TFLOP/s, us per step, GHz)"""
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        pk.purekv_calib_tile_step(st, rows, iters, q0)
+        torch.cuda.synchronize()
+        a.record()
+        flops, ticks = pk.purekv_calib_tile_step(st, rows, iters, q0)
+        b.record()
+        torch.cuda.synchronize()
+        cyc, ref = (int(x) for x in ticks.tolist())
+        ms = a.elapsed_time(b)
+        return flops / (ms * 1e-3) / 1e12, ms * 1e3 / iters, cyc / max(ref, 1) / 10.0
+
     if args.only_stage == "mfma_calib":
         step()
         torch.cuda.synchronize()
@@ -230,6 +243,10 @@ def main() -> int:
                 tf, ghz = mfma_calib(mix, rnd)
                 print(f"{name:46s} {'random' if rnd else 'constant':8s} operands: {tf:7.1f} TFLOP/s at {ghz:.2f} GHz",
                       flush=True)
+        for rows in (32, 64):
+            tf, us, ghz = step_calib(rows)
+            print(f"tile-step skeleton, {256 // rows} wavefronts x {rows} rows, random operands: {tf:7.1f} TFLOP/s, "
+                  f"{us:.3f} us per step at {ghz:.2f} GHz", flush=True)
         return 0
 
     if args.only_stage is not None:
@@ -314,6 +331,7 @@ def main() -> int:
 
     # what the board sustains for the bare matrix instruction, constant and random operands (power limit)
     calib_const, calib_rand = mfma_calib(0, False), mfma_calib(0, True)
+    calib_step = step_calib(32)
 
     kept_flops, mask_flops = st.kept_tile_flops(), st.mask_flops()
     dense_kept = dense.kept_tile_flops()
@@ -370,6 +388,12 @@ def main() -> int:
                 "what": "register-resident v_mfma_f32_32x32x16_bf16 loop, 256 workgroups x 8 wavefronts, ~20 ms",
                 "constant_operands_tflops": round(calib_const[0], 1), "constant_operands_ghz": round(calib_const[1], 2),
                 "random_operands_tflops": round(calib_rand[0], 1), "random_operands_ghz": round(calib_rand[1], 2),
+            },
+            "tile_step_skeleton_measured": {
+                "what": "both products' MFMAs + LDS fragment reads + softmax vector work + 32 KB tile loads + one barrier "
+                        "per 256 rows x 64 keys, 8 wavefronts x 32 rows, random operands, nothing else",
+                "tflops": round(calib_step[0], 1), "us_per_tile_step": round(calib_step[1], 3),
+                "ghz": round(calib_step[2], 2),
             },
         },
         "context": "paper: 5.0x KV compression, 3.16x prefill speed-up, whole model on 1x A100 40GB (not comparable)",

@@ -258,6 +258,19 @@ PUREKV_API double purekv_plan_mask_flops(const purekv_plan_t* plan);
 PUREKV_API int purekv_calib_mfma(const purekv_plan_t* plan, int mix, int random_operands, int32_t iters, float* sink,
                                  uint64_t* ticks, void* stream);
 PUREKV_API double purekv_calib_mfma_flops(const purekv_plan_t* plan, int32_t iters);
+/*
+ * Second calibration loop: the skeleton of one attention tile step per compute unit (256 query rows x 64 keys,
+ * head_dim 128) -- both products' MFMAs, one 1 KB LDS fragment read per fragment, the softmax vector work of every
+ * score, 32 KB of K/V tile loads into LDS and one barrier per step, on pseudo-random operands; no masks, maxima,
+ * tables or output.  rows_per_wavefront 32: eight wavefronts, every fragment feeds one MFMA (the prefill kernel's
+ * shape); 64: four wavefronts, every fragment feeds two.  What a prefill kernel of this formulation can reach on
+ * this board is read against it.
+ *   src   device, 4 MiB of finite bf16 values (read as K/V tiles);  sink, ticks, iters, stream: as above.
+ * purekv_calib_tile_step_flops: 4 * 256 * 64 * 128 flops per step and workgroup.
+ */
+PUREKV_API int purekv_calib_tile_step(const purekv_plan_t* plan, int rows_per_wavefront, int32_t iters, const void* src,
+                                      float* sink, uint64_t* ticks, void* stream);
+PUREKV_API double purekv_calib_tile_step_flops(const purekv_plan_t* plan, int32_t iters);
 
 /* Static description of a status code; for PUREKV_EHIP the text of the last HIP error seen by this
  * thread is appended. */

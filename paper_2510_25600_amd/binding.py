@@ -68,6 +68,8 @@ def _load() -> ctypes.CDLL:
         "purekv_plan_mask_flops": (c_double, [P]),
         "purekv_calib_mfma": (c_int, [P, c_int, c_int, c_int32, P, P, P]),
         "purekv_calib_mfma_flops": (c_double, [P, c_int32]),
+        "purekv_calib_tile_step": (c_int, [P, c_int, c_int32, P, P, P, P]),
+        "purekv_calib_tile_step_flops": (c_double, [P, c_int32]),
         "purekv_strerror": (c_char_p, [c_int]),
     }
     for name, (res, args) in sig.items():
@@ -84,7 +86,8 @@ EXPORTS = (
     "purekv_lowlayer_importance", "purekv_topk_select", "purekv_kv_compact", "purekv_kv_append",
     "purekv_decode_attn", "purekv_decode_step", "purekv_stack_workspace_bytes", "purekv_stack_layer",
     "purekv_stack_select_compact", "purekv_budget", "purekv_plan_kept_tile_flops", "purekv_plan_mask_flops",
-    "purekv_calib_mfma", "purekv_calib_mfma_flops", "purekv_strerror",
+    "purekv_calib_mfma", "purekv_calib_mfma_flops", "purekv_calib_tile_step", "purekv_calib_tile_step_flops",
+    "purekv_strerror",
 )
 
 
@@ -364,3 +367,20 @@ def purekv_calib_mfma(plan: Plan, mix: int, random_operands: bool, iters: int,
     _check(_lib.purekv_calib_mfma(plan.handle, mix, int(bool(random_operands)), iters, sink.data_ptr(),
                                   ticks.data_ptr(), _stream()), "purekv_calib_mfma")
     return float(_lib.purekv_calib_mfma_flops(plan.handle, iters)), ticks
+
+
+def purekv_calib_tile_step(plan: Plan, rows_per_wavefront: int, iters: int, src: torch.Tensor,
+                           sink: Optional[torch.Tensor] = None, ticks: Optional[torch.Tensor] = None):
+    """Launches the tile-step skeleton once on the current stream (asynchronous).  `src`: bf16 device tensor of at
+    least 4 MiB of finite values.  Returns (flops of the launch, ticks) like purekv_calib_mfma."""
+    _dev_bf16(src, "src")
+    if src.numel() * 2 < (4 << 20):
+        raise ValueError("src must hold at least 4 MiB")
+    dev = src.device
+    if sink is None:
+        sink = torch.empty(512 * plan.counts()["n_workgroups"], dtype=torch.float32, device=dev)
+    if ticks is None:
+        ticks = torch.zeros(2, dtype=torch.int64, device=dev)
+    _check(_lib.purekv_calib_tile_step(plan.handle, rows_per_wavefront, iters, src.data_ptr(), sink.data_ptr(),
+                                       ticks.data_ptr(), _stream()), "purekv_calib_tile_step")
+    return float(_lib.purekv_calib_tile_step_flops(plan.handle, iters)), ticks

@@ -346,6 +346,17 @@ int purekv_calib_mfma(const purekv_plan_t* p, int mix, int random_operands, int3
   return launch_calib_mfma(*p, mix, random_operands != 0, iters, sink, ticks, static_cast<hipStream_t>(stream));
 }
 
+int purekv_calib_tile_step(const purekv_plan_t* p, int rows_per_wavefront, int32_t iters, const void* src, float* sink,
+                           uint64_t* ticks, void* stream) {
+  if (!launchable(p) || src == nullptr || sink == nullptr || ticks == nullptr) return PUREKV_EINVAL;
+  if ((rows_per_wavefront != 32 && rows_per_wavefront != 64) || iters < 1 || iters > (1 << 20)) return PUREKV_EINVAL;
+  return launch_calib_step(*p, rows_per_wavefront, iters, src, sink, ticks, static_cast<hipStream_t>(stream));
+}
+
+double purekv_calib_tile_step_flops(const purekv_plan_t* p, int32_t iters) {
+  return (p == nullptr || iters < 1) ? 0.0 : calib_step_flops(*p, iters);
+}
+
 double purekv_calib_mfma_flops(const purekv_plan_t* p, int32_t iters) {
   return (p == nullptr || iters < 1) ? 0.0 : calib_mfma_flops(*p, iters);
 }

@@ -80,10 +80,138 @@ __global__ __launch_bounds__(512, 1) void calib_mfma_kernel(float* sink, unsigne
   }
 }
 
+
+// Skeleton of one attention tile step per compute unit (256 query rows x 64 keys, head_dim 128): only what every
+// kernel of this formulation must issue -- 32 MFMAs per 32 rows, one 1 KB LDS fragment read per fragment, the
+// softmax vector work of a score (2 multiply-adds, 2 exponentials, 1 convert per MFMA of the score product), 32 KB
+// of K/V tile loads from L2 into LDS and one barrier -- no masks, maxima, row sums, tables or output.
+// RB = 1: 8 wavefronts of 32 rows (every fragment feeds one MFMA); RB = 2: 4 wavefronts of 64 rows (every fragment
+// feeds two, at one wavefront per SIMD).  Operands are pseudo-random; `src` supplies the tile loads.
+typedef __attribute__((address_space(3))) const void* CalibLdsPtr;
+template <int RB>
+__global__ __launch_bounds__(512 / RB) void calib_step_kernel(float* sink, unsigned long long* ticks, int iters,
+                                                             const char* src) {
+  constexpr int NW = 8 / RB;        // wavefronts
+  constexpr int NL = 32 / NW;       // 1 KB tile loads per wavefront and step
+  __shared__ __attribute__((aligned(16))) uint16_t kv[2][2][64 * 128];   // [buffer][K, V]
+  for (int i = threadIdx.x; i < 2 * 2 * 64 * 128; i += blockDim.x) {
+    const float r = ((int)((((uint32_t)i + 1u) * 2654435761u) >> 16 & 0xFFFFu) - 32768) * (1.0f / 32768.f);
+    (&kv[0][0][0])[i] = (uint16_t)(__float_as_uint(r) >> 16);
+  }
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  bf16x8 qf[RB][8];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t hsh = ((uint32_t)(lane * 8 + i) + (uint32_t)(s * 977 + rb * 131 + wave * 7919) + blockIdx.x * 31u) * 2654435761u;
+        qf[rb][s][i] = (__bf16)(((int)(hsh >> 16 & 0xFFFFu) - 32768) * (1.0f / 32768.f));
+      }
+  floatx16 S[RB][2], O[RB][4];
+  u32x4 P[RB][4];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[rb][h][i] = 0.f;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) O[rb][b][i] = 0.f;
+      P[rb][b] = u32x4{0x3e003e00u, 0x3e003e00u, 0x3e003e00u, 0x3e003e00u};
+    }
+  }
+  const float c1 = 0.5f, c2 = -6.f;   // scores ~ N(0, 3.8): probabilities spread over (2^-12, 1)
+  const int kq0 = kswz<128>(lane & 31, lane >> 5);
+  uint32_t pos = (blockIdx.x * 37u) & 127u;   // 128 positions of 32 KB = the 4 MB source
+  __syncthreads();
+  const unsigned long long t0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
+  for (int it = 0; it < iters; ++it) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's tile loads have landed
+    __syncthreads();
+    {   // tile loads of the next step into the other buffer, which everybody has finished reading
+      const uint32_t lds_base = (uint32_t)(size_t)(CalibLdsPtr)(&kv[(it + 1) & 1][0][0]) + (uint32_t)(wave * NL) * 1024u;
+      const uint32_t off = pos * 32768u + (uint32_t)(wave * NL) * 1024u + lane * 16u;
+#pragma unroll
+      for (int l = 0; l < NL; ++l)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base + l * 1024u),
+                     "v"(off + l * 1024u), "s"(src)
+                     : "memory");
+      pos = (pos + 1) & 127u;
+    }
+    const uint16_t* Ks = kv[it & 1][0];
+    const uint16_t* Vs = kv[it & 1][1];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {   // score product of one 32-key half, softmax work on the other half's scores
+      const int h = i >> 3, s = i & 7;
+      const bf16x8 f = *reinterpret_cast<const bf16x8*>(Ks + h * 32 * 128 + (kq0 ^ (16 * s)));
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        S[rb][h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[rb][s], S[rb][h], 0, 0, 0);
+        float y0 = S[rb][h ^ 1][2 * s], y1 = S[rb][h ^ 1][2 * s + 1];
+        uint32_t pk;
+        asm volatile("v_fma_f32 %0, %0, %2, %3\n\tv_fma_f32 %1, %1, %2, %3" : "+v"(y0), "+v"(y1) : "v"(c1), "v"(c2));
+        asm volatile("v_exp_f32 %0, %0\n\tv_exp_f32 %1, %1\n\ts_nop 0" : "+v"(y0), "+v"(y1));
+        asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pk) : "v"(y0), "v"(y1));
+        P[rb][(h ^ 1) * 2 + (s >> 2)][s & 3] = pk;
+        S[rb][h ^ 1][2 * s] = y0 * 0.f;   // the consumed scores start from zero when their half accumulates again
+        S[rb][h ^ 1][2 * s + 1] = y1 * 0.f;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {   // second product
+      const int b = i >> 2, ks = i & 3;
+      const bf16x8 f = *reinterpret_cast<const bf16x8*>(Vs + ((ks * 16 * 128 + (kq0 ^ (16 * (2 * b + (ks & 1))))) & 8191));
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        O[rb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, __builtin_bit_cast(bf16x8, P[rb][ks]), O[rb][b], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  const unsigned long long t1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+  float s = 0.f;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s += O[rb][b][i];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s += S[rb][h][i];
+  }
+  sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    ticks[0] = t1 - t0;
+    ticks[1] = r1 - r0;
+  }
+}
+
 }  // namespace
 
 double calib_mfma_flops(const purekv_plan& p, int32_t iters) {
   return 2.0 * 32 * 32 * 16 * CALIB_MFMAS * (double)iters * PUREKV_WAVES * (double)p.n_queues;
+}
+
+double calib_step_flops(const purekv_plan& p, int32_t iters) {
+  return 4.0 * 256 * 64 * 128 * (double)iters * (double)p.n_queues;   // both products of 256 rows x 64 keys x 128
+}
+
+int launch_calib_step(const purekv_plan& p, int rows_per_wavefront, int32_t iters, const void* src, float* sink,
+                      uint64_t* ticks, hipStream_t st) {
+  auto* tk = reinterpret_cast<unsigned long long*>(ticks);
+  const char* sp = static_cast<const char*>(src);
+  if (rows_per_wavefront == 32)
+    hipLaunchKernelGGL(calib_step_kernel<1>, dim3((unsigned)p.n_queues), dim3(512), 0, st, sink, tk, iters, sp);
+  else
+    hipLaunchKernelGGL(calib_step_kernel<2>, dim3((unsigned)p.n_queues), dim3(256), 0, st, sink, tk, iters, sp);
+  PUREKV_HIP_TRY(hipGetLastError());
+  return PUREKV_OK;
 }
 
 int launch_calib_mfma(const purekv_plan& p, int mix, int random_operands, int32_t iters, float* sink, uint64_t* ticks,

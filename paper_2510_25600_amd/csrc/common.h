@@ -91,6 +91,9 @@ int decode_counter_count(const purekv_plan& p);
 int launch_calib_mfma(const purekv_plan& p, int mix, int random_operands, int32_t iters, float* sink, uint64_t* ticks,
                       hipStream_t st);
 double calib_mfma_flops(const purekv_plan& p, int32_t iters);
+int launch_calib_step(const purekv_plan& p, int rows_per_wavefront, int32_t iters, const void* src, float* sink,
+                      uint64_t* ticks, hipStream_t st);
+double calib_step_flops(const purekv_plan& p, int32_t iters);
 
 size_t prefill_ws_bytes(const purekv_plan& p);
 size_t topk_ws_bytes(const purekv_plan& p, int32_t n_layers, int32_t w);

@@ -423,3 +423,26 @@ def test_layer_stack_matches_oracle(clie, st_layer, layers):
         kr, vr = orc.compact(x.k, x.v, got)   # compaction is a bit copy of what the GPU selected
         assert np.array_equal(bits_of(kc_all[l])[:, :h + w], kr) and np.array_equal(bits_of(vc_all[l])[:, :h + w], vr)
         assert not bits_of(kc_all[l])[:, h + w:].any()
+
+
+@pytest.mark.parametrize("rows", [32, 64])
+def test_tile_step_skeleton_runs(rows):
+    """Second calibration loop: runs on the plan's grid, fills the sink with finite values, reports its clock,
+    refuses bad arguments."""
+    plan = _plan(WORKLOADS["tiny_4f"], 3)
+    n_wg = plan.counts()["n_workgroups"]
+    src = torch.randn(2 << 20, device="cuda").to(torch.bfloat16)   # 4 MiB
+    sink = torch.full((512 * n_wg,), float("nan"), dtype=torch.float32, device="cuda")
+    flops, ticks = pk.purekv_calib_tile_step(plan, rows, 50, src, sink=sink)
+    torch.cuda.synchronize()
+    assert flops == 4.0 * 256 * 64 * 128 * 50 * n_wg
+    assert bool(torch.isfinite(sink[: (512 // (rows // 32)) * n_wg]).all())
+    cyc, ref = ticks.tolist()
+    assert cyc >= 50 * 32 * 32 and ref > 0 and 0.05 < cyc / ref / 10.0 < 3.0
+    lib = pk.raw()
+    P = lambda t: t.data_ptr()  # noqa: E731
+    assert lib.purekv_calib_tile_step(plan.handle, 48, 50, P(src), P(sink), P(ticks), None) == pk.EINVAL
+    assert lib.purekv_calib_tile_step(plan.handle, 32, 0, P(src), P(sink), P(ticks), None) == pk.EINVAL
+    assert lib.purekv_calib_tile_step(plan.handle, 32, 50, None, P(sink), P(ticks), None) == pk.EINVAL
+    with pytest.raises(ValueError):
+        pk.purekv_calib_tile_step(plan, 32, 50, src[:1000])

@@ -77,6 +77,8 @@ def test_compute_calls_validate_before_touching_the_gpu():
     assert lib.purekv_decode_attn(h, one, one, one, 4, 4, one, one, 1 << 20, None) == pk.EINVAL
     assert lib.purekv_decode_step(h, one, one, one, one, one, 3, 4, one, one, 1 << 20, None) == pk.EINVAL
     assert lib.purekv_calib_mfma(h, 0, 0, 10, one, one, None) == pk.EINVAL
+    assert lib.purekv_calib_tile_step(h, 32, 10, one, one, one, None) == pk.EINVAL
+    assert lib.purekv_calib_tile_step_flops(h, 10) == 4.0 * 256 * 64 * 128 * 10 * plan.counts()["n_workgroups"]
     assert lib.purekv_calib_mfma_flops(None, 10) == 0.0
     assert lib.purekv_calib_mfma_flops(h, 10) == 2.0 * 32 * 32 * 16 * 16 * 10 * 8 * plan.counts()["n_workgroups"]
     stack = pk.Stack(4, 1, 2, 8, 4)
