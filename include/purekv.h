@@ -8,7 +8,9 @@
  *   - the V-norm weighting S = C * ||V|| (Eq. 3 for the low layer, Eq. 4 for the high layers that
  *     reuse C^low with their own V) and the per-KV-head selection "recent w + top h" (Sec. 3.1);
  *   - the gather of the kept K/V rows into a compact cache;
- *   - single-token decode attention against that compact cache.
+ *   - single-token decode attention against that compact cache, alone or fused with the append of the token;
+ *   - the layer stack that ties these together (which layers are dense, which estimate the importance);
+ *   - two calibration loops that measure what the board sustains (no part of the method).
  *
  * Conventions
  *   - Token order: video tokens frame-major (index i < F*P: frame i / P, patch i % P), then text.
