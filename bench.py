@@ -336,6 +336,8 @@ def main() -> int:
     kept_flops, mask_flops = st.kept_tile_flops(), st.mask_flops()
     dense_kept = dense.kept_tile_flops()
     st_call_ms = stage_ms["st_prefill"]           # prefill kernel + merge, events inside the timed steps
+    st_idx = STAGES.index("st_prefill")
+    st_samples = [events[s_][st_idx].elapsed_time(events[s_][st_idx + 1]) for s_ in range(args.steps)]
     st_tflops = kept_flops / (st_call_ms * 1e-3) / 1e12
     topk_bytes = (n - w) * d * 2 * hkv + (n - w) * 4 * hkv * 3 + n_keep * 4 * hkv   # V read, C read, S write+read, idx
     comp_bytes = 2 * 2 * n_keep * d * 2 * hkv + n_keep * 4 * hkv                    # K,V rows read + written, idx
@@ -360,6 +362,8 @@ def main() -> int:
                    "tile": f"{pk.BLOCK}-row block x {pk.BLOCK}-key block ({pk.WAVES} wavefronts of {pk.BLOCK} rows per workgroup, {pk.BK}-key tiles)", "step": "low layer (dense prefill+LSE, importance, top-h, compaction) + "
                    "high layer (ST-SpAttn prefill, top-h, compaction, append+decode)"},
         "prefill_ms_per_layer": round(st_call_ms, 4),
+        "prefill_ms_per_layer_median": round(float(np.median(st_samples)), 4),
+        "prefill_ms_per_layer_min": round(float(np.min(st_samples)), 4),
         "prefill_ms_per_layer_back_to_back": round(st_ms, 4),
         "mfma_peak_frac": round(st_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
         "mask_tflops": round(mask_flops / (st_call_ms * 1e-3) / 1e12, 2),
