@@ -100,7 +100,38 @@ void build_plan(purekv_plan& p, int n_cu) {
       p.mask_pairs += row_pairs(sets[i - r0], i);
     }
     const int32_t last_tile = std::min((r1 - 1) / BK, n_ktiles - 1);  // causal: no key beyond the last row
+    // Two shortcuts keep the planner linear in the number of listed tiles for long sequences; both only skip
+    // work whose outcome is known.  (1) Rows that see every earlier key (dense pattern, text rows): a key tile that
+    // ends at or before the first row of the query tile is needed in full by every row block.  (2) Video rows of a
+    // sparse pattern can only see the first frame, their own frame up to themselves and their previous-frame keys:
+    // tiles outside those three ranges are not examined.
+    const bool all_dense_rows = g.pattern == PUREKV_PATTERN_DENSE || r0 >= g.Nv;
+    const bool all_video_rows = g.pattern != PUREKV_PATTERN_DENSE && r1 <= g.Nv;
+    uint32_t need_all = 0;
+    int32_t blocks_all = 0;
+    for (int32_t rb = 0; rb < g.R; ++rb)
+      if (r0 + rb * kBlockRows < r1) need_all |= 3u << (2 * rb), blocks_all += 2;
+    int32_t own_tile = 0, prev_lo = 1, prev_hi = 0;   // first tile of the own-frame range; previous-frame tiles
+    if (all_video_rows) {
+      const int32_t own0 = (g.pattern & PUREKV_PATTERN_SPATIAL) ? (r0 / g.P) * g.P : r0;
+      own_tile = own0 / BK;
+      if ((g.pattern & PUREKV_PATTERN_TEMPORAL) && r1 - 1 - g.P >= 0) {
+        prev_lo = std::max(0, r0 - g.P) / BK;
+        prev_hi = (r1 - 1 - g.P) / BK;
+      }
+    }
+    const int32_t first_frame_tile = (g.P - 1) / BK;
     for (int32_t c = 0; c <= last_tile; ++c) {
+      if (all_dense_rows && (c + 1) * BK - 1 <= r0) {
+        p.tiles.push_back({c, need_all, 0u});   // kind "full" is 0 in every field
+        p.n_blocks += blocks_all;
+        p.n_kind[kKindFull] += blocks_all;
+        continue;
+      }
+      if (all_video_rows && c > first_frame_tile && c < own_tile && !(c >= prev_lo && c <= prev_hi)) {
+        c = std::min(own_tile, prev_lo > c && prev_lo <= prev_hi ? prev_lo : own_tile) - 1;   // jump to the next range
+        continue;
+      }
       uint32_t need = 0, kinds = 0;
       for (int32_t rb = 0; rb < g.R; ++rb) {
         const int32_t w0 = r0 + rb * kBlockRows, w1 = std::min(w0 + kBlockRows, r1);
