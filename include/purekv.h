@@ -107,6 +107,18 @@ typedef enum {
 PUREKV_API int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* stream);
 PUREKV_API int purekv_plan_create_host(const purekv_shape_t* shape, int32_t n_workgroups, purekv_plan_t** out);
 PUREKV_API int purekv_plan_destroy(purekv_plan_t* plan);
+/*
+ * Plans over a subset of the query heads, for models that give different heads different patterns (the other
+ * reading of the "dual path" of Sec. 3.2: some heads spatial, others temporal): head_mask is a HOST array of
+ * n_q_heads bytes, non-zero = the head belongs to this plan (at least one).  A prefill call with such a plan
+ * computes the selected heads only and leaves the other heads' rows of `out` (and `lse`) untouched, so one call per
+ * pattern, each with the plan of its heads, fills `out`.  Heads are planned one per workgroup (no stacking).
+ * The other entry points ignore the subset.
+ */
+PUREKV_API int purekv_plan_create_heads(const purekv_shape_t* shape, const uint8_t* head_mask, purekv_plan_t** out,
+                                        void* stream);
+PUREKV_API int purekv_plan_create_heads_host(const purekv_shape_t* shape, const uint8_t* head_mask, int32_t n_workgroups,
+                                             purekv_plan_t** out);
 
 /* Plan inspection (host memory).  counts[0..15] = N, number of query tiles, number of work items,
  * number of (query tile, key tile) references, number of (row block, 32-key block) pairs computed per

@@ -48,6 +48,8 @@ def _load() -> ctypes.CDLL:
         "purekv_plan_create": (c_int, [POINTER(Shape), POINTER(P), P]),
         "purekv_plan_create_host": (c_int, [POINTER(Shape), c_int32, POINTER(P)]),
         "purekv_plan_destroy": (c_int, [P]),
+        "purekv_plan_create_heads": (c_int, [POINTER(Shape), P, POINTER(c_void_p), P]),
+        "purekv_plan_create_heads_host": (c_int, [POINTER(Shape), P, c_int32, POINTER(c_void_p)]),
         "purekv_plan_counts": (c_int, [P, POINTER(c_int64)]),
         "purekv_plan_qtile_list": (c_int, [P, c_int32, POINTER(c_int32), c_int32]),
         "purekv_plan_item": (c_int, [P, c_int32, POINTER(c_int32)]),
@@ -81,7 +83,8 @@ def _load() -> ctypes.CDLL:
 
 _lib = _load()
 EXPORTS = (
-    "purekv_plan_create", "purekv_plan_create_host", "purekv_plan_destroy", "purekv_plan_counts",
+    "purekv_plan_create", "purekv_plan_create_host", "purekv_plan_destroy", "purekv_plan_create_heads",
+    "purekv_plan_create_heads_host", "purekv_plan_counts",
     "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_workspace_bytes", "purekv_st_spattn_prefill",
     "purekv_lowlayer_importance", "purekv_topk_select", "purekv_kv_compact", "purekv_kv_append",
     "purekv_decode_attn", "purekv_decode_step", "purekv_stack_workspace_bytes", "purekv_stack_layer",
@@ -128,11 +131,22 @@ class Plan:
 
     def __init__(self, n_frames: int, patch_h: int, patch_w: int, n_text: int, n_q_heads: int, n_kv_heads: int,
                  head_dim: int, pattern: int = PATTERN_ST, softmax_scale: float = 0.0, host_only: bool = False,
-                 n_workgroups: int = 256):
+                 n_workgroups: int = 256, head_mask=None):
+        """head_mask: optional sequence of n_q_heads truth values: the plan covers those query heads only."""
         self.shape = Shape(n_frames, patch_h, patch_w, n_text, n_q_heads, n_kv_heads, head_dim, pattern,
                            softmax_scale)
         self._h = c_void_p()
-        if host_only:
+        if head_mask is not None:
+            if len(head_mask) != n_q_heads:
+                raise ValueError("head_mask needs one entry per query head")
+            hm = (ctypes.c_uint8 * n_q_heads)(*[1 if x else 0 for x in head_mask])
+            if host_only:
+                _check(_lib.purekv_plan_create_heads_host(byref(self.shape), hm, n_workgroups, byref(self._h)),
+                       "purekv_plan_create_heads_host")
+            else:
+                _check(_lib.purekv_plan_create_heads(byref(self.shape), hm, byref(self._h), _stream()),
+                       "purekv_plan_create_heads")
+        elif host_only:
             _check(_lib.purekv_plan_create_host(byref(self.shape), n_workgroups, byref(self._h)),
                    "purekv_plan_create_host")
         else:

@@ -29,12 +29,23 @@ static int check_shape(const purekv_shape_t* s) {
   return PUREKV_OK;
 }
 
-static int make_plan(const purekv_shape_t* s, purekv_plan_t** out, int n_cu) {
+static int make_plan(const purekv_shape_t* s, purekv_plan_t** out, int n_cu, const uint8_t* head_mask = nullptr) {
   if (out == nullptr) return PUREKV_EINVAL;
   const int rc = check_shape(s);
   if (rc != PUREKV_OK) return rc;
+  if (head_mask != nullptr) {   // at least one head
+    bool any = false;
+    for (int32_t hq = 0; hq < s->n_q_heads; ++hq) any |= head_mask[hq] != 0;
+    if (!any) return PUREKV_EINVAL;
+  }
   purekv_plan* p = new (std::nothrow) purekv_plan();
   if (p == nullptr) return PUREKV_ENOMEM;
+  try {
+    if (head_mask != nullptr) p->head_sel.assign(head_mask, head_mask + s->n_q_heads);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return PUREKV_ENOMEM;
+  }
   Geometry& g = p->g;
   g.F = s->n_frames;
   g.P = s->patch_h * s->patch_w;
@@ -70,7 +81,24 @@ int purekv_plan_create_host(const purekv_shape_t* shape, int32_t n_workgroups, p
   return make_plan(shape, out, n_workgroups);
 }
 
+static int create_on_device(const purekv_shape_t* shape, const uint8_t* head_mask, purekv_plan_t** out, void* stream);
+
 int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* stream) {
+  return create_on_device(shape, nullptr, out, stream);
+}
+
+int purekv_plan_create_heads(const purekv_shape_t* shape, const uint8_t* head_mask, purekv_plan_t** out, void* stream) {
+  if (head_mask == nullptr) return PUREKV_EINVAL;
+  return create_on_device(shape, head_mask, out, stream);
+}
+
+int purekv_plan_create_heads_host(const purekv_shape_t* shape, const uint8_t* head_mask, int32_t n_workgroups,
+                                  purekv_plan_t** out) {
+  if (head_mask == nullptr || n_workgroups < 1 || n_workgroups > 65536) return PUREKV_EINVAL;
+  return make_plan(shape, out, n_workgroups, head_mask);
+}
+
+static int create_on_device(const purekv_shape_t* shape, const uint8_t* head_mask, purekv_plan_t** out, void* stream) {
   if (out == nullptr) return PUREKV_EINVAL;
   int rc = check_shape(shape);
   if (rc != PUREKV_OK) return rc;
@@ -78,7 +106,7 @@ int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* s
   PUREKV_HIP_TRY(hipGetDevice(&dev));
   PUREKV_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
   purekv_plan_t* p = nullptr;
-  rc = make_plan(shape, &p, n_cu > 0 ? n_cu : 256);
+  rc = make_plan(shape, &p, n_cu > 0 ? n_cu : 256, head_mask);
   if (rc != PUREKV_OK) return rc;
   p->device = dev;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -92,6 +120,10 @@ int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* s
   const size_t cb = (size_t)decode_counter_count(*p) * sizeof(int32_t);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_counters), cb);
   if (e == hipSuccess) e = hipMemsetAsync(p->d_counters, 0, cb, st);
+  if (e == hipSuccess && !p->head_sel.empty()) {
+    e = hipMalloc(reinterpret_cast<void**>(&p->d_head_sel), p->head_sel.size());
+    if (e == hipSuccess) e = hipMemcpyAsync(p->d_head_sel, p->head_sel.data(), p->head_sel.size(), hipMemcpyHostToDevice, st);
+  }
   if (e == hipSuccess && sb) e = hipMemcpyAsync(p->d_stream, p->stream.data(), sb, hipMemcpyHostToDevice, st);
   if (e == hipSuccess && ub) e = hipMemcpyAsync(p->d_units, p->units.data(), ub, hipMemcpyHostToDevice, st);
   if (e == hipSuccess && qb) e = hipMemcpyAsync(p->d_queue_begin, p->queue_begin.data(), qb, hipMemcpyHostToDevice, st);
@@ -115,6 +147,7 @@ int purekv_plan_destroy(purekv_plan_t* p) {
   if (p->d_queue_unit0) (void)hipFree(p->d_queue_unit0);
   if (p->d_merges) (void)hipFree(p->d_merges);
   if (p->d_counters) (void)hipFree(p->d_counters);
+  if (p->d_head_sel) (void)hipFree(p->d_head_sel);
   delete p;
   return PUREKV_OK;
 }
@@ -171,12 +204,12 @@ int purekv_plan_item(const purekv_plan_t* p, int32_t it, int32_t item[6]) {
 
 double purekv_plan_kept_tile_flops(const purekv_plan_t* p) {
   if (p == nullptr) return 0.0;
-  return 4.0 * kBlockRows * kBlockKeys * p->g.d * (double)p->n_blocks * p->g.Hq;
+  return 4.0 * kBlockRows * kBlockKeys * p->g.d * (double)p->n_blocks * p->n_heads_sel;
 }
 
 double purekv_plan_mask_flops(const purekv_plan_t* p) {
   if (p == nullptr) return 0.0;
-  return 4.0 * p->g.d * p->mask_pairs * p->g.Hq;
+  return 4.0 * p->g.d * p->mask_pairs * p->n_heads_sel;
 }
 
 size_t purekv_workspace_bytes(const purekv_plan_t* p, int op, int32_t n_layers, int32_t w, int32_t cap) {

@@ -79,10 +79,18 @@ void build_plan(purekv_plan& p, int n_cu) {
   {
     const int32_t gs = largest_divisor_up_to(g.G, kWaves), r = kWaves / gs;
     const bool stack = (g.pattern != PUREKV_PATTERN_DENSE && gs >= 2) || (gs * r == kWaves && gs >= 2);
-    g.Gs = stack ? gs : 1;
-    g.R = stack ? r : kWaves;
+    const bool subset = !p.head_sel.empty();   // a head subset is planned head by head
+    g.Gs = (stack && !subset) ? gs : 1;
+    g.R = (stack && !subset) ? r : kWaves;
     g.n_groups = g.Hq / g.Gs;
+    p.n_heads_sel = g.Hq;
+    if (subset) {
+      p.n_heads_sel = 0;
+      for (int32_t hq = 0; hq < g.Hq; ++hq) p.n_heads_sel += p.head_sel[hq] != 0;
+    }
   }
+  auto group_selected = [&](int32_t grp) { return p.head_sel.empty() || p.head_sel[grp] != 0; };   // Gs == 1 for subsets
+  const int32_t n_groups_sel = p.head_sel.empty() ? g.n_groups : p.n_heads_sel;
   const int32_t rows_per_qtile = g.R * kBlockRows;
   p.n_qtiles = (g.N + rows_per_qtile - 1) / rows_per_qtile;
   const int32_t n_ktiles = (g.N + BK - 1) / BK;
@@ -172,7 +180,7 @@ void build_plan(purekv_plan& p, int n_cu) {
   }
 
   // ---- work items: cut lists that are long against the average load of one workgroup ----
-  const double total_steps = double(p.tiles.size()) * g.n_groups;
+  const double total_steps = double(p.tiles.size()) * n_groups_sel;
   // Slice length: 0.8 of the average load of a workgroup (measured on the 32-frame benchmark shape: shorter
   // slices balance no better after the refinement pass below and double the partial results to merge).
   const int32_t chunk = std::max<int32_t>(8, static_cast<int32_t>(0.8 * total_steps / std::max(1, n_cu) + 0.5));
@@ -208,9 +216,10 @@ void build_plan(purekv_plan& p, int n_cu) {
   // ---- deal (item, head group) units onto persistent workgroups: longest first, least-loaded queue ----
   // Workgroup q runs on XCD q % 8 (round-robin dispatch); when the head counts allow it, the units of one
   // KV head stay on a fixed set of XCDs so that each L2 holds the K/V of few KV heads.
-  const int64_t n_units = int64_t(p.items.size()) * g.n_groups;
+  const int64_t n_units = int64_t(p.items.size()) * n_groups_sel;
   p.n_queues = static_cast<int32_t>(std::min<int64_t>(std::max(1, n_cu), std::max<int64_t>(1, n_units)));
-  const bool affinity = (p.n_queues % 8 == 0) && (g.Hkv % 8 == 0 || 8 % g.Hkv == 0);
+  // (not for a head subset: its KV heads may be few, and every queue has to receive a unit)
+  const bool affinity = p.head_sel.empty() && (p.n_queues % 8 == 0) && (g.Hkv % 8 == 0 || 8 % g.Hkv == 0);
   auto allowed = [&](int32_t q, int32_t kvh) {
     if (!affinity) return true;
     const int32_t x = q % 8;
@@ -220,6 +229,7 @@ void build_plan(purekv_plan& p, int n_cu) {
   std::vector<double> load(p.n_queues, 0.0);
   for (size_t it = 0; it < p.items.size(); ++it) {
     for (int32_t grp = 0; grp < g.n_groups; ++grp) {
+      if (!group_selected(grp)) continue;
       const int32_t kvh = grp * g.Gs / g.G;
       int32_t best = -1;
       for (int32_t q = 0; q < p.n_queues; ++q)

@@ -62,6 +62,7 @@ struct PrefillArgs {
   const int32_t* queue_begin;   // [n_queues + 1] offsets into stream
   const int32_t* queue_unit0;   // [n_queues + 1] first unit of each queue (units are numbered in stream order)
   const MergeItem* merges;
+  const uint8_t* head_sel;      // [Hq] or null: a plan over a head subset (one head per workgroup) merges only those
   int32_t N, Nv, P, Hq, Hkv;
   int32_t Gs, R, n_groups;   // workgroup shape: wavefront w -> row block w / Gs, head w % Gs
   uint32_t pattern;
@@ -723,6 +724,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const PrefillArgs a) {
   const int hq = grp * a.Gs + hl;
   const int row = mi.qtile * (a.R * 32) + rb * 32 + (part & 1) * MERGE_ROWS + threadIdx.x / 16;
   if (row >= a.N) return;
+  if (a.head_sel != nullptr && a.head_sel[hq] == 0) return;   // no slice of this head exists
   float mx = -INFINITY, mxx = -INFINITY;
   for (int s = 0; s < mi.n_splits; ++s) {
     const size_t prow = ((size_t)(mi.slot0 + s) * a.n_groups + grp) * WG_ROWS + r;
@@ -794,6 +796,7 @@ int launch_prefill(const purekv_plan& p, const void* q, const void* k, const voi
   a.queue_begin = p.d_queue_begin;
   a.queue_unit0 = p.d_queue_unit0;
   a.merges = p.d_merges;
+  a.head_sel = p.d_head_sel;
   a.N = p.g.N;
   a.Nv = p.g.Nv;
   a.P = p.g.P;

@@ -446,3 +446,40 @@ def test_tile_step_skeleton_runs(rows):
     assert lib.purekv_calib_tile_step(plan.handle, 32, 50, None, P(sink), P(ticks), None) == pk.EINVAL
     with pytest.raises(ValueError):
         pk.purekv_calib_tile_step(plan, 32, 50, src[:1000])
+
+
+@pytest.mark.parametrize("name,patterns", [
+    ("longtext_2f", [3, 1]),                         # split text rows: the merge kernel must skip the other head
+    ("heads7_3f", [1, 2, 1, 2, 3, 3, 0]),            # all four patterns inside one KV group
+    ("heads3_4f", [2, 2, 1, 1, 1, 2]),               # d = 64, two KV heads
+])
+def test_per_head_patterns_through_head_subset_plans(name, patterns):
+    """The other reading of the dual path: every query head has a pattern of its own.  One plan per pattern over
+    the heads that use it, one prefill call per plan into the same output: every head must match the oracle under
+    ITS pattern, and a call must not touch the rows of heads outside its plan."""
+    wl = SMALL[name]
+    assert len(patterns) == wl.n_q_heads
+    inp = generate(wl, seed=17)
+    q, k, v = to_dev(inp.q), to_dev(inp.k), to_dev(inp.v)
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((wl.n_q_heads, wl.n_tokens), float("nan"), dtype=torch.float32, device="cuda")
+    done = np.zeros(wl.n_q_heads, bool)
+    for pattern in sorted(set(patterns)):
+        mask = [p == pattern for p in patterns]
+        plan = pk.Plan(wl.n_frames, wl.patch_h, wl.patch_w, wl.n_text, wl.n_q_heads, wl.n_kv_heads, wl.head_dim,
+                       pattern, head_mask=mask)
+        before = bits_of(out).copy()
+        pk.purekv_st_spattn_prefill(plan, q, k, v, out=out, lse=lse)
+        torch.cuda.synchronize()
+        after = bits_of(out)
+        untouched = ~np.array(mask)
+        assert np.array_equal(after[untouched], before[untouched]), f"pattern {pattern} wrote outside its heads"
+        done |= np.array(mask)
+    assert done.all()
+    qf, kf, vf = F64(inp.q), F64(inp.k), F64(inp.v)
+    got, got_lse = f64_of(out), f64_of(lse)
+    for pattern in sorted(set(patterns)):
+        heads = [h for h, p in enumerate(patterns) if p == pattern]
+        ref, ref_lse = orc.masked_attention(qf, kf, vf, wl.n_frames, wl.patches, wl.n_text, pattern, heads=heads)
+        check_attention(got[heads], ref, f"{name} pattern {pattern} heads {heads}")   # the oracle returns the asked heads
+        assert np.abs(got_lse[heads] - ref_lse).max() < 2e-3

@@ -221,3 +221,47 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=120)
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+@pytest.mark.parametrize("pattern", [1, 2, 3])
+@pytest.mark.parametrize("mask", [[1, 0, 0, 1, 0, 1, 0, 0], [0, 0, 0, 0, 0, 0, 1, 0], [1] * 8])
+def test_head_subset_plan_lists_only_the_selected_heads(mask, pattern):
+    """A plan over a head subset: one head per workgroup, the same tile lists as the plan of all heads in that
+    shape, every (work item, selected head) unit exactly once and no unit of any other head; flop counts scale
+    with the number of selected heads; every queue holds at least one unit."""
+    F, ph, pw, T, hq, hkv, d = 3, 6, 7, 300, 8, 2, 64
+    sub = pk.Plan(F, ph, pw, T, hq, hkv, d, pattern, host_only=True, n_workgroups=16, head_mask=mask)
+    c = sub.counts()
+    assert c["stacked_heads"] == 1 and c["row_blocks"] == pk.WAVES and c["n_head_groups"] == hq
+    # the reference: the same shape with one query head per KV head is planned head by head as well
+    ref = pk.Plan(F, ph, pw, T, hkv, hkv, d, pattern, host_only=True, n_workgroups=16)
+    cr = ref.counts()
+    assert cr["stacked_heads"] == 1 and cr["n_qtiles"] == c["n_qtiles"] and cr["n_blocks"] == c["n_blocks"]
+    assert all(sub.qtile_list(q) == ref.qtile_list(q) for q in range(c["n_qtiles"]))
+    sel = [h for h in range(hq) if mask[h]]
+    units = [u for q in range(c["n_workgroups"]) for u in sub.queue(q)]
+    assert sorted(units) == [(i, h0) for i in range(c["n_items"]) for h0 in sel]
+    assert all(len(sub.queue(q)) >= 1 for q in range(c["n_workgroups"]))
+    assert sub.kept_tile_flops() == 4.0 * pk.BLOCK * pk.BLOCK * d * c["n_blocks"] * len(sel)
+    full = pk.Plan(F, ph, pw, T, hq, hkv, d, pattern, host_only=True, n_workgroups=16)
+    assert abs(sub.mask_flops() * hq - full.mask_flops() * len(sel)) <= 1e-9 * full.mask_flops() * hq
+    for p in (sub, ref, full):
+        p.close()
+
+
+def test_head_subset_plan_argument_errors():
+    lib = pk.raw()
+    good = pk.Shape(2, 4, 4, 8, 4, 2, 64, 3, 0.0)
+    h = ctypes.c_void_p()
+    none = (ctypes.c_uint8 * 4)(0, 0, 0, 0)
+    some = (ctypes.c_uint8 * 4)(0, 1, 0, 0)
+    assert lib.purekv_plan_create_heads_host(ctypes.byref(good), none, 16, ctypes.byref(h)) == pk.EINVAL   # no head
+    assert lib.purekv_plan_create_heads_host(ctypes.byref(good), None, 16, ctypes.byref(h)) == pk.EINVAL
+    assert lib.purekv_plan_create_heads_host(ctypes.byref(good), some, 0, ctypes.byref(h)) == pk.EINVAL
+    assert lib.purekv_plan_create_heads_host(None, some, 16, ctypes.byref(h)) == pk.EINVAL
+    assert lib.purekv_plan_create_heads_host(ctypes.byref(good), some, 16, None) == pk.EINVAL
+    assert lib.purekv_plan_create_heads(ctypes.byref(good), None, ctypes.byref(h), None) == pk.EINVAL
+    assert lib.purekv_plan_create_heads_host(ctypes.byref(good), some, 16, ctypes.byref(h)) == pk.OK
+    assert lib.purekv_plan_destroy(h) == pk.OK
+    with pytest.raises(ValueError):
+        pk.Plan(2, 4, 4, 8, 4, 2, 64, 3, host_only=True, head_mask=[1, 0])
