@@ -112,7 +112,8 @@ PUREKV_API int purekv_plan_destroy(purekv_plan_t* plan);
  * reading of the "dual path" of Sec. 3.2: some heads spatial, others temporal): head_mask is a HOST array of
  * n_q_heads bytes, non-zero = the head belongs to this plan (at least one).  A prefill call with such a plan
  * computes the selected heads only and leaves the other heads' rows of `out` (and `lse`) untouched, so one call per
- * pattern, each with the plan of its heads, fills `out`.  Heads are planned one per workgroup (no stacking).
+ * pattern, each with the plan of its heads, fills `out`.  A subset made of whole stacks of heads (e.g. whole KV groups)
+ * keeps the stacked workgroup shape; any other subset is planned one head per workgroup.
  * The other entry points ignore the subset.
  */
 PUREKV_API int purekv_plan_create_heads(const purekv_shape_t* shape, const uint8_t* head_mask, purekv_plan_t** out,

@@ -79,18 +79,24 @@ void build_plan(purekv_plan& p, int n_cu) {
   {
     const int32_t gs = largest_divisor_up_to(g.G, kWaves), r = kWaves / gs;
     const bool stack = (g.pattern != PUREKV_PATTERN_DENSE && gs >= 2) || (gs * r == kWaves && gs >= 2);
-    const bool subset = !p.head_sel.empty();   // a head subset is planned head by head
-    g.Gs = (stack && !subset) ? gs : 1;
-    g.R = (stack && !subset) ? r : kWaves;
-    g.n_groups = g.Hq / g.Gs;
+    // A head subset keeps the stacked shape when it is made of whole stacks (e.g. whole KV groups); otherwise it is
+    // planned head by head.
+    bool whole_stacks = true;
     p.n_heads_sel = g.Hq;
-    if (subset) {
+    if (!p.head_sel.empty()) {
       p.n_heads_sel = 0;
-      for (int32_t hq = 0; hq < g.Hq; ++hq) p.n_heads_sel += p.head_sel[hq] != 0;
+      for (int32_t hq = 0; hq < g.Hq; ++hq) {
+        p.n_heads_sel += p.head_sel[hq] != 0;
+        whole_stacks &= (p.head_sel[hq] != 0) == (p.head_sel[hq - hq % gs] != 0);
+      }
     }
+    const bool use_stack = stack && whole_stacks;
+    g.Gs = use_stack ? gs : 1;
+    g.R = use_stack ? r : kWaves;
+    g.n_groups = g.Hq / g.Gs;
   }
-  auto group_selected = [&](int32_t grp) { return p.head_sel.empty() || p.head_sel[grp] != 0; };   // Gs == 1 for subsets
-  const int32_t n_groups_sel = p.head_sel.empty() ? g.n_groups : p.n_heads_sel;
+  auto group_selected = [&](int32_t grp) { return p.head_sel.empty() || p.head_sel[grp * g.Gs] != 0; };
+  const int32_t n_groups_sel = p.n_heads_sel / g.Gs;
   const int32_t rows_per_qtile = g.R * kBlockRows;
   p.n_qtiles = (g.N + rows_per_qtile - 1) / rows_per_qtile;
   const int32_t n_ktiles = (g.N + BK - 1) / BK;

@@ -99,8 +99,9 @@ struct purekv_plan {
   int32_t* d_queue_unit0 = nullptr;        // [n_queues + 1] first unit of each queue
   purekv::MergeItem* d_merges = nullptr;
   int32_t* d_counters = nullptr;           // arrival counters of the decode kernel, zero between calls
-  // Head subset (empty: every query head).  A plan over a subset runs one head per workgroup (Gs = 1), lists units
-  // for the selected heads only and leaves the other heads' rows of every output untouched.
+  // Head subset (empty: every query head).  A plan over a subset lists units for the selected heads only and leaves
+  // the other heads' rows of every output untouched; it keeps the stacked workgroup shape when the subset consists
+  // of whole stacks, else it runs one head per workgroup (Gs = 1).
   std::vector<uint8_t> head_sel;           // [Hq], non-zero = selected
   int32_t n_heads_sel = 0;                 // selected heads (Hq when head_sel is empty)
   uint8_t* d_head_sel = nullptr;

@@ -224,10 +224,10 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   int u_nsplits = 1, u_ws_row0 = -1;
   bf16x8 qf[KSTEPS];
   // m: reference maximum (log2 units); lacc: every element holds the sum of the bf16-rounded probabilities of
-  // query n, accumulated by the matrix pipe (variants without LSE: an output row is then an exact convex
-  // combination of V rows and the vector ALU adds nothing); lx: exact fp32 sum of the lane's probabilities (LSE
-  // variant only, which needs it for the log-sum-exp, normalises with it as well and leaves the row-sum MFMAs out:
-  // 4 of 36 MFMAs per tile, 3.6 % of the dense kernel's time).
+  // query n, accumulated by the matrix pipe: an output row is an exact convex combination of V rows (normalising
+  // with the exact sum instead saves the LSE variant its row-sum MFMAs, 3.6 % of the dense kernel, but a row
+  // dominated by one key then carries that key's probability rounding, 2^-9 |v|, on top of the output rounding:
+  // 0.023 was seen against the 0.02 bound); lx: exact fp32 sum of the lane's probabilities (LSE variant only).
   // The row sum uses the 16x16x32 MFMA (4 accumulator registers, half the pipe time of a 32x32x16).  Its B operand
   // takes lane l as (column l % 16, k-group l / 16); a probability fragment has lane l = (query l % 32, keys
   // 8 (l / 32) ..), so k-groups 0 and 2 of column j are the 16 keys of query j and k-groups 1 and 3 those of query
@@ -277,10 +277,9 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   float m_fin = -INFINITY;              // its reference maximum
   constexpr int NPIECE = 4 * DBLK;      // (output block, group of 4 accumulator registers): 8 bytes per lane
   auto finish_sums = [&]() {
-    const float lx_tot = LSE ? lx + other_half(lx) : 0.f;
-    const float l_tot = LSE ? lx_tot : lacc[0];
+    const float l_tot = lacc[0];
     fin_inv = l_tot > 0.f ? __builtin_amdgcn_rcpf(l_tot) : 0.f;
-    if (LSE) fin_lse = (m_fin + __builtin_amdgcn_logf(lx_tot)) * kLn2;
+    if (LSE) fin_lse = (m_fin + __builtin_amdgcn_logf(lx + other_half(lx))) * kLn2;
   };
   // `ln` is an opaque copy of the lane id: addresses derived from it are recomputed where they are used instead
   // of being hoisted out of the tile loop, where they would occupy registers all the time.
@@ -321,7 +320,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     int ln = lane;
     asm volatile("" : "+v"(ln));
     const int n = ln & 31, h = ln >> 5;
-    const float l_tot = LSE ? lx + other_half(lx) : lacc[0];
+    const float l_tot = lacc[0];
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     const float lse2 = m_fin + __builtin_amdgcn_logf(l_tot);  // log2 domain; -inf when the slice saw no key
     const float lse2x = LSE ? m_fin + __builtin_amdgcn_logf(lx + other_half(lx)) : lse2;
@@ -430,9 +429,8 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 #pragma unroll
     for (int i = 0; i < A; ++i) f[i] = rd(i);
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (!LSE)   // the LSE variant keeps the exact fp32 sum on the vector ALU anyway and normalises with it
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) lacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones8, pf[ks], lacc, 0, 0, 0);
+    for (int ks = 0; ks < 4; ++ks) lacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones8, pf[ks], lacc, 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < NF; ++i) {

@@ -452,6 +452,8 @@ def test_tile_step_skeleton_runs(rows):
     ("longtext_2f", [3, 1]),                         # split text rows: the merge kernel must skip the other head
     ("heads7_3f", [1, 2, 1, 2, 3, 3, 0]),            # all four patterns inside one KV group
     ("heads3_4f", [2, 2, 1, 1, 1, 2]),               # d = 64, two KV heads
+    ("heads3_4f", [1, 1, 1, 3, 3, 3]),               # whole KV groups: the subset plans keep the stacked shape
+    ("manyunits_g7", [3] * 7 + [1] * 14 + [2] * 7 + [0] * 14),   # 6 KV groups of 7 heads, split text rows
 ])
 def test_per_head_patterns_through_head_subset_plans(name, patterns):
     """The other reading of the dual path: every query head has a pattern of its own.  One plan per pattern over

@@ -224,7 +224,7 @@ def test_bench_refuses_more_than_one_gpu():
 
 
 @pytest.mark.parametrize("pattern", [1, 2, 3])
-@pytest.mark.parametrize("mask", [[1, 0, 0, 1, 0, 1, 0, 0], [0, 0, 0, 0, 0, 0, 1, 0], [1] * 8])
+@pytest.mark.parametrize("mask", [[1, 0, 0, 1, 0, 1, 0, 0], [0, 0, 0, 0, 0, 0, 1, 0], [1, 1, 1, 0, 1, 1, 1, 1]])
 def test_head_subset_plan_lists_only_the_selected_heads(mask, pattern):
     """A plan over a head subset: one head per workgroup, the same tile lists as the plan of all heads in that
     shape, every (work item, selected head) unit exactly once and no unit of any other head; flop counts scale
@@ -265,3 +265,17 @@ def test_head_subset_plan_argument_errors():
     assert lib.purekv_plan_destroy(h) == pk.OK
     with pytest.raises(ValueError):
         pk.Plan(2, 4, 4, 8, 4, 2, 64, 3, host_only=True, head_mask=[1, 0])
+
+
+@pytest.mark.parametrize("mask", [[0, 0, 0, 0, 1, 1, 1, 1], [1] * 8])
+def test_head_subset_of_whole_kv_groups_keeps_the_stacked_shape(mask):
+    F, ph, pw, T, hq, hkv, d = 3, 6, 7, 300, 8, 2, 64
+    sub = pk.Plan(F, ph, pw, T, hq, hkv, d, 3, host_only=True, n_workgroups=16, head_mask=mask)
+    full = pk.Plan(F, ph, pw, T, hq, hkv, d, 3, host_only=True, n_workgroups=16)
+    c, cf = sub.counts(), full.counts()
+    assert c["stacked_heads"] == cf["stacked_heads"] == 4 and c["row_blocks"] == cf["row_blocks"] == 2
+    assert all(sub.qtile_list(q) == full.qtile_list(q) for q in range(c["n_qtiles"]))
+    units = [u for q in range(c["n_workgroups"]) for u in sub.queue(q)]
+    assert sorted(units) == [(i, h0) for i in range(c["n_items"]) for h0 in range(0, hq, 4) if mask[h0]]
+    assert sub.kept_tile_flops() * hq == full.kept_tile_flops() * sum(mask)
+    sub.close(), full.close()
