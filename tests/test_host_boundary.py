@@ -279,3 +279,18 @@ def test_head_subset_of_whole_kv_groups_keeps_the_stacked_shape(mask):
     assert sorted(units) == [(i, h0) for i in range(c["n_items"]) for h0 in range(0, hq, 4) if mask[h0]]
     assert sub.kept_tile_flops() * hq == full.kept_tile_flops() * sum(mask)
     sub.close(), full.close()
+
+
+def test_plan_lists_match_oracle_mask_random_shapes():
+    """Seeded sweep over odd shapes (frame sizes that are not multiples of the key tile, frames shorter than a
+    row block, long and empty texts, every pattern): the planner's shortcuts for known tiles must never change a
+    list, a need bit or a kind."""
+    rng = np.random.default_rng(2510)
+    for _ in range(60):
+        ph, pw = int(rng.integers(1, 14)), int(rng.integers(1, 14))
+        F = int(rng.integers(1, max(2, min(12, 1200 // (ph * pw)) + 1)))
+        T = int(rng.choice([0, 1, 7, 33, 64, 129, 400]))
+        hkv = int(rng.choice([1, 2, 3]))
+        g = int(rng.choice([1, 2, 4, 7]))
+        pattern = int(rng.integers(0, 4))
+        _check_plan_against_oracle(F, ph, pw, T, hkv * g, hkv, 64, pattern, n_wg=int(rng.choice([3, 16, 256])))
