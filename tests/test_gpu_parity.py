@@ -485,3 +485,30 @@ def test_per_head_patterns_through_head_subset_plans(name, patterns):
         ref, ref_lse = orc.masked_attention(qf, kf, vf, wl.n_frames, wl.patches, wl.n_text, pattern, heads=heads)
         check_attention(got[heads], ref, f"{name} pattern {pattern} heads {heads}")   # the oracle returns the asked heads
         assert np.abs(got_lse[heads] - ref_lse).max() < 2e-3
+
+
+def test_prefill_random_shapes_sweep():
+    """Seeded sweep: odd frame sizes, texts from none to long, head groupings 1..7, both head sizes, every
+    pattern, with and without the log-sum-exp output -- each through the kernel and against the oracle."""
+    rng = np.random.default_rng(25600)
+    for case in range(24):
+        ph, pw = int(rng.integers(1, 14)), int(rng.integers(1, 14))
+        F = int(rng.integers(1, max(2, min(10, 900 // (ph * pw)) + 1)))
+        T = int(rng.choice([0, 1, 7, 33, 129, 700]))
+        hkv = int(rng.choice([1, 2, 3]))
+        g = int(rng.choice([1, 2, 4, 7]))
+        d = int(rng.choice([64, 128]))
+        pattern = int(rng.integers(0, 4))
+        wl = small_variant(f"sweep{case}", n_frames=F, patch_h=ph, patch_w=pw, n_text=T, n_q_heads=hkv * g,
+                           n_kv_heads=hkv, head_dim=d)
+        print(f"[case] sweep {case}: F={F} P={ph}x{pw} T={T} heads {hkv * g}/{hkv} d={d} pattern={pattern}", flush=True)
+        inp = generate(wl, seed=100 + case)
+        plan = _plan(wl, pattern)
+        q, k, v = to_dev(inp.q), to_dev(inp.k), to_dev(inp.v)
+        out, lse = pk.purekv_st_spattn_prefill(plan, q, k, v, want_lse=True)
+        out2 = pk.purekv_st_spattn_prefill(plan, q, k, v)
+        torch.cuda.synchronize()
+        ref, ref_lse = orc.masked_attention(F64(inp.q), F64(inp.k), F64(inp.v), F, ph * pw, T, pattern)
+        check_attention(f64_of(out), ref, f"sweep {case} (lse variant)")
+        check_attention(f64_of(out2), ref, f"sweep {case}")
+        assert np.abs(f64_of(lse) - ref_lse).max() < 2e-3
