@@ -512,3 +512,36 @@ def test_prefill_random_shapes_sweep():
         check_attention(f64_of(out), ref, f"sweep {case} (lse variant)")
         check_attention(f64_of(out2), ref, f"sweep {case}")
         assert np.abs(f64_of(lse) - ref_lse).max() < 2e-3
+
+
+def test_importance_random_shapes_sweep():
+    """Seeded sweep of the column sums: window sizes from one row to the whole sequence (text rows only, video rows
+    under a mask, windows that are not a multiple of the 32-row block), odd frame sizes, 1..7 heads per KV head."""
+    rng = np.random.default_rng(314)
+    for case in range(20):
+        ph, pw = int(rng.integers(1, 12)), int(rng.integers(1, 12))
+        F = int(rng.integers(1, max(2, min(8, 700 // (ph * pw)) + 1)))
+        T = int(rng.choice([0, 5, 40, 130, 300]))
+        hkv = int(rng.choice([1, 2]))
+        g = int(rng.choice([1, 3, 7]))
+        d = int(rng.choice([64, 128]))
+        pattern = int(rng.integers(0, 4))
+        n = F * ph * pw + T
+        w = int(rng.choice([1, 31, 32, 33, max(1, T), max(1, n // 3), n]))
+        w = min(max(w, 1), n)
+        wl = small_variant(f"isweep{case}", n_frames=F, patch_h=ph, patch_w=pw, n_text=T, n_q_heads=hkv * g,
+                           n_kv_heads=hkv, head_dim=d)
+        print(f"[case] importance sweep {case}: N={n} w={w} heads {hkv * g}/{hkv} d={d} pattern={pattern}", flush=True)
+        inp = generate(wl, seed=200 + case)
+        plan = _plan(wl, pattern)
+        q, k, v = to_dev(inp.q), to_dev(inp.k), to_dev(inp.v)
+        _, lse = pk.purekv_st_spattn_prefill(plan, q, k, v, want_lse=True)
+        c = pk.purekv_lowlayer_importance(plan, q, k, lse, w)
+        torch.cuda.synchronize()
+        ref = orc.window_column_sums(F64(inp.q), F64(inp.k), F, ph * pw, T, pattern, w)
+        got = f64_of(c)
+        assert got.shape == ref.shape
+        if ref.size:
+            rel = np.abs(got - ref) / np.maximum(np.abs(ref), 1e-12)
+            assert rel.max() <= IMPORTANCE_REL, f"case {case}: worst rel {rel.max():.3g}"
+            assert np.all(got[ref == 0] == 0)
