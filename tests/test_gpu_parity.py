@@ -545,3 +545,31 @@ def test_importance_random_shapes_sweep():
             rel = np.abs(got - ref) / np.maximum(np.abs(ref), 1e-12)
             assert rel.max() <= IMPORTANCE_REL, f"case {case}: worst rel {rel.max():.3g}"
             assert np.all(got[ref == 0] == 0)
+
+
+def test_decode_random_shapes_sweep():
+    """Seeded sweep of the decode step: cache lengths around the 32-key wavefront tiles and the 256-key chunks, 1 to
+    20 query heads per KV head (more than one block of 16), both head sizes; fused append + attention against the
+    oracle on the grown cache, and the cache rows themselves."""
+    from workloads import f32_to_bf16_bits
+    rng = np.random.default_rng(77)
+    for case in range(24):
+        hkv = int(rng.choice([1, 2, 5]))
+        g = int(rng.choice([1, 2, 7, 16, 17, 20]))
+        d = int(rng.choice([64, 128]))
+        n0 = int(rng.choice([0, 1, 15, 16, 31, 32, 33, 255, 256, 257, 511, 513, 1000, 2049]))
+        hq = hkv * g
+        bits = lambda *shape: f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))  # noqa: E731
+        cap = n0 + 3
+        kc_h, vc_h = bits(hkv, cap, d), bits(hkv, cap, d)
+        kc, vc = to_dev(kc_h), to_dev(vc_h)
+        plan = pk.Plan(1, 4, 4, 4, hq, hkv, d, 3)
+        print(f"[case] decode sweep {case}: heads {hq}/{hkv} d={d} n0={n0}", flush=True)
+        for t in range(2):
+            q, kn, vn = bits(hq, d), bits(hkv, d), bits(hkv, d)
+            out = pk.purekv_decode_step(plan, to_dev(q), to_dev(kn), to_dev(vn), kc, vc, n0 + t)
+            torch.cuda.synchronize()
+            kc_h[:, n0 + t], vc_h[:, n0 + t] = kn, vn
+            assert np.array_equal(bits_of(kc), kc_h) and np.array_equal(bits_of(vc), vc_h)
+            ref = orc.decode_attention(F64(q), F64(kc_h)[:, :n0 + t + 1], F64(vc_h)[:, :n0 + t + 1])
+            check_attention(f64_of(out), ref, f"decode sweep {case} step {t}")
