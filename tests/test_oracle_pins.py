@@ -339,3 +339,132 @@ def test_stack_selection_shares_the_estimating_layers_column_sums():
     idx2 = orc.stack_selection(c_layers, v_layers, clie, h, n, w)
     assert hot[clie][0] not in idx2[4][0, :h] and np.array_equal(idx2[3], idx[3])
     assert [orc.stack_pattern(l, 3) for l in range(5)] == [0, 0, 0, 3, 3] and orc.stack_pattern(4, 5) == 0
+
+
+# ------------------------------------------------------------------ several KV heads (GQA indexing)
+# Every pin above that touches column sums, V-norms, compaction or decode runs on one KV head, where
+# "query head hq reads KV head hq // G" cannot be told from hq % Hkv, nor idx[kv] from idx[0].  The pins
+# below use Hq = 6, Hkv = 3 (G = 2: hq // G = 0 0 1 1 2 2, hq % Hkv = 0 1 2 0 1 2) with KV heads that can be
+# told apart, and never call the oracle to build their expected values.
+
+def _gqa_inputs(seed=11):
+    wl = small_variant("gqa_3kv", n_frames=3, patch_h=3, patch_w=4, n_text=9, n_q_heads=6, n_kv_heads=3, head_dim=16)
+    inp = generate(wl, seed=seed, decode_steps=1)
+    return wl, _f64(inp.q), _f64(inp.k), _f64(inp.v), inp
+
+
+def _library_probs(q_h, k_h, mask, scale):
+    s = torch.from_numpy(q_h @ k_h.T * scale).masked_fill(~torch.from_numpy(mask), -math.inf)
+    return torch.softmax(s, -1).numpy()
+
+
+@pytest.mark.parametrize("pattern", [0, 3])
+def test_column_sums_per_kv_head_against_library_softmax(pattern):
+    """Eq. 2 under GQA: the column sums of KV head kv collect the query heads kv*G .. kv*G+G-1, each scored
+    against THAT head's keys.  Expected values from the library softmax on explicit per-head matrices."""
+    wl, q, k, v, _ = _gqa_inputs()
+    n, w, g = wl.n_tokens, 7, wl.group
+    scale = 1 / math.sqrt(wl.head_dim)
+    mask = _mask_triple_loop(wl.n_frames, wl.patch_h, wl.patch_w, wl.n_text, pattern)
+    c = orc.window_column_sums(q, k, wl.n_frames, wl.patches, wl.n_text, pattern, w)
+    assert c.shape == (3, n - w)
+    for kv in range(3):
+        expect = np.zeros(n)
+        for hq in (kv * g, kv * g + 1):
+            expect += _library_probs(q[hq], k[kv], mask, scale)[n - w:].sum(0)
+        assert np.abs(c[kv] - expect[:n - w]).max() < 1e-12
+        # the other heads' expected values are far away: a wrong head mapping cannot pass by accident
+        other = np.zeros(n)
+        for hq in (kv, kv + 3):   # the query heads hq % Hkv == kv
+            other += _library_probs(q[hq], k[hq // g], mask, scale)[n - w:].sum(0)
+        assert np.abs(c[kv] - other[:n - w]).max() > 1e-3
+
+
+def test_column_sums_harmonic_value_only_on_the_head_with_identical_keys():
+    """One KV head whose keys are all identical gives G * (H_N - H_{N-w}) on every column of ITS row of C
+    (closed form, dense pattern); the other KV heads, with distinct keys, do not."""
+    wl, q, k, v, _ = _gqa_inputs()
+    n, w, g = wl.n_tokens, wl.window, wl.group
+    harmonic = g * sum(1.0 / (i + 1) for i in range(n - w, n))
+    for same in range(3):
+        k2 = k.copy()
+        k2[same] = k[same, :1]
+        c = orc.window_column_sums(q, k2, wl.n_frames, wl.patches, wl.n_text, 0, w)
+        for kv in range(3):
+            dev = np.abs(c[kv] - harmonic).max()
+            assert (dev < 1e-12) if kv == same else (dev > 1e-2)
+
+
+def test_vnorm_per_kv_head_constant_norms():
+    """Eq. 3: a V whose rows all have norm 2, 3, 5 in KV heads 0, 1, 2 scales each head's C by that number."""
+    rng = np.random.default_rng(12)
+    hkv, n, d, m = 3, 30, 16, 23
+    v = rng.standard_normal((hkv, n, d))
+    norms = np.array([2.0, 3.0, 5.0])
+    v *= (norms[:, None] / np.sqrt((v * v).sum(2)))[:, :, None]
+    c = rng.random((hkv, m)) + 0.1
+    s = orc.vnorm_scores(c, v)
+    assert s.shape == (hkv, m)
+    for kv in range(hkv):
+        assert np.abs(s[kv] / c[kv] - norms[kv]).max() < 1e-12
+    # one key of one head zeroed: only that entry of that head drops to zero
+    v[1, 4] = 0.0
+    s2 = orc.vnorm_scores(c, v)
+    assert s2[1, 4] == 0.0 and np.array_equal(np.delete(s2.ravel(), 1 * m + 4), np.delete(s.ravel(), 1 * m + 4))
+
+
+def test_compaction_uses_each_heads_own_index_list():
+    """Rows carry (head, row) in their bits, every KV head has a different index list: row r of head kv of the
+    compact cache must be row idx[kv, r] of head kv, checked element by element in Python."""
+    hkv, n, d, keep = 3, 20, 4, 6
+    k_bits = np.zeros((hkv, n, d), np.uint16)
+    v_bits = np.zeros((hkv, n, d), np.uint16)
+    for kv in range(hkv):
+        for j in range(n):
+            k_bits[kv, j] = 1000 * kv + 10 * j + np.arange(d)
+            v_bits[kv, j] = 40000 + 1000 * kv + 10 * j + np.arange(d)
+    idx = np.array([[0, 2, 4, 6, 8, 19], [1, 3, 5, 7, 9, 11], [12, 13, 14, 15, 16, 17]], np.int32)
+    kc, vc = orc.compact(k_bits, v_bits, idx)
+    assert kc.shape == (hkv, keep, d) and vc.shape == (hkv, keep, d)
+    for kv in range(hkv):
+        for r in range(keep):
+            for e in range(d):
+                assert kc[kv, r, e] == 1000 * kv + 10 * int(idx[kv, r]) + e
+                assert vc[kv, r, e] == 40000 + 1000 * kv + 10 * int(idx[kv, r]) + e
+
+
+def test_decode_reads_the_kv_head_of_the_query_heads_group():
+    """Decode under GQA: with V constant per KV head (1, 2, 3) the output of query head hq is hq // G + 1
+    whatever the scores; with real V, every query head equals the library softmax over ITS group's cache."""
+    wl, q, k, v, inp = _gqa_inputs()
+    g, d = wl.group, wl.head_dim
+    qn = _f64(inp.q_new[0])
+    kc, vc = k[:, 5:25], v[:, 5:25]
+    v_const = np.empty_like(vc)
+    for kv in range(3):
+        v_const[kv] = kv + 1.0
+    o = orc.decode_attention(qn, kc, v_const)
+    assert o.shape == (6, d)
+    for hq in range(6):
+        assert np.abs(o[hq] - (hq // g + 1.0)).max() < 1e-12
+    o = orc.decode_attention(qn, kc, vc)
+    for hq in range(6):
+        p = torch.softmax(torch.from_numpy(kc[hq // g] @ qn[hq] / math.sqrt(d)), 0).numpy()
+        assert np.abs(o[hq] - p @ vc[hq // g]).max() < 1e-12
+        p_wrong = torch.softmax(torch.from_numpy(kc[hq % 3] @ qn[hq] / math.sqrt(d)), 0).numpy()
+        if hq % 3 != hq // g:
+            assert np.abs(o[hq] - p_wrong @ vc[hq % 3]).max() > 1e-3
+
+
+def test_attention_and_lse_per_kv_head_against_library_softmax():
+    """Prefill under GQA with real K/V: every query head against the library softmax over its group's K/V."""
+    wl, q, k, v, _ = _gqa_inputs()
+    scale = 1 / math.sqrt(wl.head_dim)
+    mask = _mask_triple_loop(wl.n_frames, wl.patch_h, wl.patch_w, wl.n_text, 3)
+    out, lse = orc.masked_attention(q, k, v, wl.n_frames, wl.patches, wl.n_text, 3)
+    for hq in range(6):
+        kv = hq // wl.group
+        a = _library_probs(q[hq], k[kv], mask, scale)
+        assert np.abs(out[hq] - a @ v[kv]).max() < 1e-12
+        s = torch.from_numpy(q[hq] @ k[kv].T * scale).masked_fill(~torch.from_numpy(mask), -math.inf)
+        assert np.abs(lse[hq] - torch.logsumexp(s, -1).numpy()).max() < 1e-12
