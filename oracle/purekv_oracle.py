@@ -24,6 +24,7 @@ Readings of the paper where it is silent (all listed in the design notes):
 from __future__ import annotations
 
 import math
+from fractions import Fraction
 from typing import Optional, Sequence, Tuple
 
 import numpy as np
@@ -153,8 +154,13 @@ def vnorm_scores(c: np.ndarray, v: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------
 
 def budget(n: int, w: int, ratio: float) -> int:
-    """h such that window + top-h holds floor(ratio * N) entries (never negative)."""
-    return max(0, int(math.floor(ratio * float(n))) - w)
+    """h such that window + top-h holds floor(ratio * N) entries (never negative).
+
+    The ratio is the decimal number as written (the paper's budgets are 5 %, 20 %, 35 %, 50 % of the
+    sequence, Sec. 4.2), so the product is formed in exact rational arithmetic: floor(0.29 * 100) is 29,
+    not the 28 that the binary double nearest to 0.29 would give."""
+    kept = math.floor(Fraction(repr(float(ratio))) * n)
+    return max(0, int(kept) - w)
 
 
 def topk_select(s: np.ndarray, h: int, n: int, w: int) -> np.ndarray:

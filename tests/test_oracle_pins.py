@@ -274,6 +274,12 @@ def test_budget_matches_paper_ratio():
     assert orc.budget(100, 50, 0.2) == 0
     assert [orc.budget(16640, 256, r) for r in (0.1, 0.2, 0.33)] == [1408, 3072, 5235]
     assert orc.budget(8448, 256, 0.2) == 1433 and orc.budget(4736, 128, 0.2) == 819
+    # the ratio is the decimal number as written: integer arithmetic on percent and per-mille values
+    for n in (100, 288, 1000, 4736, 8448, 16640, 33280):
+        for pct in range(0, 101):
+            assert orc.budget(n, 0, pct / 100) == (pct * n) // 100, (n, pct)
+        for pm in range(0, 1001, 7):
+            assert orc.budget(n, 3, pm / 1000) == max(0, (pm * n) // 1000 - 3), (n, pm)
 
 
 def test_salient_keys_are_selected():
