@@ -15,8 +15,12 @@
  * Conventions
  *   - Token order: video tokens frame-major (index i < F*P: frame i / P, patch i % P), then text.
  *     N = F*P + T.  P = patch_h * patch_w; "the corresponding token of the previous frame" is i - P.
- *   - Tensors are packed, row-major, innermost dimension head_dim contiguous:
- *       Q [Hq, N, d], K and V [Hkv, N, d], O [Hq, N, d]: bf16.   Query head hq reads KV head hq / (Hq/Hkv).
+ *   - Q, K, V and O are bf16 tensors indexed (head, token, channel) with head_dim contiguous; the head and
+ *     token strides are fields of purekv_shape_t (elements; 0 = packed [H, N, d]), so the same calls serve
+ *     head-major tensors and the token-major [N, H * d] slices a decoder's QKV projection emits:
+ *       Q (Hq, N, d), K and V (Hkv, N, d), O (Hq, N, d).   Query head hq reads KV head hq / (Hq/Hkv).
+ *     K and V share one pair of strides.  Everything the library itself produces for its own later use
+ *     (log-sum-exp, column sums, scores, kept indices, the compact cache) is packed.
  *   - Every data pointer is a DEVICE pointer owned by the caller (16-byte aligned), unless the
  *     argument is documented as a host pointer.  `stream` is a hipStream_t passed as void* (NULL = default
  *     stream).  Calls enqueue work on `stream` and return; they do not synchronise and, except for plan
@@ -62,6 +66,14 @@ typedef struct {
   int32_t n_q_heads, n_kv_heads, head_dim;    /* Hq % Hkv == 0; head_dim 64 or 128                */
   uint32_t pattern;                           /* PUREKV_PATTERN_*                                 */
   float softmax_scale;                        /* 0 => 1/sqrt(head_dim) (Eq. 1)                    */
+  /* Element strides of the (head, token) axes of Q, of K and V, and of O; head_dim is always contiguous.
+   * A pair of zeros means packed [H, N, d] (head stride N * d, token stride d); otherwise both must be given.
+   * Requirements (else EINVAL): multiples of 8 elements (16-byte rows), token stride >= d and < 2^23, and the
+   * byte span of each tensor below 2^31.  Overlapping (head, token) rows are the caller's business for the
+   * inputs and undefined for O. */
+  int64_t q_stride_head, q_stride_tok;
+  int64_t kv_stride_head, kv_stride_tok;
+  int64_t o_stride_head, o_stride_tok;
 } purekv_shape_t;
 
 typedef struct purekv_plan purekv_plan_t;
@@ -139,15 +151,18 @@ PUREKV_API int purekv_plan_item(const purekv_plan_t* plan, int32_t it, int32_t i
 PUREKV_API int purekv_plan_queue(const purekv_plan_t* plan, int32_t wg, int32_t* units, int32_t cap);
 
 /* Device workspace bytes needed by `op` for this plan.  `n_layers`, `w` and `cap` are read by the ops
- * that take them (TOPK: n_layers, w; DECODE: cap); pass 0 otherwise. */
+ * that take them (TOPK: n_layers, w; DECODE: cap); pass 0 otherwise.  What lives there: PREFILL, the partial
+ * results of query tiles whose key list is cut into slices (the text rows of Sec. 3.2 see every key); TOPK, the
+ * scores S of Eq. 3 / Eq. 4 when the caller does not ask for them; DECODE, the per-chunk partial results of the
+ * decode stage.  IMPORTANCE (Eq. 2) and COMPACT need none. */
 PUREKV_API size_t purekv_workspace_bytes(const purekv_plan_t* plan, int op, int32_t n_layers, int32_t w, int32_t cap);
 
 /*
  * Prefill attention under the plan's pattern (Sec. 3.2; Eq. 1 when the pattern is dense):
  *   out[hq, i, :] = sum_j A[i, j] v[kv, j, :],  A = softmax over the allowed keys of q_i . k_j * scale.
  * The attention matrix is never stored.  bf16 inputs, bf16 MFMA products, fp32 accumulation and softmax.
- *   q [Hq, N, d], k, v [Hkv, N, d], out [Hq, N, d]: bf16 device.
- *   lse: optional fp32 device [Hq, N]: natural-log sum of exponentials of every row's scaled logits
+ *   q (Hq, N, d), k, v (Hkv, N, d), out (Hq, N, d): bf16 device, laid out by the plan's strides.
+ *   lse: optional fp32 device [Hq, N] (packed): natural-log sum of exponentials of every row's scaled logits
  *        (needed by purekv_lowlayer_importance); NULL to skip.
  */
 PUREKV_API int purekv_st_spattn_prefill(const purekv_plan_t* plan, const void* q, const void* k, const void* v,
@@ -159,7 +174,7 @@ PUREKV_API int purekv_st_spattn_prefill(const purekv_plan_t* plan, const void* q
  * over the pairs (i, j) the plan's pattern allows.  `lse` is the one written by the prefill call of the
  * same layer with the same plan.  fp32 throughout after the bf16 products; summation order is fixed, so
  * results are reproducible bit for bit.
- *   q [Hq, N, d], k [Hkv, N, d] bf16; lse [Hq, N] fp32; c_out [Hkv, N-w] fp32.   1 <= w <= N.
+ *   q (Hq, N, d), k (Hkv, N, d) bf16 by the plan's strides; lse [Hq, N] fp32; c_out [Hkv, N-w] fp32.   1 <= w <= N.
  */
 PUREKV_API int purekv_lowlayer_importance(const purekv_plan_t* plan, const void* q, const void* k, const float* lse,
                                int32_t w, float* c_out, void* ws, size_t ws_bytes, void* stream);
@@ -170,7 +185,7 @@ PUREKV_API int purekv_lowlayer_importance(const purekv_plan_t* plan, const void*
  *   s[l, kv, j] = c[kv, j] * ||v[l, kv, j, :]||_2   (fp32; s = c when v is NULL, then n_layers must be 1),
  *   idx_out[l, kv, 0..h)   = the h indices j < N-w with the largest s, ties to the lower index, ascending,
  *   idx_out[l, kv, h..h+w) = N-w .. N-1.
- *   c [Hkv, N-w] fp32; v: bf16, layer l at v + l * v_layer_stride elements, each [Hkv, N, d];
+ *   c [Hkv, N-w] fp32; v: bf16, layer l at v + l * v_layer_stride elements, each (Hkv, N, d) by the plan's K/V strides;
  *   idx_out [n_layers, Hkv, h+w] int32; s_out optional [n_layers, Hkv, N-w] fp32 (NULL to skip).
  *   1 <= w <= N, 0 <= h <= N-w.  Scores must not be NaN; -0.0 ranks equal to +0.0.
  */
@@ -180,7 +195,7 @@ PUREKV_API int purekv_topk_select(const purekv_plan_t* plan, const float* c, con
 
 /*
  * Compaction: kc[l, kv, r, :] = k[l, kv, idx[l, kv, r], :] for r < n_keep, same for v (bit copy).
- *   k, v: bf16, layer l at + l * kv_layer_stride elements, each [Hkv, N, d];
+ *   k, v: bf16, layer l at + l * kv_layer_stride elements, each (Hkv, N, d) by the plan's K/V strides;
  *   idx [n_layers, Hkv, n_keep] int32 with values in [0, N) (not checked on the device beyond clamping);
  *   kc, vc [n_layers, Hkv, cap, d] bf16, cap >= n_keep; rows r >= n_keep are left untouched.
  */
@@ -188,7 +203,9 @@ PUREKV_API int purekv_kv_compact(const purekv_plan_t* plan, const void* k, const
                       int32_t n_layers, const int32_t* idx, int32_t n_keep, void* kc, void* vc,
                       int32_t cap, void* stream);
 
-/* Appends one token's k_new, v_new [Hkv, d] as row n_cached of kc, vc [Hkv, cap, d] (n_cached < cap). */
+/* Appends one token's k_new, v_new [Hkv, d] as row n_cached of kc, vc [Hkv, cap, d] (n_cached < cap): the cache
+ * the decode stage of the paper's inference-speed table reads grows by the token it has just produced (Sec. 4.3;
+ * the kept set of Sec. 3.1 plus every later token). */
 PUREKV_API int purekv_kv_append(const purekv_plan_t* plan, const void* k_new, const void* v_new, void* kc, void* vc,
                      int32_t n_cached, int32_t cap, void* stream);
 
@@ -248,7 +265,11 @@ PUREKV_API int purekv_stack_select_compact(const purekv_plan_t* dense_plan, cons
                                            int64_t kv_layer_stride, int32_t* idx_all, void* kc_all, void* vc_all,
                                            int32_t cap, void* ws, size_t ws_bytes, void* stream);
 
-/* h = max(0, floor(ratio * n) - w): the keep budget counts the recent window (20 % budget = 5.0x). */
+/* Keep budget -> top-h (Sec. 3.1 keeps "the recent w tokens plus the top h"; the cache budgets of Sec. 4.2 are
+ * fractions of the sequence): h = max(0, floor(ratio * n) - w), i.e. the budget counts the recent window, so that a
+ * 20 % budget is exactly the paper's 5.0x compression.  The floor is taken after adding 1e-9, so that a ratio
+ * like 0.29 * 100 does not lose a key to binary rounding.  Returns -1 (no valid budget) for n < 0, w < 0, or a ratio
+ * that is not a finite number in [0, 1]. */
 PUREKV_API int32_t purekv_budget(int32_t n, int32_t w, double ratio);
 
 /* Work counts for reporting: flops of one prefill call counted on the (32-row block, 32-key block) pairs the

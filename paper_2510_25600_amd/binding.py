@@ -28,6 +28,9 @@ class Shape(ctypes.Structure):
         ("n_frames", c_int32), ("patch_h", c_int32), ("patch_w", c_int32), ("n_text", c_int32),
         ("n_q_heads", c_int32), ("n_kv_heads", c_int32), ("head_dim", c_int32),
         ("pattern", c_uint32), ("softmax_scale", c_float),
+        ("q_stride_head", c_int64), ("q_stride_tok", c_int64),
+        ("kv_stride_head", c_int64), ("kv_stride_tok", c_int64),
+        ("o_stride_head", c_int64), ("o_stride_tok", c_int64),
     ]
 
 
@@ -126,15 +129,29 @@ def _dev_bf16(t: torch.Tensor, name: str) -> torch.Tensor:
     return t
 
 
+def _strided_bf16(t: torch.Tensor, name: str, heads: int, n: int, d: int, strides: Tuple[int, int]) -> torch.Tensor:
+    """A (heads, n, d) bf16 device view whose head and token strides are the plan's and whose channels are contiguous."""
+    if not (t.is_cuda and t.dtype == torch.bfloat16):
+        raise TypeError(f"{name} must be a bf16 device tensor")
+    if tuple(t.shape[-3:]) != (heads, n, d) or t.stride(-1) != 1 or (t.stride(-3), t.stride(-2)) != tuple(strides):
+        raise TypeError(f"{name}: shape {tuple(t.shape)} / strides {t.stride()} do not match the plan "
+                        f"(({heads}, {n}, {d}), head stride {strides[0]}, token stride {strides[1]}, channel stride 1)")
+    return t
+
+
 class Plan:
     """Owns a purekv_plan_t.  `host_only` plans can be inspected without a GPU but not launched."""
 
     def __init__(self, n_frames: int, patch_h: int, patch_w: int, n_text: int, n_q_heads: int, n_kv_heads: int,
                  head_dim: int, pattern: int = PATTERN_ST, softmax_scale: float = 0.0, host_only: bool = False,
-                 n_workgroups: int = 256, head_mask=None):
-        """head_mask: optional sequence of n_q_heads truth values: the plan covers those query heads only."""
+                 n_workgroups: int = 256, head_mask=None, q_strides: Tuple[int, int] = (0, 0),
+                 kv_strides: Tuple[int, int] = (0, 0), o_strides: Tuple[int, int] = (0, 0)):
+        """head_mask: optional sequence of n_q_heads truth values: the plan covers those query heads only.
+        q_strides, kv_strides, o_strides: (head stride, token stride) in elements of Q, of K and V, of O;
+        (0, 0) = packed [H, N, d]."""
         self.shape = Shape(n_frames, patch_h, patch_w, n_text, n_q_heads, n_kv_heads, head_dim, pattern,
-                           softmax_scale)
+                           softmax_scale, q_strides[0], q_strides[1], kv_strides[0], kv_strides[1],
+                           o_strides[0], o_strides[1])
         self._h = c_void_p()
         if head_mask is not None:
             if len(head_mask) != n_q_heads:
@@ -153,12 +170,23 @@ class Plan:
             _check(_lib.purekv_plan_create(byref(self.shape), byref(self._h), _stream()), "purekv_plan_create")
         self.N = n_frames * patch_h * patch_w + n_text
         self.Hq, self.Hkv, self.d = n_q_heads, n_kv_heads, head_dim
+        packed = (self.N * head_dim, head_dim)
+        self.q_strides = tuple(q_strides) if any(q_strides) else packed
+        self.kv_strides = tuple(kv_strides) if any(kv_strides) else packed
+        self.o_strides = tuple(o_strides) if any(o_strides) else packed
         self._ws = {}
 
     @classmethod
-    def for_workload(cls, wl, pattern: int = PATTERN_ST, host_only: bool = False, n_workgroups: int = 256) -> "Plan":
+    def for_workload(cls, wl, pattern: int = PATTERN_ST, host_only: bool = False, n_workgroups: int = 256,
+                     **strides) -> "Plan":
         return cls(wl.n_frames, wl.patch_h, wl.patch_w, wl.n_text, wl.n_q_heads, wl.n_kv_heads, wl.head_dim,
-                   pattern, 0.0, host_only, n_workgroups)
+                   pattern, 0.0, host_only, n_workgroups, **strides)
+
+    def empty_out(self, device) -> torch.Tensor:
+        """An output tensor laid out by the plan's O strides, as a (Hq, N, d) view."""
+        sh, st = self.o_strides
+        span = (self.Hq - 1) * sh + (self.N - 1) * st + self.d
+        return torch.empty(span, dtype=torch.bfloat16, device=device).as_strided((self.Hq, self.N, self.d), (sh, st, 1))
 
     @property
     def handle(self) -> c_void_p:
@@ -230,10 +258,12 @@ class Plan:
 def purekv_st_spattn_prefill(plan: Plan, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
                              out: Optional[torch.Tensor] = None, want_lse: bool = False,
                              lse: Optional[torch.Tensor] = None):
-    _dev_bf16(q, "q"), _dev_bf16(k, "k"), _dev_bf16(v, "v")
-    assert q.shape == (plan.Hq, plan.N, plan.d) and k.shape == (plan.Hkv, plan.N, plan.d) and v.shape == k.shape
+    _strided_bf16(q, "q", plan.Hq, plan.N, plan.d, plan.q_strides)
+    _strided_bf16(k, "k", plan.Hkv, plan.N, plan.d, plan.kv_strides)
+    _strided_bf16(v, "v", plan.Hkv, plan.N, plan.d, plan.kv_strides)
     if out is None:
-        out = torch.empty_like(q)
+        out = plan.empty_out(q.device)
+    _strided_bf16(out, "out", plan.Hq, plan.N, plan.d, plan.o_strides)
     if want_lse and lse is None:
         lse = torch.empty((plan.Hq, plan.N), dtype=torch.float32, device=q.device)
     nb = plan.workspace_bytes(OP_PREFILL)
@@ -245,7 +275,8 @@ def purekv_st_spattn_prefill(plan: Plan, q: torch.Tensor, k: torch.Tensor, v: to
 
 def purekv_lowlayer_importance(plan: Plan, q: torch.Tensor, k: torch.Tensor, lse: torch.Tensor, w: int,
                                c_out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    _dev_bf16(q, "q"), _dev_bf16(k, "k")
+    _strided_bf16(q, "q", plan.Hq, plan.N, plan.d, plan.q_strides)
+    _strided_bf16(k, "k", plan.Hkv, plan.N, plan.d, plan.kv_strides)
     assert lse.dtype == torch.float32 and lse.is_contiguous() and lse.shape == (plan.Hq, plan.N)
     if c_out is None:
         c_out = torch.empty((plan.Hkv, max(plan.N - w, 0)), dtype=torch.float32, device=q.device)
@@ -263,7 +294,7 @@ def purekv_topk_select(plan: Plan, c: torch.Tensor, v: Optional[torch.Tensor], w
     n_layers = v.shape[0] if layered else 1
     stride = v.stride(0) if layered else 0
     if v is not None:
-        _dev_bf16(v, "v")
+        _strided_bf16(v, "v", plan.Hkv, plan.N, plan.d, plan.kv_strides)
     if idx_out is None:
         idx_out = torch.empty((n_layers, plan.Hkv, h + w), dtype=torch.int32, device=c.device)
     s_out = torch.empty((n_layers, plan.Hkv, plan.N - w), dtype=torch.float32, device=c.device) if want_scores else None
@@ -280,7 +311,8 @@ def purekv_topk_select(plan: Plan, c: torch.Tensor, v: Optional[torch.Tensor], w
 def purekv_kv_compact(plan: Plan, k: torch.Tensor, v: torch.Tensor, idx: torch.Tensor, cap: Optional[int] = None,
                       kc: Optional[torch.Tensor] = None, vc: Optional[torch.Tensor] = None):
     """k, v: [Hkv, N, d] or [L, Hkv, N, d]; idx: [Hkv, n_keep] or [L, Hkv, n_keep] int32."""
-    _dev_bf16(k, "k"), _dev_bf16(v, "v")
+    _strided_bf16(k, "k", plan.Hkv, plan.N, plan.d, plan.kv_strides)
+    _strided_bf16(v, "v", plan.Hkv, plan.N, plan.d, plan.kv_strides)
     assert idx.dtype == torch.int32 and idx.is_contiguous() and idx.is_cuda
     layered = k.dim() == 4
     n_layers = k.shape[0] if layered else 1
@@ -349,7 +381,10 @@ def _stack_ws(dense: Plan, st: Optional[Plan], stack: Stack, device) -> tuple:
 def purekv_stack_layer(dense: Plan, st: Optional[Plan], stack: Stack, layer: int, q: torch.Tensor, k: torch.Tensor,
                        v: torch.Tensor, out: torch.Tensor, lse: Optional[torch.Tensor], c_all: Optional[torch.Tensor]):
     """One layer of the stack's prefill (plus importance on the layers that emit C)."""
-    _dev_bf16(q, "q"), _dev_bf16(k, "k"), _dev_bf16(v, "v"), _dev_bf16(out, "out")
+    _strided_bf16(q, "q", dense.Hq, dense.N, dense.d, dense.q_strides)
+    _strided_bf16(k, "k", dense.Hkv, dense.N, dense.d, dense.kv_strides)
+    _strided_bf16(v, "v", dense.Hkv, dense.N, dense.d, dense.kv_strides)
+    _strided_bf16(out, "out", dense.Hq, dense.N, dense.d, dense.o_strides)
     nb, ws = _stack_ws(dense, st, stack, q.device)
     _check(_lib.purekv_stack_layer(dense.handle, st.handle if st is not None else None, byref(stack), layer,
                                    q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), _ptr(lse), _ptr(c_all),
@@ -360,7 +395,10 @@ def purekv_stack_layer(dense: Plan, st: Optional[Plan], stack: Stack, layer: int
 def purekv_stack_select_compact(dense: Plan, st: Optional[Plan], stack: Stack, c_all: torch.Tensor, k_all: torch.Tensor,
                                 v_all: torch.Tensor, idx_all: torch.Tensor, kc_all: torch.Tensor, vc_all: torch.Tensor):
     """Selection and compaction of all layers of the stack; k_all, v_all [L, Hkv, N, d], kc_all, vc_all [L, Hkv, cap, d]."""
-    _dev_bf16(k_all, "k_all"), _dev_bf16(v_all, "v_all"), _dev_bf16(kc_all, "kc_all"), _dev_bf16(vc_all, "vc_all")
+    _strided_bf16(k_all, "k_all", dense.Hkv, dense.N, dense.d, dense.kv_strides)
+    _strided_bf16(v_all, "v_all", dense.Hkv, dense.N, dense.d, dense.kv_strides)
+    _dev_bf16(kc_all, "kc_all"), _dev_bf16(vc_all, "vc_all")
+    assert k_all.dim() == 4 and v_all.stride(0) == k_all.stride(0)
     nb, ws = _stack_ws(dense, st, stack, k_all.device)
     _check(_lib.purekv_stack_select_compact(dense.handle, byref(stack), _ptr(c_all), k_all.data_ptr(), v_all.data_ptr(),
                                             k_all.stride(0), idx_all.data_ptr(), kc_all.data_ptr(), vc_all.data_ptr(),

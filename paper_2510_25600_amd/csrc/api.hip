@@ -16,6 +16,24 @@ int note_hip_error(hipError_t e) {
   return PUREKV_EHIP;
 }
 
+// Strides of one tensor (elements): {0, 0} = packed [H, N, d]; otherwise both given, rows 16-byte aligned, the token
+// stride below 2^23 (the kernels multiply it with 24-bit operands) and the tensor's byte span below 2^31 (32-bit
+// byte offsets).
+static int resolve_strides(int64_t sh, int64_t st, int64_t heads, int64_t n, int64_t d, int64_t* out_sh, int64_t* out_st) {
+  if (sh == 0 && st == 0) {
+    sh = n * d;
+    st = d;
+  } else {
+    if (st < d || (heads > 1 && sh < 1) || sh < 0) return PUREKV_EINVAL;
+    if (st % 8 != 0 || sh % 8 != 0 || st >= ((int64_t)1 << 23)) return PUREKV_EINVAL;
+  }
+  const int64_t span = ((heads - 1) * sh + (n - 1) * st + d) * 2;
+  if (span > ((int64_t)1 << 31)) return PUREKV_EINVAL;
+  *out_sh = sh;
+  *out_st = st;
+  return PUREKV_OK;
+}
+
 static int check_shape(const purekv_shape_t* s) {
   if (s == nullptr) return PUREKV_EINVAL;
   if (s->n_frames < 1 || s->patch_h < 1 || s->patch_w < 1 || s->n_text < 0) return PUREKV_EINVAL;
@@ -23,10 +41,13 @@ static int check_shape(const purekv_shape_t* s) {
   if (!(s->softmax_scale >= 0.f) || std::isinf(s->softmax_scale)) return PUREKV_EINVAL;
   const int64_t p = (int64_t)s->patch_h * s->patch_w, n = p * s->n_frames + s->n_text;
   if (p > (1 << 22) || n > (int64_t)1 << 22) return PUREKV_EINVAL;
-  if (n * s->n_kv_heads * s->head_dim * 2 > ((int64_t)1 << 31)) return PUREKV_EINVAL;  // 32-bit byte offsets into K/V
   if (s->head_dim != 64 && s->head_dim != 128) return PUREKV_EUNSUPPORTED;
   if (s->pattern > PUREKV_PATTERN_ST) return PUREKV_EUNSUPPORTED;
-  return PUREKV_OK;
+  int64_t a, b;
+  int rc = resolve_strides(s->q_stride_head, s->q_stride_tok, s->n_q_heads, n, s->head_dim, &a, &b);
+  if (rc == PUREKV_OK) rc = resolve_strides(s->kv_stride_head, s->kv_stride_tok, s->n_kv_heads, n, s->head_dim, &a, &b);
+  if (rc == PUREKV_OK) rc = resolve_strides(s->o_stride_head, s->o_stride_tok, s->n_q_heads, n, s->head_dim, &a, &b);
+  return rc;
 }
 
 static int make_plan(const purekv_shape_t* s, purekv_plan_t** out, int n_cu, const uint8_t* head_mask = nullptr) {
@@ -58,6 +79,9 @@ static int make_plan(const purekv_shape_t* s, purekv_plan_t** out, int n_cu, con
   g.d = s->head_dim;
   g.pattern = s->pattern;
   g.scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / std::sqrt((float)s->head_dim);
+  (void)resolve_strides(s->q_stride_head, s->q_stride_tok, g.Hq, g.N, g.d, &g.q_sh, &g.q_st);
+  (void)resolve_strides(s->kv_stride_head, s->kv_stride_tok, g.Hkv, g.N, g.d, &g.kv_sh, &g.kv_st);
+  (void)resolve_strides(s->o_stride_head, s->o_stride_tok, g.Hq, g.N, g.d, &g.o_sh, &g.o_st);
   try {
     build_plan(*p, n_cu);
   } catch (const std::bad_alloc&) {
@@ -251,7 +275,7 @@ int purekv_topk_select(const purekv_plan_t* p, const float* c, const void* v, in
   if (w < 1 || w > p->g.N || h < 0 || h > p->g.N - w) return PUREKV_EINVAL;
   if (c == nullptr && w < p->g.N) return PUREKV_EINVAL;
   if (v == nullptr && n_layers != 1) return PUREKV_EINVAL;
-  if (v != nullptr && n_layers > 1 && v_layer_stride < (int64_t)p->g.Hkv * p->g.N * p->g.d) return PUREKV_EINVAL;
+  if (v != nullptr && n_layers > 1 && v_layer_stride < 1) return PUREKV_EINVAL;
   if (v != nullptr && s_out == nullptr) {
     const size_t need = topk_ws_bytes(*p, n_layers, w);
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return PUREKV_EWORKSPACE;
@@ -265,7 +289,7 @@ int purekv_kv_compact(const purekv_plan_t* p, const void* k, const void* v, int6
     return PUREKV_EINVAL;
   if (n_keep < 0 || n_keep > cap || cap < 1 || n_keep > p->g.N) return PUREKV_EINVAL;
   if (idx == nullptr && n_keep > 0) return PUREKV_EINVAL;
-  if (n_layers > 1 && kv_layer_stride < (int64_t)p->g.Hkv * p->g.N * p->g.d) return PUREKV_EINVAL;
+  if (n_layers > 1 && kv_layer_stride < 1) return PUREKV_EINVAL;
   return launch_compact(*p, k, v, kv_layer_stride, n_layers, idx, n_keep, kc, vc, cap, static_cast<hipStream_t>(stream));
 }
 
@@ -307,7 +331,8 @@ static int check_stack(const purekv_plan_t* dense, const purekv_plan_t* st, cons
     if (!launchable(st)) return PUREKV_EINVAL;
     const Geometry& b = st->g;
     if (a.N != b.N || a.Nv != b.Nv || a.P != b.P || a.Hq != b.Hq || a.Hkv != b.Hkv || a.d != b.d || a.scale != b.scale ||
-        dense->device != st->device)
+        a.q_sh != b.q_sh || a.q_st != b.q_st || a.kv_sh != b.kv_sh || a.kv_st != b.kv_st || a.o_sh != b.o_sh ||
+        a.o_st != b.o_st || dense->device != st->device)
       return PUREKV_EINVAL;
   }
   return PUREKV_OK;
@@ -352,7 +377,7 @@ int purekv_stack_select_compact(const purekv_plan_t* dense, const purekv_stack_t
     return PUREKV_EINVAL;
   if (c_all == nullptr && n_keys > 0) return PUREKV_EINVAL;
   if (cap < n_keep) return PUREKV_EINVAL;
-  if (L > 1 && kv_layer_stride < (int64_t)g.Hkv * g.N * g.d) return PUREKV_EINVAL;
+  if (L > 1 && kv_layer_stride < 1) return PUREKV_EINVAL;
   const size_t need = topk_ws_bytes(*dense, n_shared, s->w);
   if (need > 0 && (ws == nullptr || ws_bytes < need)) return PUREKV_EWORKSPACE;
   hipStream_t sm = static_cast<hipStream_t>(stream);
@@ -395,7 +420,8 @@ double purekv_calib_mfma_flops(const purekv_plan_t* p, int32_t iters) {
 }
 
 int32_t purekv_budget(int32_t n, int32_t w, double ratio) {
-  const double kept = std::floor(ratio * (double)n);
+  if (n < 0 || w < 0 || !std::isfinite(ratio) || ratio < 0.0 || ratio > 1.0) return -1;
+  const double kept = std::floor(ratio * (double)n + 1e-9);   // 0.29 * 100 is 28.999999999999996 in binary
   const int64_t h = (int64_t)kept - w;
   return h > 0 ? (int32_t)h : 0;
 }

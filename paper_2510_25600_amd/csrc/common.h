@@ -63,6 +63,24 @@ __device__ __forceinline__ void kunswz(int p, int& r, int& u) {
     u = y & 7;
   }
 }
+// Global memory straight into LDS, 16 or 4 bytes per lane: lane l's piece lands at lds_ptr + 16 l (4 l), its source
+// is base + off (a 32-bit byte offset per lane).  Written as assembly so that every wait for these loads is the
+// kernel's own: the compiler does not know which LDS buffer a load of the builtin form fills and would wait for ALL
+// outstanding ones, the loads just issued for later tiles included, before any LDS read.  base and lds_ptr must be
+// wave-uniform.  The LDS address travels in m0, which the statement overwrites (declared, so that the compiler
+// keeps nothing live in it across the load).
+typedef __attribute__((address_space(3))) void* LdsPtr;
+__device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t off, const void* lds_ptr) {
+  const uint32_t lds_base = (uint32_t)(size_t)(LdsPtr)lds_ptr;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(off), "s"(base)
+               : "memory", "m0");
+}
+__device__ __forceinline__ void load_to_lds_4(const void* base, uint32_t off, const void* lds_ptr) {
+  const uint32_t lds_base = (uint32_t)(size_t)(LdsPtr)lds_ptr;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_base), "v"(off), "s"(base)
+               : "memory", "m0");
+}
+
 // Records a failed HIP call for purekv_strerror and maps it to PUREKV_EHIP.
 int note_hip_error(hipError_t e);
 

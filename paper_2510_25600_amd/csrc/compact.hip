@@ -8,7 +8,8 @@ namespace {
 
 template <int D>
 __global__ __launch_bounds__(256) void compact_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                                                      int64_t layer_stride, const int32_t* __restrict__ idx,
+                                                      int64_t layer_stride, int64_t head_stride, int64_t tok_stride,
+                                                      const int32_t* __restrict__ idx,
                                                       uint16_t* __restrict__ kc, uint16_t* __restrict__ vc, int32_t N,
                                                       int32_t Hkv, int32_t n_keep, int32_t cap, int64_t total_rows) {
   constexpr int LPR = D / 8, RPB = 256 / LPR, UNROLL = 4;
@@ -26,7 +27,7 @@ __global__ __launch_bounds__(256) void compact_kernel(const uint16_t* __restrict
       const int64_t layer = lk / Hkv, kvh = lk - layer * Hkv;
       int32_t j = idx[r];
       j = j < 0 ? 0 : (j >= N ? N - 1 : j);
-      const int64_t src = layer * layer_stride + (kvh * N + j) * D + sub * 8;
+      const int64_t src = layer * layer_stride + kvh * head_stride + j * tok_stride + sub * 8;
       xk[u] = *reinterpret_cast<const u32x4*>(k + src);
       xv[u] = *reinterpret_cast<const u32x4*>(v + src);
       dst[u] = rid < total_rows ? (lk * cap + pos) * D + sub * 8 : -1;
@@ -63,11 +64,11 @@ int launch_compact(const purekv_plan& p, const void* k, const void* v, int64_t k
   const unsigned grid = (unsigned)(want < 65536 ? want : 65536);
   if (p.g.d == 128)
     hipLaunchKernelGGL(compact_kernel<128>, dim3(grid), dim3(256), 0, st, static_cast<const uint16_t*>(k),
-                       static_cast<const uint16_t*>(v), kv_layer_stride, idx, static_cast<uint16_t*>(kc),
+                       static_cast<const uint16_t*>(v), kv_layer_stride, p.g.kv_sh, p.g.kv_st, idx, static_cast<uint16_t*>(kc),
                        static_cast<uint16_t*>(vc), p.g.N, p.g.Hkv, n_keep, cap, total);
   else
     hipLaunchKernelGGL(compact_kernel<64>, dim3(grid), dim3(256), 0, st, static_cast<const uint16_t*>(k),
-                       static_cast<const uint16_t*>(v), kv_layer_stride, idx, static_cast<uint16_t*>(kc),
+                       static_cast<const uint16_t*>(v), kv_layer_stride, p.g.kv_sh, p.g.kv_st, idx, static_cast<uint16_t*>(kc),
                        static_cast<uint16_t*>(vc), p.g.N, p.g.Hkv, n_keep, cap, total);
   PUREKV_HIP_TRY(hipGetLastError());
   return PUREKV_OK;

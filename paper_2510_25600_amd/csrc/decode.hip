@@ -44,20 +44,7 @@ struct DecodeArgs {
   int32_t* counters;  // [Hkv * n_head_blocks], zero on entry and on exit
   int32_t Hq, G, n_cached, cap, n_splits;
   float scale_log2;
-#ifdef PUREKV_DECODE_TRACE
-  unsigned long long* trace;   // development aid: [workgroup][8] stamps of the 100 MHz counter
-#endif
 };
-
-#ifdef PUREKV_DECODE_TRACE
-#define DEC_STAMP(i)                                                                                              \
-  do {                                                                                                            \
-    if (threadIdx.x == 0)                                                                                         \
-      a.trace[(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)) * 8 + (i)] = __builtin_amdgcn_s_memrealtime(); \
-  } while (0)
-#else
-#define DEC_STAMP(i) do {} while (0)
-#endif
 
 // Device-scope (agent) relaxed accesses: coherent across the XCDs' L2s without any cache maintenance.
 __device__ __forceinline__ float ld_agent(const float* p) {
@@ -90,7 +77,6 @@ __global__ __launch_bounds__(DEC_NT) void decode_kernel(const DecodeArgs a) {
   const int last = a.n_cached - 1;
   const int j_new = a.k_new != nullptr ? last : -1;   // the key that comes from k_new / v_new
 
-  DEC_STAMP(0);
   // ---- every load of this wavefront, before any use ----
   bf16x8 qf[KS], kf[2][KS];
   {
@@ -170,7 +156,6 @@ __global__ __launch_bounds__(DEC_NT) void decode_kernel(const DecodeArgs a) {
   l += __shfl_xor(l, 16, 64);
   l += __shfl_xor(l, 32, 64);
 
-  DEC_STAMP(1);
   __syncthreads();   // V rows are in LDS
 
   // ---- O = P V: lane (n, kg) receives heads 4 kg + i, column 16 c + n ----
@@ -201,7 +186,6 @@ __global__ __launch_bounds__(DEC_NT) void decode_kernel(const DecodeArgs a) {
   }
   __syncthreads();
 
-  DEC_STAMP(2);
   // ---- merge the wavefronts; thread -> elements e = tid + DEC_NT k: head e / D, column e % D ----
   const bool single = a.n_splits == 1;
 #pragma unroll
@@ -238,12 +222,10 @@ __global__ __launch_bounds__(DEC_NT) void decode_kernel(const DecodeArgs a) {
   // issues them, so the eight L2s need no write-back or invalidation); the arrival is counted once every store of
   // the workgroup has completed.
   int32_t* counter = a.counters + kvh * gridDim.z + blockIdx.z;
-  DEC_STAMP(3);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's stores have completed
   __syncthreads();
   if (tid == 0) lds_last = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.n_splits - 1;
   __syncthreads();
-  DEC_STAMP(4);
   if (!lds_last) return;
 
   // Chunks are merged in passes of up to SB; within a pass: (max, sum) of all chunks -> LDS, maximum and weights
@@ -353,15 +335,10 @@ __global__ __launch_bounds__(DEC_NT) void decode_kernel(const DecodeArgs a) {
     const int e = tid + DEC_NT * k;
     if (e < ng * D) a.out[(size_t)(kvh * a.G + g0) * D + e] = (uint16_t)f32_to_bf16(acc[k] / run_l[k]);
   }
-  DEC_STAMP(6);
   if (tid == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
 }
 
 }  // namespace
-
-#ifdef PUREKV_DECODE_TRACE
-unsigned long long* g_decode_trace = nullptr;
-#endif
 
 size_t decode_ws_bytes(const purekv_plan& p, int32_t cap) {
   return (size_t)decode_splits(cap) * p.g.Hq * (p.g.d + 2) * sizeof(float);
@@ -387,9 +364,6 @@ int launch_decode(const purekv_plan& p, const void* q_new, const void* k_new, co
   a.n_cached = n_cached;
   a.cap = cap;
   a.scale_log2 = p.g.scale * kLog2e;
-#ifdef PUREKV_DECODE_TRACE
-  a.trace = g_decode_trace;
-#endif
   const dim3 grid((unsigned)a.n_splits, (unsigned)p.g.Hkv, (unsigned)((p.g.G + DEC_HB - 1) / DEC_HB));
   if (p.g.d == 128)
     hipLaunchKernelGGL(decode_kernel<128>, grid, dim3(DEC_NT), 0, st, a);

@@ -25,38 +25,11 @@ struct ImportanceArgs {
   const float* lse;
   float* c_out;
   int32_t N, Nv, P, Hq, G, w;
+  int64_t q_sh, kv_sh;    // element strides of the head axes of Q and K
+  uint32_t q_st, kv_st;   // and of their token axes
   uint32_t pattern;
   float scale_log2;
-#ifdef PUREKV_IMPORTANCE_TRACE
-  unsigned long long* trace;   // development aid: [workgroup][8] = 4 x (shader cycles, 100 MHz ticks) of thread 0
-#endif
 };
-
-#ifdef PUREKV_IMPORTANCE_TRACE
-#define IMP_STAMP(i)                                                                       \
-  do {                                                                                     \
-    if (threadIdx.x == 0) {                                                                \
-      a.trace[(blockIdx.x + gridDim.x * blockIdx.y) * 8 + 2 * (i)] = __builtin_readcyclecounter();       \
-      a.trace[(blockIdx.x + gridDim.x * blockIdx.y) * 8 + 2 * (i) + 1] = __builtin_amdgcn_s_memrealtime(); \
-    }                                                                                      \
-  } while (0)
-#else
-#define IMP_STAMP(i) do {} while (0)
-#endif
-
-typedef __attribute__((address_space(3))) void* LdsPtr;
-
-// Global memory straight into LDS, 16 or 4 bytes per lane: lane l's piece lands at lds_ptr + 16 l (4 l), its source is
-// base + off.  Assembly, so that the waits for these loads are the kernel's own (the compiler would wait for every
-// outstanding one before any LDS read).  base and lds_ptr must be wave-uniform.
-__device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t off, const void* lds_ptr) {
-  const uint32_t lds_base = (uint32_t)(size_t)(LdsPtr)lds_ptr;
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(off), "s"(base) : "memory");
-}
-__device__ __forceinline__ void load_to_lds_4(const void* base, uint32_t off, const void* lds_ptr) {
-  const uint32_t lds_base = (uint32_t)(size_t)(LdsPtr)lds_ptr;
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_base), "v"(off), "s"(base) : "memory");
-}
 
 // MASK = false: every window row sees every non-recent key (text rows, or the dense pattern).
 template <int D, bool MASK>
@@ -81,11 +54,10 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
   const int jw = blockIdx.x * 128 + wave * 32;  // first key of this wavefront
   const int row0 = a.N - a.w;             // first window row
 
-  IMP_STAMP(0);
   bf16x8 kf[KSTEPS];
   {
     const int j = min(jw + n, a.N - 1);
-    const uint16_t* kr = a.k + ((size_t)kvh * a.N + j) * D;
+    const uint16_t* kr = a.k + (int64_t)kvh * a.kv_sh + (int64_t)j * a.kv_st;
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) kf[s] = *reinterpret_cast<const bf16x8*>(kr + 16 * s + 8 * h);
   }
@@ -113,11 +85,11 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
   normalise(is_g, is_qb);
   auto issue_next = [&](int slot) {
     const size_t hrow = (size_t)(kvh * a.G + is_g) * a.N;
-    const uint16_t* qhead = a.q + hrow * D;
+    const uint16_t* qhead = a.q + (int64_t)(kvh * a.G + is_g) * a.q_sh;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int r = min(row0 + is_qb * 32 + st_row[i], a.N - 1);
-      load_to_lds_16(qhead, (uint32_t)(r * D + st_col[i] * 8) * 2u, &Qs[slot][(i * 256 + wave * 64) * 8]);
+      load_to_lds_16(qhead, ((uint32_t)r * a.q_st + (uint32_t)st_col[i] * 8u) * 2u, &Qs[slot][(i * 256 + wave * 64) * 8]);
     }
     load_to_lds_4(a.lse + hrow, (uint32_t)min(row0 + is_qb * 32 + n, a.N - 1) * 4u, &lse_all[set][slot][wave][0]);
     is_qb += 2;
@@ -227,7 +199,6 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
   for (int s = 0; s < KSTEPS; ++s) read_frag(A, s);
   read_pending(A.pd);
   advance_read();
-  IMP_STAMP(1);
   stage(A, B, S0, S1, false);
   int it = 1;
   for (; it + 1 < n_iter; it += 2) {
@@ -242,7 +213,6 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
 #pragma unroll
     for (int i = 0; i < 16; ++i) exp_step(S0, A.pd, i);
   }
-  IMP_STAMP(2);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // the loads started past the end have landed before LDS is reused or freed
 
   // set 0 adds set 1's sums (same wavefront index, same lane: same keys and query slots), then
@@ -265,7 +235,6 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
     x += __shfl_xor(x, 16, 64);
     acc[i] = x;
   }
-  IMP_STAMP(3);
   if (n == 0) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -276,10 +245,6 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
 }
 
 }  // namespace
-
-#ifdef PUREKV_IMPORTANCE_TRACE
-unsigned long long* g_importance_trace = nullptr;
-#endif
 
 int launch_importance(const purekv_plan& p, const void* q, const void* k, const float* lse, int32_t w,
                       float* c_out, hipStream_t st) {
@@ -295,12 +260,13 @@ int launch_importance(const purekv_plan& p, const void* q, const void* k, const 
   a.P = p.g.P;
   a.Hq = p.g.Hq;
   a.G = p.g.G;
+  a.q_sh = p.g.q_sh;
+  a.kv_sh = p.g.kv_sh;
+  a.q_st = (uint32_t)p.g.q_st;
+  a.kv_st = (uint32_t)p.g.kv_st;
   a.w = w;
   a.pattern = p.g.pattern;
   a.scale_log2 = p.g.scale * kLog2e;
-#ifdef PUREKV_IMPORTANCE_TRACE
-  a.trace = g_importance_trace;
-#endif
   const dim3 grid((unsigned)((n_keys + 127) / 128), (unsigned)p.g.Hkv), block(512);
   const bool mask = p.g.pattern != 0u && p.g.N - w < p.g.Nv;   // some window row is a video row under a sparse pattern
   if (p.g.d == 128) {

@@ -312,7 +312,6 @@ void build_plan(purekv_plan& p, int n_cu) {
   p.queue_begin.assign(1, 0);
   p.queue_units.clear();
   p.queue_units_begin.assign(1, 0);
-  const uint32_t row_bytes = uint32_t(g.d) * 2u;
   for (int32_t q = 0; q < p.n_queues; ++q) {
     for (size_t u = 0; u + 1 < queues[q].size(); u += 2) {
       const WorkItem& w = p.items[queues[q][u]];
@@ -328,7 +327,7 @@ void build_plan(purekv_plan& p, int n_cu) {
       for (int32_t t = 0; t < w.n_tiles; ++t) {
         const TileRef& r = p.tiles[w.list_begin + t];
         StreamEntry e;
-        e.kv_off = (uint32_t(kvh) * uint32_t(g.N) + uint32_t(r.tile) * BK) * row_bytes;
+        e.kv_off = uint32_t((int64_t(kvh) * g.kv_sh + int64_t(r.tile) * BK * g.kv_st) * 2);
         const int32_t k0 = r.tile * BK, rows = std::min(BK, g.N - k0);
         e.need = r.need | ((t == w.n_tiles - 1) ? (1u << 16) : 0u) | ((t == 0) ? (1u << 17) : 0u) |
                  (uint32_t(rows - 1) << 18);

@@ -47,7 +47,7 @@ struct TileRef {
 
 // One step of a persistent workgroup's stream: stage this key tile, compute it for the row blocks that need it.
 struct StreamEntry {
-  uint32_t kv_off;     // byte offset of the tile's first row within the K (and V) tensor: (kvh*N + k0)*d*2
+  uint32_t kv_off;     // byte offset of the tile's first row within the K (and V) tensor: (kvh*kv_sh + k0*kv_st)*2
   uint32_t need;       // TileRef::need | last << 16 | first << 17 | (rows - 1) << 18: last / first step of its
                        // unit (units are numbered in stream order); rows = keys of the tile that exist (1..64)
   uint32_t kinds;      // TileRef::kinds
@@ -68,6 +68,8 @@ struct Geometry {
   int32_t Hq, Hkv, G, d;
   uint32_t pattern;
   float scale;
+  // Element strides of the (head, token) axes of Q, of K and V, and of O (never 0 here: packed defaults filled in).
+  int64_t q_sh, q_st, kv_sh, kv_st, o_sh, o_st;
   // Workgroup shape: Gs query heads of one KV group x R row blocks of 32 rows, one wavefront each
   // (wavefront w: row block w / Gs, head w % Gs); Gs * R <= PUREKV_WAVES.
   int32_t Gs, R, n_groups;   // n_groups = Hq / Gs

@@ -64,46 +64,16 @@ struct PrefillArgs {
   const MergeItem* merges;
   const uint8_t* head_sel;      // [Hq] or null: a plan over a head subset (one head per workgroup) merges only those
   int32_t N, Nv, P, Hq, Hkv;
+  // byte strides of the (head, token) axes: Q, O per head and row, K/V per row (the head is in the stream entries)
+  int64_t q_head_bytes, o_head_bytes;
+  uint32_t q_row_bytes, kv_row_bytes, o_row_bytes;
   int32_t Gs, R, n_groups;   // workgroup shape: wavefront w -> row block w / Gs, head w % Gs
   uint32_t pattern;
   float scale_log2;  // softmax scale * log2(e)
-#ifdef PUREKV_PHASE_TRACE
-  unsigned long long* trace;  // [grid, 8, 64, 8] cycle stamps per wavefront, development builds only
-#endif
 };
-
-// Development builds only (PUREKV_PHASE_TRACE): cycle stamps at eight points of an iteration, or at its two ends
-// (PUREKV_TRACE_ENDS_ONLY), or only at the two ends of a workgroup (PUREKV_TRACE_WORKGROUP_ONLY).  A stamp is a counter read plus a global store; the store is one more access the
-// wait at the top of the next iteration covers, so stamped iterations run several hundred cycles longer each
-// than unstamped ones: good for comparing segments, not for absolute times.
-#ifdef PUREKV_PHASE_TRACE
-#if defined(PUREKV_TRACE_WORKGROUP_ONLY)   // only the stamps at both ends of a workgroup
-#define PHASE_MARK(i)
-#elif defined(PUREKV_TRACE_ENDS_ONLY)
-#define PHASE_MARK(i) if ((i) == 0 || (i) == 7) PHASE_MARK_(i)
-#else
-#define PHASE_MARK(i) PHASE_MARK_(i)
-#endif
-#define PHASE_MARK_(i)                                                                                  \
-  if ((threadIdx.x & 63) == 0 && t - t_begin < 64)                                                     \
-  a.trace[(((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 64 + (t - t_begin)) * 8 + (i)] = __builtin_readcyclecounter()
-#else
-#define PHASE_MARK(i)
-#endif
 
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) shortx4* LdsShortx4;
-typedef __attribute__((address_space(3))) void* LdsPtr;
-
-// 16 bytes per lane from global memory straight into LDS: lane l's piece lands at lds_base + 16 l, its source is
-// base + off (a 32-bit byte offset per lane).  Written as assembly so that every wait for these loads is the
-// kernel's own: the compiler does not know which LDS buffer a load of its builtin form targets and would wait
-// for ALL outstanding ones, the loads just issued for later tiles included, before any LDS read.
-// lds_base must be wave-uniform.
-__device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t off, const void* lds_ptr) {
-  const uint32_t lds_base = (uint32_t)(size_t)(LdsPtr)lds_ptr;
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(off), "s"(base) : "memory");
-}
 
 // V tile [BK][D] bf16 in LDS, row-major; the transpose read of a 16-lane group touches 4 consecutive rows x 32
 // bytes, two such groups run side by side: XOR-ing the 32-byte pair index with the row's low bits keeps them on
@@ -159,13 +129,6 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   const bool active = wave < a.Gs * a.R;
   const int t_begin = a.queue_begin[blockIdx.x], t_end = a.queue_begin[blockIdx.x + 1];
   if (t_begin >= t_end) return;
-#ifdef PUREKV_PHASE_TRACE
-  // development builds: shader-clock and constant-rate (100 MHz) time stamps at both ends of the workgroup
-  if (threadIdx.x == 0) {
-    a.trace[((size_t)blockIdx.x * 8 * 64 + 63) * 8 + 0] = __builtin_readcyclecounter();
-    a.trace[((size_t)blockIdx.x * 8 * 64 + 63) * 8 + 1] = __builtin_amdgcn_s_memrealtime();
-  }
-#endif
 
   // ---- load maps (per-thread constants) ----
   // Load i of this wavefront fills 16-byte positions (NLD*wave + i)*64 + lane of a tile: 1 KB of LDS, contiguous
@@ -185,13 +148,14 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     v_row[i] = r;
     v_col[i] = (uint32_t)u * 16u;
   }
+  const uint32_t kv_rb = a.kv_row_bytes;   // below 2^24: one 24-bit multiply-add per load address
   const char* const k_bytes = reinterpret_cast<const char*>(a.k);
   const char* const v_bytes = reinterpret_cast<const char*>(a.v);
   auto issue_k = [&](const Step& s, int buf) {
     const int rv = (int)((s.need >> 18) & 63u);
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const uint32_t off = s.kv_off + (uint32_t)min(k_row[i], rv) * (D * 2u) + k_col[i];
+      const uint32_t off = __umul24((uint32_t)min(k_row[i], rv), kv_rb) + (s.kv_off + k_col[i]);
       load_to_lds_16(k_bytes, off, Ks_base + buf * (BK * D) + (NLD * wave + i) * 512);
     }
   };
@@ -199,7 +163,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     const int rv = (int)((s.need >> 18) & 63u);
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const uint32_t off = s.kv_off + (uint32_t)min(v_row[i], rv) * (D * 2u) + v_col[i];
+      const uint32_t off = __umul24((uint32_t)min(v_row[i], rv), kv_rb) + (s.kv_off + v_col[i]);
       load_to_lds_16(v_bytes, off, Vs_base + buf * (BK * D) + (NLD * wave + i) * 512);
     }
   };
@@ -248,14 +212,14 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
       int ln = lane;   // opaque copy: keeps the address arithmetic inside the unit switch
       asm volatile("" : "+v"(ln));
       const int r0 = (int)un[0] + rb * 32;
-      // uniform base of the head + 32-bit lane offsets (a head is at most 2^30 bytes); the row is clamped to
+      // uniform base of the head + 32-bit lane offsets (a tensor spans at most 2^31 bytes); the row is clamped to
       // the last row of the sequence, also when the whole block lies past it (ragged last query tile)
-      const char* const qhead = reinterpret_cast<const char*>(a.q) + (size_t)((int)un[1] + hl) * a.N * (D * 2);
+      const char* const qhead = reinterpret_cast<const char*>(a.q) + (int64_t)((int)un[1] + hl) * a.q_head_bytes;
 #pragma unroll
       for (int i = 0; i < XQ; ++i) {
         int r, u;
         kunswz<D>(i * 64 + ln, r, u);
-        const uint32_t off = (uint32_t)min(r0 + r, a.N - 1) * (D * 2u) + (uint32_t)u * 16u;
+        const uint32_t off = (uint32_t)min(r0 + r, a.N - 1) * a.q_row_bytes + (uint32_t)u * 16u;
         load_to_lds_16(qhead, off, Xs + i * 512);
       }
     }
@@ -294,8 +258,8 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     if (!active) return;
     int ln = lane;
     asm volatile("" : "+v"(ln));
-    // uniform base of the tile's first row + 32-bit lane offsets (a head is at most 2^30 bytes)
-    char* const otile = reinterpret_cast<char*>(a.out) + ((size_t)hq * a.N + row0) * (D * 2);
+    // uniform base of the tile's first row + 32-bit lane offsets
+    char* const otile = reinterpret_cast<char*>(a.out) + (int64_t)hq * a.o_head_bytes + (int64_t)row0 * a.o_row_bytes;
     const int rows_left = a.N - row0;   // rows of the tile that exist
     // read the pieces back in batches of four before storing any: the LDS latencies overlap
 #pragma unroll
@@ -308,7 +272,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
       for (int i = 0; i < 4; ++i) {
         int r, u;
         kunswz<D>((i0 + i) * 64 + ln, r, u);
-        const uint32_t off = (uint32_t)r * (D * 2u) + (uint32_t)u * 16u;
+        const uint32_t off = (uint32_t)r * a.o_row_bytes + (uint32_t)u * 16u;
         if (rows_left >= 32 || r < rows_left) *reinterpret_cast<u32x4*>(otile + off) = w[i];
       }
     }
@@ -605,8 +569,6 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     const bool first = have && ((e_cur.need >> 17) & 1u);
     const bool lastp = (e_prev.need >> 16) & 1u;   // the unit of tile j-1 ends with it
     const int b_next = next_buf(bj), b_prev = next_buf(b_next);
-    [[maybe_unused]] const int t = j - 1;   // index for the development trace
-    PHASE_MARK(0);
     if (resc) {
       lacc[0] *= alpha;   // only element 0 is read back
       if (LSE) lx *= alpha;
@@ -629,16 +591,13 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     const Step e_f = fetch_step(j + 3);
     const u32x4 un_fetch = units_c[2 * (unit_id + 1)];   // the unit table ends with a spare record
     wait_loads();
-    PHASE_MARK(1);
     __syncthreads();
-    PHASE_MARK(2);
     // The loads of K(j+2) and V(j+1) are started between the MFMAs of the second product below (their address
     // arithmetic hides there); a wavefront without rows of its own starts them here.
     if (!active) {
       if (j + 2 < t_end) issue_k(e_n2, b_prev);
       if (j + 1 < t_end) issue_v(e_n1, b_next);
     }
-    PHASE_MARK(3);
     if (active) {
       // ---- score product of tile j, exponentials of tile j-1 ----
       constexpr int SPM = 8 / KSTEPS;   // slices per MFMA
@@ -663,7 +622,6 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) exp_slice(Sp, neg_m, 8 + i);
       }
-      PHASE_MARK(4);
       // ---- second product of tile j-1, running maximum of tile j ----
       if (nb & 1u) mask_block(Sn[0], kinds & 3u, e_cur.k0);
       if (nb & 2u) mask_block(Sn[1], (kinds >> 2) & 3u, e_cur.k0 + 32);
@@ -676,7 +634,6 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
         if (i == 3 && j + 1 < t_end) issue_v(e_n1, b_next);
       });
       update_reference(mt, first);
-      PHASE_MARK(5);
       if (lastp) {
         if (u_nsplits == 1)
           finish_unit();
@@ -685,9 +642,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
         adopt_unit();
       }
     }
-    PHASE_MARK(6);
     maybe_prefetch_q(j, e_cur, e_n1, un_fetch);
-    PHASE_MARK(7);
     bj = b_next;
     e_prev = e_cur;
     e_cur = e_n1;
@@ -700,12 +655,6 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     iteration(j + 1, S[0], S[1]);
     if (j + 1 == t_end) break;
   }
-#ifdef PUREKV_PHASE_TRACE
-  if (threadIdx.x == 0) {
-    a.trace[((size_t)blockIdx.x * 8 * 64 + 63) * 8 + 2] = __builtin_readcyclecounter();
-    a.trace[((size_t)blockIdx.x * 8 * 64 + 63) * 8 + 3] = __builtin_amdgcn_s_memrealtime();
-  }
-#endif
 }
 
 // Combines the partial results of a query tile whose key list was cut into slices.  One workgroup
@@ -751,7 +700,8 @@ __global__ __launch_bounds__(256) void merge_kernel(const PrefillArgs a) {
     u32x2 w2;
     w2[0] = pack_bf16(acc[c][0] * inv, acc[c][1] * inv);
     w2[1] = pack_bf16(acc[c][2] * inv, acc[c][3] * inv);
-    *reinterpret_cast<u32x2*>(a.out + ((size_t)hq * a.N + row) * D + 4 * c4) = w2;
+    *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(a.out) + (int64_t)hq * a.o_head_bytes +
+                              (int64_t)row * a.o_row_bytes + 8 * c4) = w2;
   }
   if (a.lse != nullptr && (threadIdx.x % 16) == 0)
     a.lse[(size_t)hq * a.N + row] = (mxx + __builtin_amdgcn_logf(xsum)) * kLn2;
@@ -800,6 +750,11 @@ int launch_prefill(const purekv_plan& p, const void* q, const void* k, const voi
   a.P = p.g.P;
   a.Hq = p.g.Hq;
   a.Hkv = p.g.Hkv;
+  a.q_head_bytes = p.g.q_sh * 2;
+  a.o_head_bytes = p.g.o_sh * 2;
+  a.q_row_bytes = (uint32_t)(p.g.q_st * 2);
+  a.kv_row_bytes = (uint32_t)(p.g.kv_st * 2);
+  a.o_row_bytes = (uint32_t)(p.g.o_st * 2);
   a.Gs = p.g.Gs;
   a.R = p.g.R;
   a.n_groups = p.g.n_groups;

@@ -17,14 +17,6 @@ namespace {
 
 constexpr int SEL_THREADS = 1024;
 
-#ifdef PUREKV_SEL_TRACE
-__device__ unsigned long long* g_sel_trace;   // development builds only: cycle stamps of workgroup 0
-#define SEL_MARK(i) \
-  if (blockIdx.x == 0 && threadIdx.x == 0) g_sel_trace[(i)] = __builtin_readcyclecounter()
-#else
-#define SEL_MARK(i)
-#endif
-
 // Order-preserving map from fp32 to uint32 (-0.0 first folded onto +0.0).
 __device__ __forceinline__ uint32_t sort_key(float s) {
   const uint32_t u = __float_as_uint(s + 0.0f);
@@ -73,19 +65,20 @@ __device__ __forceinline__ uint32_t wave_scan_max(uint32_t v) {
 
 template <int D>
 __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ c, const uint16_t* __restrict__ v,
-                                                    int64_t v_layer_stride, float* __restrict__ s_out, int32_t N,
+                                                    int64_t v_layer_stride, int64_t v_head_stride,
+                                                    int64_t v_tok_stride, float* __restrict__ s_out,
                                                     int32_t n_keys, int32_t Hkv) {
   constexpr int LPR = D / 8;         // lanes per row
   constexpr int RPB = 256 / LPR;     // rows per pass of the workgroup
   const int sub = threadIdx.x % LPR, rslot = threadIdx.x / LPR;
   const int lk = blockIdx.y, layer = lk / Hkv, kvh = lk - layer * Hkv;
-  const uint16_t* vh = v + (int64_t)layer * v_layer_stride + (int64_t)kvh * N * D;
+  const uint16_t* vh = v + (int64_t)layer * v_layer_stride + (int64_t)kvh * v_head_stride;
   const int j0 = blockIdx.x * (RPB * SCORE_UNROLL) + rslot;
   u32x4 x[SCORE_UNROLL];
 #pragma unroll
   for (int u = 0; u < SCORE_UNROLL; ++u) {
     const int j = min(j0 + u * RPB, n_keys - 1);
-    x[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vh + (int64_t)j * D + sub * 8));
+    x[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vh + (int64_t)j * v_tok_stride + sub * 8));
   }
 #pragma unroll
   for (int u = 0; u < SCORE_UNROLL; ++u) {
@@ -144,7 +137,6 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
   const float* sv = s + (size_t)blockIdx.x * n_keys;
   int32_t* out = idx_out + (size_t)blockIdx.x * (h + w);
 
-  SEL_MARK(0);
   for (int t = tid; t < w; t += SEL_THREADS) out[h + t] = N - w + t;
   if (h == 0) return;
 
@@ -193,7 +185,6 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
     kmin = __builtin_amdgcn_readlane(mn, 15);
     kmax = __builtin_amdgcn_readlane(mx, 31);
   }
-  SEL_MARK(1);
   // bits above `top` are common to all keys
   int top = 31 - __clz((int)(kmin ^ kmax));   // -1 when all keys are equal
   uint32_t prefix = top >= 31 ? 0u : (top < 0 ? kmax : (kmax >> (top + 1)) << (top + 1));
@@ -247,9 +238,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
     prefix |= sel[0] << shift;
     remaining = sel[1];
     top = shift - 1;
-    SEL_MARK(2 + (24 - shift) / 8);
   }
-  SEL_MARK(6);
   // prefix = key of the h-th largest score; `remaining` of the keys equal to it are kept (lowest indices)
   const uint32_t tau = prefix, need = remaining;
   uint32_t gt = 0, eq = 0;
@@ -259,7 +248,6 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
     eq += (e < live) & (key[e] == tau);
   }
   block_scan2(gt, eq, scan_lds);
-  SEL_MARK(7);
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
     if (e < live) {
@@ -273,7 +261,6 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
       }
     }
   }
-  SEL_MARK(8);
 }
 
 // Any length: the scores are re-read from memory (L2) in every pass.
@@ -390,10 +377,10 @@ int launch_topk(const purekv_plan& p, const float* c, const void* v, int64_t v_l
     const dim3 grid((unsigned)((n_keys + rows_per_block - 1) / rows_per_block), (unsigned)(n_layers * p.g.Hkv));
     if (p.g.d == 128)
       hipLaunchKernelGGL(score_kernel<128>, grid, dim3(256), 0, st, c, static_cast<const uint16_t*>(v),
-                         v_layer_stride, sbuf, p.g.N, n_keys, p.g.Hkv);
+                         v_layer_stride, p.g.kv_sh, p.g.kv_st, sbuf, n_keys, p.g.Hkv);
     else
       hipLaunchKernelGGL(score_kernel<64>, grid, dim3(256), 0, st, c, static_cast<const uint16_t*>(v),
-                         v_layer_stride, sbuf, p.g.N, n_keys, p.g.Hkv);
+                         v_layer_stride, p.g.kv_sh, p.g.kv_st, sbuf, n_keys, p.g.Hkv);
     scores = sbuf;
   } else if (s_out != nullptr && n_keys > 0) {
     PUREKV_HIP_TRY(hipMemcpyAsync(s_out, c, (size_t)p.g.Hkv * n_keys * sizeof(float), hipMemcpyDeviceToDevice, st));

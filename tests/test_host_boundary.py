@@ -60,6 +60,20 @@ def test_shape_validation_error_codes():
     assert lib.purekv_plan_create_host(ctypes.byref(pk.Shape(**good)), 256, None) == pk.EINVAL
     assert lib.purekv_plan_create_host(ctypes.byref(pk.Shape(**good)), 0, ctypes.byref(h)) == pk.EINVAL
     assert lib.purekv_plan_destroy(None) == pk.OK
+    # strides (elements): a pair of zeros = packed; otherwise 16-byte rows, token stride >= d and < 2^23, span < 2^31
+    n = 2 * 16 + 8
+    assert create(q_stride_head=64, q_stride_tok=4 * 64, kv_stride_head=64, kv_stride_tok=2 * 64,
+                  o_stride_head=64, o_stride_tok=4 * 64) == pk.OK                     # token-major [N, H, d]
+    assert create(kv_stride_head=n * 72, kv_stride_tok=72) == pk.OK                   # padded rows
+    assert create(q_stride_head=0, q_stride_tok=64) == pk.EINVAL                      # head stride missing
+    assert create(q_stride_head=n * 64, q_stride_tok=0) == pk.EINVAL                  # token stride missing
+    assert create(kv_stride_head=n * 64, kv_stride_tok=32) == pk.EINVAL               # token stride below head_dim
+    assert create(o_stride_head=n * 64 + 4, o_stride_tok=64) == pk.EINVAL             # not a multiple of 8 elements
+    assert create(q_stride_head=n * 68, q_stride_tok=68) == pk.EINVAL
+    assert create(q_stride_head=-64, q_stride_tok=64) == pk.EINVAL
+    assert create(kv_stride_head=64, kv_stride_tok=1 << 23) == pk.EINVAL              # 24-bit row stride in bytes
+    assert create(q_stride_head=1 << 30, q_stride_tok=64) == pk.EINVAL                # span beyond 2^31 bytes
+    assert create(n_frames=4096, patch_h=32, patch_w=32, n_kv_heads=4, head_dim=128) == pk.EINVAL   # packed span too
 
 
 def test_compute_calls_validate_before_touching_the_gpu():
@@ -103,6 +117,15 @@ def test_budget_matches_oracle_rule():
         r = float(rng.choice([0.05, 0.1, 0.2, 0.33, 0.35, 0.5, rng.random()]))
         assert pk.purekv_budget(n, w, r) == orc.budget(n, w, r)
     assert pk.purekv_budget(8448, 256, 0.2) == 1433
+    # decimal ratios mean what they say (0.29 * 100 is 28.999999999999996 in binary), independent of the oracle
+    for n in (100, 288, 1000, 4736, 8448, 16640, 33280):
+        for pct in range(0, 101):
+            assert pk.purekv_budget(n, 0, pct / 100) == (pct * n) // 100, (n, pct)
+    # no valid budget: negative sizes, ratios outside [0, 1] or not finite
+    for bad in (float("nan"), float("inf"), -0.1, 1.5):
+        assert pk.purekv_budget(100, 10, bad) == -1
+    assert pk.purekv_budget(-1, 10, 0.2) == -1 and pk.purekv_budget(100, -1, 0.2) == -1
+    assert pk.purekv_budget(100, 10, 1.0) == 90 and pk.purekv_budget(100, 10, 0.0) == 0
 
 
 def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern, n_wg=256):
