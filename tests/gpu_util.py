@@ -26,18 +26,34 @@ def f64_of(t: torch.Tensor) -> np.ndarray:
     return t.detach().cpu().numpy().astype(np.float64)
 
 
-def value_scale(v_f64: np.ndarray) -> float:
-    """The stated attention tolerances are absolute figures for unit-variance V.  Both error sources (bf16
-    rounding of the probabilities and of the output) are relative to the magnitude of V, so for inputs whose
-    V has grown beyond unit RMS (the 128-frame chain reaches std 1.5) the bounds scale with that RMS."""
-    return max(1.0, float(np.sqrt(np.mean(v_f64 ** 2))))
-
-
-def check_attention(got: np.ndarray, ref: np.ndarray, what: str = "", scale: float = 1.0):
+def check_attention(got: np.ndarray, ref: np.ndarray, what: str = ""):
+    """The stated bounds, as they are: max-abs 2e-2 and mean-abs 2e-3.  Returns (max, mean) for the record."""
     err = np.abs(got - ref)
     assert np.isfinite(got).all(), f"{what}: non-finite output"
-    assert err.max() <= ATTN_MAX_ABS * scale, f"{what}: max abs err {err.max():.4g}"
-    assert err.mean() <= ATTN_MEAN_ABS * scale, f"{what}: mean abs err {err.mean():.4g}"
+    assert err.max() <= ATTN_MAX_ABS, f"{what}: max abs err {err.max():.4g}"
+    assert err.mean() <= ATTN_MEAN_ABS, f"{what}: mean abs err {err.mean():.4g}"
+    return float(err.max()), float(err.mean())
+
+
+BF16_HALF_ULP = 2.0 ** -8   # relative rounding error of a bf16 value (8 significant bits)
+
+
+def check_attention_wide_values(got: np.ndarray, ref: np.ndarray, v_absmax: float, what: str = ""):
+    """Per-element bound for inputs whose values have outgrown unit variance (the 128-frame chain: |O| reaches 5).
+
+    An element may be off by the stated 2e-2 wherever that covers the arithmetic, i.e. while
+        2^-8 |ref|  (the output is rounded to bf16)  +  2^-8 * 2 |V|max / 4  (bf16 rounding of the probabilities: the
+        rounding errors of a row sum to zero against the rounded denominator, what is left is at most the spread of
+        the values they weigh, 2 |V|max, times 2^-8, and errors of independent sign over >= 16 keys leave a quarter)
+    stays below 2e-2; above that the bound is that sum.  Small elements are never loosened: for |ref| <= 2 and
+    |V|max <= 6 the bound is 2e-2.  The mean stays at the stated 2e-3."""
+    err = np.abs(got - ref)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    bound = np.maximum(ATTN_MAX_ABS, BF16_HALF_ULP * np.abs(ref) + BF16_HALF_ULP * 0.5 * v_absmax)
+    worst = (err / bound).max()
+    assert worst <= 1.0, f"{what}: err {err.flat[np.argmax(err / bound)]:.4g} at |ref| {np.abs(ref).flat[np.argmax(err / bound)]:.3g}"
+    assert err.mean() <= ATTN_MEAN_ABS, f"{what}: mean abs err {err.mean():.4g}"
+    return float(err.max()), float(err.mean())
 
 
 def check_kept_sets(idx_gpu: np.ndarray, idx_ref: np.ndarray, s_ref: np.ndarray, h: int, band: float = SCORE_BAND):
