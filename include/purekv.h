@@ -194,6 +194,20 @@ PUREKV_API int purekv_topk_select(const purekv_plan_t* plan, const float* c, con
                        void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * purekv_topk_select for callers that cannot allocate or hold a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments and results as purekv_topk_select with
+ * s_out == NULL, but the scores live in a buffer that is part of the library's device image (4 MiB per GPU, held
+ * from library load until the process ends) instead of a caller workspace.  The call allocates nothing.
+ *   Limit: n_layers * Hkv * (N - w) <= 2^20 scores, else PUREKV_EWORKSPACE (use purekv_topk_select).
+ *   All calls on one GPU share that buffer: calls that may overlap on the GPU (different streams) race; calls on one
+ *   stream are ordered and safe.  The plan must have been created on the device the call runs on.
+ */
+#define PUREKV_STATIC_SCORES_MAX (1 << 20)
+PUREKV_API int purekv_topk_select_static(const purekv_plan_t* plan, const float* c, const void* v,
+                                         int64_t v_layer_stride, int32_t n_layers, int32_t w, int32_t h,
+                                         int32_t* idx_out, void* stream);
+
+/*
  * Compaction: kc[l, kv, r, :] = k[l, kv, idx[l, kv, r], :] for r < n_keep, same for v (bit copy).
  *   k, v: bf16, layer l at + l * kv_layer_stride elements, each (Hkv, N, d) by the plan's K/V strides;
  *   idx [n_layers, Hkv, n_keep] int32 with values in [0, N) (not checked on the device beyond clamping);

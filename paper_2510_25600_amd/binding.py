@@ -61,6 +61,7 @@ def _load() -> ctypes.CDLL:
         "purekv_st_spattn_prefill": (c_int, [P, P, P, P, P, P, P, c_size_t, P]),
         "purekv_lowlayer_importance": (c_int, [P, P, P, P, c_int32, P, P, c_size_t, P]),
         "purekv_topk_select": (c_int, [P, P, P, c_int64, c_int32, c_int32, c_int32, P, P, P, c_size_t, P]),
+        "purekv_topk_select_static": (c_int, [P, P, P, c_int64, c_int32, c_int32, c_int32, P, P]),
         "purekv_kv_compact": (c_int, [P, P, P, c_int64, c_int32, P, c_int32, P, P, c_int32, P]),
         "purekv_kv_append": (c_int, [P, P, P, P, P, c_int32, c_int32, P]),
         "purekv_decode_attn": (c_int, [P, P, P, P, c_int32, c_int32, P, P, c_size_t, P]),
@@ -89,7 +90,7 @@ EXPORTS = (
     "purekv_plan_create", "purekv_plan_create_host", "purekv_plan_destroy", "purekv_plan_create_heads",
     "purekv_plan_create_heads_host", "purekv_plan_counts",
     "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_workspace_bytes", "purekv_st_spattn_prefill",
-    "purekv_lowlayer_importance", "purekv_topk_select", "purekv_kv_compact", "purekv_kv_append",
+    "purekv_lowlayer_importance", "purekv_topk_select", "purekv_topk_select_static", "purekv_kv_compact", "purekv_kv_append",
     "purekv_decode_attn", "purekv_decode_step", "purekv_stack_workspace_bytes", "purekv_stack_layer",
     "purekv_stack_select_compact", "purekv_budget", "purekv_plan_kept_tile_flops", "purekv_plan_mask_flops",
     "purekv_calib_mfma", "purekv_calib_mfma_flops", "purekv_calib_tile_step", "purekv_calib_tile_step_flops",
@@ -306,6 +307,23 @@ def purekv_topk_select(plan: Plan, c: torch.Tensor, v: Optional[torch.Tensor], w
         idx_out = idx_out[0]
         s_out = None if s_out is None else s_out[0]
     return (idx_out, s_out) if want_scores else idx_out
+
+
+def purekv_topk_select_static(plan: Plan, c: torch.Tensor, v: Optional[torch.Tensor], w: int, h: int,
+                              idx_out: torch.Tensor) -> torch.Tensor:
+    """purekv_topk_select on the library's static score buffer: no workspace, and nothing is allocated here either
+    (idx_out [L, Hkv, h+w] int32, or [Hkv, h+w] when v has no layer axis, is the caller's)."""
+    assert c.dtype == torch.float32 and c.is_contiguous() and c.is_cuda
+    assert idx_out.dtype == torch.int32 and idx_out.is_contiguous() and idx_out.is_cuda
+    layered = v is not None and v.dim() == 4
+    n_layers = v.shape[0] if layered else 1
+    stride = v.stride(0) if layered else 0
+    if v is not None:
+        _strided_bf16(v, "v", plan.Hkv, plan.N, plan.d, plan.kv_strides)
+    assert idx_out.numel() == n_layers * plan.Hkv * (h + w)
+    _check(_lib.purekv_topk_select_static(plan.handle, c.data_ptr(), _ptr(v), stride, n_layers, w, h,
+                                          idx_out.data_ptr(), _stream()), "purekv_topk_select_static")
+    return idx_out
 
 
 def purekv_kv_compact(plan: Plan, k: torch.Tensor, v: torch.Tensor, idx: torch.Tensor, cap: Optional[int] = None,

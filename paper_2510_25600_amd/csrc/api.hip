@@ -133,6 +133,11 @@ static int create_on_device(const purekv_shape_t* shape, const uint8_t* head_mas
   rc = make_plan(shape, &p, n_cu > 0 ? n_cu : 256, head_mask);
   if (rc != PUREKV_OK) return rc;
   p->device = dev;
+  rc = static_score_buffer(dev, &p->d_static_scores);
+  if (rc != PUREKV_OK) {
+    delete p;
+    return rc;
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
   const size_t sb = p->stream.size() * sizeof(StreamEntry), ub = p->units.size() * sizeof(Unit),
                qb = p->queue_begin.size() * sizeof(int32_t), mb = p->merges.size() * sizeof(MergeItem);
@@ -281,6 +286,20 @@ int purekv_topk_select(const purekv_plan_t* p, const float* c, const void* v, in
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return PUREKV_EWORKSPACE;
   }
   return launch_topk(*p, c, v, v_layer_stride, n_layers, w, h, idx_out, s_out, ws, static_cast<hipStream_t>(stream));
+}
+
+int purekv_topk_select_static(const purekv_plan_t* p, const float* c, const void* v, int64_t v_layer_stride,
+                              int32_t n_layers, int32_t w, int32_t h, int32_t* idx_out, void* stream) {
+  if (!launchable(p) || idx_out == nullptr || n_layers < 1) return PUREKV_EINVAL;
+  if (w < 1 || w > p->g.N || h < 0 || h > p->g.N - w) return PUREKV_EINVAL;
+  if (c == nullptr && w < p->g.N) return PUREKV_EINVAL;
+  if (v == nullptr && n_layers != 1) return PUREKV_EINVAL;
+  if (v != nullptr && n_layers > 1 && v_layer_stride < 1) return PUREKV_EINVAL;
+  if (v != nullptr && (size_t)n_layers * p->g.Hkv * (size_t)(p->g.N - w) > topk_static_capacity_floats())
+    return PUREKV_EWORKSPACE;   // the scores do not fit the static buffer: use purekv_topk_select with a workspace
+  if (p->d_static_scores == nullptr) return PUREKV_EINVAL;
+  return launch_topk(*p, c, v, v_layer_stride, n_layers, w, h, idx_out, nullptr, p->d_static_scores,
+                     static_cast<hipStream_t>(stream));
 }
 
 int purekv_kv_compact(const purekv_plan_t* p, const void* k, const void* v, int64_t kv_layer_stride, int32_t n_layers,

@@ -97,6 +97,9 @@ int launch_importance(const purekv_plan& p, const void* q, const void* k, const 
                       float* c_out, hipStream_t st);
 int launch_topk(const purekv_plan& p, const float* c, const void* v, int64_t v_layer_stride, int32_t n_layers,
                 int32_t w, int32_t h, int32_t* idx_out, float* s_out, void* ws, hipStream_t st);
+// Library-owned score buffer of the current device (looked up once per device) and its capacity in floats.
+int static_score_buffer(int device, float** out);
+size_t topk_static_capacity_floats();
 int launch_compact(const purekv_plan& p, const void* k, const void* v, int64_t kv_layer_stride, int32_t n_layers,
                    const int32_t* idx, int32_t n_keep, void* kc, void* vc, int32_t cap, hipStream_t st);
 int launch_append(const purekv_plan& p, const void* k_new, const void* v_new, void* kc, void* vc, int32_t n_cached,

@@ -101,6 +101,7 @@ struct purekv_plan {
   int32_t* d_queue_unit0 = nullptr;        // [n_queues + 1] first unit of each queue
   purekv::MergeItem* d_merges = nullptr;
   int32_t* d_counters = nullptr;           // arrival counters of the decode kernel, zero between calls
+  float* d_static_scores = nullptr;        // the library's static score buffer on this plan's device (not owned)
   // Head subset (empty: every query head).  A plan over a subset lists units for the selected heads only and leaves
   // the other heads' rows of every output untouched; it keeps the stacked workgroup shape when the subset consists
   // of whole stacks, else it runs one head per workgroup (Gs = 1).

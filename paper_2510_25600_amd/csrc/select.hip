@@ -10,6 +10,8 @@
 //                  every pass); an ordered pass then emits, ascending, every
 //                  index above it plus the lowest-index ties.  Integer work only: the result is the one a
 //                  stable full sort would give.
+#include <mutex>
+
 #include "common.h"
 
 namespace purekv {
@@ -359,7 +361,35 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel_stream(const float*
   }
 }
 
+// Score buffer of purekv_topk_select_static: device memory that exists from the moment the library is loaded
+// on a GPU until the process ends, so that the call needs no workspace from its caller and no allocation.  Host
+// code never uses the array's name as an address (in host code the name is only a handle for the symbol look-up):
+// static_score_buffer() asks the runtime once per device for the array's device address and hands that out.
+constexpr size_t kStaticScoreFloats = (size_t)1 << 20;   // 4 MiB
+static __device__ __align__(256) float scratch[kStaticScoreFloats];
+
 }  // namespace
+
+size_t topk_static_capacity_floats() { return kStaticScoreFloats; }
+
+int static_score_buffer(int device, float** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static float* ptrs[kMaxDevices] = {};
+  if (device < 0 || device >= kMaxDevices) return PUREKV_EINVAL;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptrs[device] == nullptr) {
+    int cur = -1;
+    PUREKV_HIP_TRY(hipGetDevice(&cur));
+    if (cur != device) return PUREKV_EINVAL;   // every GPU has its own copy of the array: look it up on its own device
+    void* p = nullptr;
+    PUREKV_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return PUREKV_EHIP;
+    ptrs[device] = static_cast<float*>(p);
+  }
+  *out = ptrs[device];
+  return PUREKV_OK;
+}
 
 size_t topk_ws_bytes(const purekv_plan& p, int32_t n_layers, int32_t w) {
   // scores, when the caller does not ask for them

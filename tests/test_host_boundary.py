@@ -86,6 +86,8 @@ def test_compute_calls_validate_before_touching_the_gpu():
     assert lib.purekv_st_spattn_prefill(None, one, one, one, one, None, None, 0, None) == pk.EINVAL
     assert lib.purekv_lowlayer_importance(h, one, one, one, 8, one, None, 0, None) == pk.EINVAL
     assert lib.purekv_topk_select(h, one, None, 0, 1, 8, 4, one, None, None, 0, None) == pk.EINVAL
+    assert lib.purekv_topk_select_static(h, one, one, 0, 1, 8, 4, one, None) == pk.EINVAL
+    assert lib.purekv_topk_select_static(None, one, one, 0, 1, 8, 4, one, None) == pk.EINVAL
     assert lib.purekv_kv_compact(h, one, one, 0, 1, one, 4, one, one, 4, None) == pk.EINVAL
     assert lib.purekv_kv_append(h, one, one, one, one, 0, 4, None) == pk.EINVAL
     assert lib.purekv_decode_attn(h, one, one, one, 4, 4, one, one, 1 << 20, None) == pk.EINVAL
