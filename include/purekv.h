@@ -28,7 +28,11 @@
  *   - Return value: PUREKV_OK (0) or a negative purekv_status.  All argument validation happens on the
  *     host before any GPU call, so EINVAL / EUNSUPPORTED / EWORKSPACE never leave work half enqueued.
  *   - Workspaces: purekv_workspace_bytes() gives the size an operation needs; pass a device buffer of at
- *     least that size (may be NULL when the size is 0).  Contents need no initialisation.
+ *     least that size (may be NULL when the size is 0), 256-byte aligned.  The PREFILL and DECODE workspaces begin
+ *     with arrival counters through which workgroups of one launch hand partial results to each other: such a
+ *     buffer must be initialised ONCE with purekv_workspace_init before its first use (and again after a failed
+ *     launch, or after anything else wrote to it); every call leaves it ready for the next.  Calls that may overlap
+ *     on the GPU need workspaces of their own; a plan may be shared by any number of streams.
  */
 #ifndef PUREKV_H_
 #define PUREKV_H_
@@ -156,6 +160,12 @@ PUREKV_API int purekv_plan_queue(const purekv_plan_t* plan, int32_t wg, int32_t*
  * scores S of Eq. 3 / Eq. 4 when the caller does not ask for them; DECODE, the per-chunk partial results of the
  * decode stage.  IMPORTANCE (Eq. 2) and COMPACT need none. */
 PUREKV_API size_t purekv_workspace_bytes(const purekv_plan_t* plan, int op, int32_t n_layers, int32_t w, int32_t cap);
+/* Prepares a fresh workspace of `op` (same n_layers, w, cap as for purekv_workspace_bytes): clears the arrival
+ * counters of a PREFILL or DECODE workspace with a small kernel on `stream` (no memset node: the call may be
+ * captured in a graph); nothing to do for the other ops.  EWORKSPACE if ws is NULL or too small while the op needs
+ * one. */
+PUREKV_API int purekv_workspace_init(const purekv_plan_t* plan, int op, void* ws, size_t ws_bytes, int32_t n_layers,
+                                     int32_t w, int32_t cap, void* stream);
 
 /*
  * Prefill attention under the plan's pattern (Sec. 3.2; Eq. 1 when the pattern is dense):
@@ -235,8 +245,8 @@ PUREKV_API int purekv_decode_attn(const purekv_plan_t* plan, const void* q_new, 
  * One decode step in one launch (the decode stage of the paper's inference-speed table, per generated token):
  * stores k_new, v_new [Hkv, d] as row n_cached of kc, vc (as purekv_kv_append does) and attends q_new over rows
  * 0 .. n_cached inclusive (as purekv_decode_attn with n_cached + 1 does).  0 <= n_cached < cap.
- * Both decode calls keep per-plan arrival counters on the device: calls that share a plan must not overlap on the
- * GPU (calls on one stream never do).
+ * Both decode calls count chunk arrivals in their workspace (see "Workspaces" above): calls on different
+ * workspaces are independent, whether or not they share a plan.
  */
 PUREKV_API int purekv_decode_step(const purekv_plan_t* plan, const void* q_new, const void* k_new, const void* v_new,
                                   void* kc, void* vc, int32_t n_cached, int32_t cap, void* out, void* ws,
@@ -260,7 +270,8 @@ PUREKV_API int purekv_decode_step(const purekv_plan_t* plan, const void* q_new, 
  *   c_all fp32 [clie_layer + 1, Hkv, N - w]: layer l <= clie_layer writes block l.
  *   k_all, v_all: bf16, layer l at + l * kv_layer_stride elements, each [Hkv, N, d].
  *   idx_all int32 [n_layers, Hkv, h + w];  kc_all, vc_all bf16 [n_layers, Hkv, cap, d], cap >= h + w.
- *   ws: at least purekv_stack_workspace_bytes() bytes serve every call of the stack.
+ *   ws: at least purekv_stack_workspace_bytes() bytes serve every call of the stack; initialise it once with
+ *   purekv_stack_workspace_init (it holds the prefill workspaces of both plans, see "Workspaces" above).
  */
 typedef struct {
   int32_t n_layers;   /* L >= 1                                                            */
@@ -270,12 +281,14 @@ typedef struct {
 } purekv_stack_t;
 PUREKV_API size_t purekv_stack_workspace_bytes(const purekv_plan_t* dense_plan, const purekv_plan_t* st_plan,
                                                const purekv_stack_t* stack);
+PUREKV_API int purekv_stack_workspace_init(const purekv_plan_t* dense_plan, const purekv_plan_t* st_plan,
+                                           const purekv_stack_t* stack, void* ws, size_t ws_bytes, void* stream);
 PUREKV_API int purekv_stack_layer(const purekv_plan_t* dense_plan, const purekv_plan_t* st_plan,
                                   const purekv_stack_t* stack, int32_t layer, const void* q, const void* k,
                                   const void* v, void* out, float* lse, float* c_all, void* ws, size_t ws_bytes,
                                   void* stream);
-PUREKV_API int purekv_stack_select_compact(const purekv_plan_t* dense_plan, const purekv_stack_t* stack,
-                                           const float* c_all, const void* k_all, const void* v_all,
+PUREKV_API int purekv_stack_select_compact(const purekv_plan_t* dense_plan, const purekv_plan_t* st_plan,
+                                           const purekv_stack_t* stack, const float* c_all, const void* k_all, const void* v_all,
                                            int64_t kv_layer_stride, int32_t* idx_all, void* kc_all, void* vc_all,
                                            int32_t cap, void* ws, size_t ws_bytes, void* stream);
 

@@ -14,7 +14,9 @@ from typing import Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpurekv.so")
+# PUREKV_LIB names another build of the same sources to load instead (the host-sanitizer build of the planner and
+# the validation code, a tuning build); the default is the library built in-tree.
+LIB_PATH = os.environ.get("PUREKV_LIB") or os.path.join(_HERE, "libpurekv.so")
 
 PATTERN_DENSE, PATTERN_SPATIAL, PATTERN_TEMPORAL, PATTERN_ST = 0, 1, 2, 3
 OP_PREFILL, OP_IMPORTANCE, OP_TOPK, OP_COMPACT, OP_DECODE = 0, 1, 2, 3, 4
@@ -58,6 +60,8 @@ def _load() -> ctypes.CDLL:
         "purekv_plan_item": (c_int, [P, c_int32, POINTER(c_int32)]),
         "purekv_plan_queue": (c_int, [P, c_int32, POINTER(c_int32), c_int32]),
         "purekv_workspace_bytes": (c_size_t, [P, c_int, c_int32, c_int32, c_int32]),
+        "purekv_workspace_init": (c_int, [P, c_int, P, c_size_t, c_int32, c_int32, c_int32, P]),
+        "purekv_stack_workspace_init": (c_int, [P, P, P, P, c_size_t, P]),
         "purekv_st_spattn_prefill": (c_int, [P, P, P, P, P, P, P, c_size_t, P]),
         "purekv_lowlayer_importance": (c_int, [P, P, P, P, c_int32, P, P, c_size_t, P]),
         "purekv_topk_select": (c_int, [P, P, P, c_int64, c_int32, c_int32, c_int32, P, P, P, c_size_t, P]),
@@ -68,7 +72,7 @@ def _load() -> ctypes.CDLL:
         "purekv_decode_step": (c_int, [P, P, P, P, P, P, c_int32, c_int32, P, P, c_size_t, P]),
         "purekv_stack_workspace_bytes": (c_size_t, [P, P, P]),
         "purekv_stack_layer": (c_int, [P, P, P, c_int32, P, P, P, P, P, P, P, c_size_t, P]),
-        "purekv_stack_select_compact": (c_int, [P, P, P, P, P, c_int64, P, P, P, c_int32, P, c_size_t, P]),
+        "purekv_stack_select_compact": (c_int, [P, P, P, P, P, P, c_int64, P, P, P, c_int32, P, c_size_t, P]),
         "purekv_budget": (c_int32, [c_int32, c_int32, c_double]),
         "purekv_plan_kept_tile_flops": (c_double, [P]),
         "purekv_plan_mask_flops": (c_double, [P]),
@@ -89,7 +93,8 @@ _lib = _load()
 EXPORTS = (
     "purekv_plan_create", "purekv_plan_create_host", "purekv_plan_destroy", "purekv_plan_create_heads",
     "purekv_plan_create_heads_host", "purekv_plan_counts",
-    "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_workspace_bytes", "purekv_st_spattn_prefill",
+    "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_workspace_bytes", "purekv_workspace_init",
+    "purekv_stack_workspace_init", "purekv_st_spattn_prefill",
     "purekv_lowlayer_importance", "purekv_topk_select", "purekv_topk_select_static", "purekv_kv_compact", "purekv_kv_append",
     "purekv_decode_attn", "purekv_decode_step", "purekv_stack_workspace_bytes", "purekv_stack_layer",
     "purekv_stack_select_compact", "purekv_budget", "purekv_plan_kept_tile_flops", "purekv_plan_mask_flops",
@@ -245,14 +250,20 @@ class Plan:
     def workspace_bytes(self, op: int, n_layers: int = 0, w: int = 0, cap: int = 0) -> int:
         return int(_lib.purekv_workspace_bytes(self._h, op, n_layers, w, cap))
 
-    def _workspace(self, op: int, nbytes: int, device) -> Optional[torch.Tensor]:
-        """Device scratch owned by the Python wrapper (torch memory), reused across calls."""
+    def _workspace(self, op: int, nbytes: int, device, n_layers: int = 0, w: int = 0, cap: int = 0) -> Optional[torch.Tensor]:
+        """Device scratch owned by the Python wrapper (torch memory), reused across calls on the stream that first
+        used it (a buffer used from another stream gets a workspace of its own: concurrent calls must not share one).
+        A new buffer is handed to purekv_workspace_init once."""
         if nbytes == 0:
             return None
-        t = self._ws.get(op)
+        key = (op, torch.cuda.current_stream().cuda_stream)
+        t = self._ws.get(key)
         if t is None or t.numel() < nbytes or t.device != device:
             t = torch.empty(nbytes, dtype=torch.uint8, device=device)
-            self._ws[op] = t
+            self._ws[key] = t
+            if op >= 0:
+                _check(_lib.purekv_workspace_init(self._h, op, t.data_ptr(), nbytes, n_layers, w, cap, _stream()),
+                       "purekv_workspace_init")
         return t
 
 
@@ -364,7 +375,7 @@ def purekv_decode_attn(plan: Plan, q_new: torch.Tensor, kc: torch.Tensor, vc: to
     if out is None:
         out = torch.empty_like(q_new)
     nb = plan.workspace_bytes(OP_DECODE, cap=cap)
-    ws = plan._workspace(OP_DECODE, nb, q_new.device)
+    ws = plan._workspace(OP_DECODE, nb, q_new.device, cap=cap)
     _check(_lib.purekv_decode_attn(plan.handle, q_new.data_ptr(), kc.data_ptr(), vc.data_ptr(), n_cached, cap,
                                    out.data_ptr(), _ptr(ws), nb, _stream()), "purekv_decode_attn")
     return out
@@ -379,7 +390,7 @@ def purekv_decode_step(plan: Plan, q_new: torch.Tensor, k_new: torch.Tensor, v_n
     if out is None:
         out = torch.empty_like(q_new)
     nb = plan.workspace_bytes(OP_DECODE, cap=cap)
-    ws = plan._workspace(OP_DECODE, nb, q_new.device)
+    ws = plan._workspace(OP_DECODE, nb, q_new.device, cap=cap)
     _check(_lib.purekv_decode_step(plan.handle, q_new.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), kc.data_ptr(),
                                    vc.data_ptr(), n_cached, cap, out.data_ptr(), _ptr(ws), nb, _stream()),
            "purekv_decode_step")
@@ -392,8 +403,19 @@ class Stack(ctypes.Structure):
 
 
 def _stack_ws(dense: Plan, st: Optional[Plan], stack: Stack, device) -> tuple:
-    nb = int(_lib.purekv_stack_workspace_bytes(dense.handle, st.handle if st is not None else None, byref(stack)))
-    return nb, dense._workspace(-1, nb, device)
+    sth = st.handle if st is not None else None
+    nb = int(_lib.purekv_stack_workspace_bytes(dense.handle, sth, byref(stack)))
+    if nb == 0:
+        return 0, None
+    key = (-1, torch.cuda.current_stream().cuda_stream, int(st._h.value or 0) if st is not None else 0,
+           stack.n_layers, stack.clie_layer, stack.st_layer, stack.w)
+    t = dense._ws.get(key)
+    if t is None or t.numel() < nb or t.device != device:
+        t = torch.empty(nb, dtype=torch.uint8, device=device)
+        dense._ws[key] = t
+        _check(_lib.purekv_stack_workspace_init(dense.handle, sth, byref(stack), t.data_ptr(), nb, _stream()),
+               "purekv_stack_workspace_init")
+    return nb, t
 
 
 def purekv_stack_layer(dense: Plan, st: Optional[Plan], stack: Stack, layer: int, q: torch.Tensor, k: torch.Tensor,
@@ -418,7 +440,7 @@ def purekv_stack_select_compact(dense: Plan, st: Optional[Plan], stack: Stack, c
     _dev_bf16(kc_all, "kc_all"), _dev_bf16(vc_all, "vc_all")
     assert k_all.dim() == 4 and v_all.stride(0) == k_all.stride(0)
     nb, ws = _stack_ws(dense, st, stack, k_all.device)
-    _check(_lib.purekv_stack_select_compact(dense.handle, byref(stack), _ptr(c_all), k_all.data_ptr(), v_all.data_ptr(),
+    _check(_lib.purekv_stack_select_compact(dense.handle, st.handle if st is not None else None, byref(stack), _ptr(c_all), k_all.data_ptr(), v_all.data_ptr(),
                                             k_all.stride(0), idx_all.data_ptr(), kc_all.data_ptr(), vc_all.data_ptr(),
                                             kc_all.shape[-2], _ptr(ws), nb, _stream()), "purekv_stack_select_compact")
     return idx_all, kc_all, vc_all

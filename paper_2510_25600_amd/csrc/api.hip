@@ -38,6 +38,7 @@ static int check_shape(const purekv_shape_t* s) {
   if (s == nullptr) return PUREKV_EINVAL;
   if (s->n_frames < 1 || s->patch_h < 1 || s->patch_w < 1 || s->n_text < 0) return PUREKV_EINVAL;
   if (s->n_q_heads < 1 || s->n_kv_heads < 1 || s->n_q_heads % s->n_kv_heads != 0) return PUREKV_EINVAL;
+  if (s->n_q_heads > 4096) return PUREKV_EINVAL;   // 32-bit byte offsets into the per-slice tables of split lists
   if (!(s->softmax_scale >= 0.f) || std::isinf(s->softmax_scale)) return PUREKV_EINVAL;
   const int64_t p = (int64_t)s->patch_h * s->patch_w, n = p * s->n_frames + s->n_text;
   if (p > (1 << 22) || n > (int64_t)1 << 22) return PUREKV_EINVAL;
@@ -140,25 +141,16 @@ static int create_on_device(const purekv_shape_t* shape, const uint8_t* head_mas
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
   const size_t sb = p->stream.size() * sizeof(StreamEntry), ub = p->units.size() * sizeof(Unit),
-               qb = p->queue_begin.size() * sizeof(int32_t), mb = p->merges.size() * sizeof(MergeItem);
+               qb = p->queue_begin.size() * sizeof(int32_t);
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->d_stream), sb ? sb : 16);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_units), ub ? ub : 16);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_queue_begin), qb ? qb : 16);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_queue_unit0), qb ? qb : 16);
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_merges), mb ? mb : 16);
-  const size_t cb = (size_t)decode_counter_count(*p) * sizeof(int32_t);
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->d_counters), cb);
-  if (e == hipSuccess) e = hipMemsetAsync(p->d_counters, 0, cb, st);
-  if (e == hipSuccess && !p->head_sel.empty()) {
-    e = hipMalloc(reinterpret_cast<void**>(&p->d_head_sel), p->head_sel.size());
-    if (e == hipSuccess) e = hipMemcpyAsync(p->d_head_sel, p->head_sel.data(), p->head_sel.size(), hipMemcpyHostToDevice, st);
-  }
   if (e == hipSuccess && sb) e = hipMemcpyAsync(p->d_stream, p->stream.data(), sb, hipMemcpyHostToDevice, st);
   if (e == hipSuccess && ub) e = hipMemcpyAsync(p->d_units, p->units.data(), ub, hipMemcpyHostToDevice, st);
   if (e == hipSuccess && qb) e = hipMemcpyAsync(p->d_queue_begin, p->queue_begin.data(), qb, hipMemcpyHostToDevice, st);
   if (e == hipSuccess && qb)
     e = hipMemcpyAsync(p->d_queue_unit0, p->queue_units_begin.data(), qb, hipMemcpyHostToDevice, st);
-  if (e == hipSuccess && mb) e = hipMemcpyAsync(p->d_merges, p->merges.data(), mb, hipMemcpyHostToDevice, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);  // the host vectors must outlive the copies: finish them now
   if (e != hipSuccess) {
     purekv_plan_destroy(p);
@@ -174,9 +166,6 @@ int purekv_plan_destroy(purekv_plan_t* p) {
   if (p->d_units) (void)hipFree(p->d_units);
   if (p->d_queue_begin) (void)hipFree(p->d_queue_begin);
   if (p->d_queue_unit0) (void)hipFree(p->d_queue_unit0);
-  if (p->d_merges) (void)hipFree(p->d_merges);
-  if (p->d_counters) (void)hipFree(p->d_counters);
-  if (p->d_head_sel) (void)hipFree(p->d_head_sel);
   delete p;
   return PUREKV_OK;
 }
@@ -253,6 +242,19 @@ size_t purekv_workspace_bytes(const purekv_plan_t* p, int op, int32_t n_layers, 
     default:
       return 0;
   }
+}
+
+int purekv_workspace_init(const purekv_plan_t* p, int op, void* ws, size_t ws_bytes, int32_t n_layers, int32_t w,
+                          int32_t cap, void* stream) {
+  if (!launchable(p)) return PUREKV_EINVAL;
+  if (op < PUREKV_OP_PREFILL || op > PUREKV_OP_DECODE) return PUREKV_EINVAL;
+  const size_t need = purekv_workspace_bytes(p, op, n_layers, w, cap);
+  if (need == 0) return PUREKV_OK;
+  if (ws == nullptr || ws_bytes < need) return PUREKV_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (op == PUREKV_OP_PREFILL) return launch_prefill_ws_init(*p, ws, st);
+  if (op == PUREKV_OP_DECODE) return launch_decode_ws_init(*p, ws, st);
+  return PUREKV_OK;   // the other workspaces hold nothing that outlives a call
 }
 
 int purekv_st_spattn_prefill(const purekv_plan_t* p, const void* q, const void* k, const void* v, void* out,
@@ -357,11 +359,37 @@ static int check_stack(const purekv_plan_t* dense, const purekv_plan_t* st, cons
   return PUREKV_OK;
 }
 
+// One buffer serves every call of a stack: [prefill workspace of the dense plan][prefill workspace of the sparse
+// plan][scores of the selection].  The three parts are disjoint because the prefill workspaces begin with arrival
+// counters that must stay zero between calls: nothing else may ever write there.
+struct StackWs {
+  size_t st_off = 0, scores_off = 0, total = 0;
+};
+static StackWs stack_ws_layout(const purekv_plan_t* dense, const purekv_plan_t* st, const purekv_stack_t* s) {
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  StackWs l;
+  l.st_off = up(prefill_ws_bytes(*dense));
+  l.scores_off = l.st_off + (s->st_layer < s->n_layers ? up(prefill_ws_bytes(*st)) : 0);
+  l.total = l.scores_off + topk_ws_bytes(*dense, s->n_layers - s->clie_layer, s->w);
+  return l;
+}
+
 size_t purekv_stack_workspace_bytes(const purekv_plan_t* dense, const purekv_plan_t* st, const purekv_stack_t* s) {
   if (check_stack(dense, st, s) != PUREKV_OK) return 0;
-  size_t need = std::max(prefill_ws_bytes(*dense), topk_ws_bytes(*dense, s->n_layers - s->clie_layer, s->w));
-  if (s->st_layer < s->n_layers) need = std::max(need, prefill_ws_bytes(*st));
-  return need;
+  return stack_ws_layout(dense, st, s).total;
+}
+
+int purekv_stack_workspace_init(const purekv_plan_t* dense, const purekv_plan_t* st, const purekv_stack_t* s, void* ws,
+                                size_t ws_bytes, void* stream) {
+  const int rc = check_stack(dense, st, s);
+  if (rc != PUREKV_OK) return rc;
+  const StackWs l = stack_ws_layout(dense, st, s);
+  if (l.total == 0) return PUREKV_OK;
+  if (ws == nullptr || ws_bytes < l.total) return PUREKV_EWORKSPACE;
+  hipStream_t sm = static_cast<hipStream_t>(stream);
+  int r = launch_prefill_ws_init(*dense, ws, sm);
+  if (r == PUREKV_OK && s->st_layer < s->n_layers) r = launch_prefill_ws_init(*st, static_cast<char*>(ws) + l.st_off, sm);
+  return r;
 }
 
 int purekv_stack_layer(const purekv_plan_t* dense, const purekv_plan_t* st, const purekv_stack_t* s, int32_t layer,
@@ -375,30 +403,33 @@ int purekv_stack_layer(const purekv_plan_t* dense, const purekv_plan_t* st, cons
   const purekv_plan_t* p = sparse ? st : dense;
   const int n_keys = p->g.N - s->w;
   if (emits_c && (lse == nullptr || (c_all == nullptr && n_keys > 0))) return PUREKV_EINVAL;
-  const size_t need = prefill_ws_bytes(*p);
-  if (need > 0 && (ws == nullptr || ws_bytes < need)) return PUREKV_EWORKSPACE;
+  const StackWs lay = stack_ws_layout(dense, st, s);
+  if (lay.total > 0 && (ws == nullptr || ws_bytes < lay.total)) return PUREKV_EWORKSPACE;
+  if (ws != nullptr && sparse) ws = static_cast<char*>(ws) + lay.st_off;
   hipStream_t sm = static_cast<hipStream_t>(stream);
   const int rp = launch_prefill(*p, q, k, v, out, emits_c ? lse : nullptr, ws, sm);
   if (rp != PUREKV_OK || !emits_c) return rp;
   return launch_importance(*p, q, k, lse, s->w, c_all + (size_t)layer * p->g.Hkv * n_keys, sm);
 }
 
-int purekv_stack_select_compact(const purekv_plan_t* dense, const purekv_stack_t* s, const float* c_all, const void* k_all,
-                                const void* v_all, int64_t kv_layer_stride, int32_t* idx_all, void* kc_all, void* vc_all,
-                                int32_t cap, void* ws, size_t ws_bytes, void* stream) {
-  if (!launchable(dense) || s == nullptr) return PUREKV_EINVAL;
-  if (s->n_layers < 1 || s->clie_layer < 0 || s->clie_layer >= s->st_layer || s->st_layer > s->n_layers)
-    return PUREKV_EINVAL;
+int purekv_stack_select_compact(const purekv_plan_t* dense, const purekv_plan_t* st, const purekv_stack_t* s,
+                                const float* c_all, const void* k_all, const void* v_all, int64_t kv_layer_stride,
+                                int32_t* idx_all, void* kc_all, void* vc_all, int32_t cap, void* ws, size_t ws_bytes,
+                                void* stream) {
+  const int rcs = check_stack(dense, st, s);
+  if (rcs != PUREKV_OK) return rcs;
   const Geometry& g = dense->g;
-  if (s->w < 1 || s->w > g.N || s->h < 0 || s->h > g.N - s->w) return PUREKV_EINVAL;
   const int n_keys = g.N - s->w, n_keep = s->h + s->w, L = s->n_layers, n_shared = L - s->clie_layer;
   if (k_all == nullptr || v_all == nullptr || idx_all == nullptr || kc_all == nullptr || vc_all == nullptr)
     return PUREKV_EINVAL;
   if (c_all == nullptr && n_keys > 0) return PUREKV_EINVAL;
   if (cap < n_keep) return PUREKV_EINVAL;
   if (L > 1 && kv_layer_stride < 1) return PUREKV_EINVAL;
+  // the same buffer the layers used: the scores go behind the prefill counters (see stack_ws_layout)
+  const size_t scores_off = stack_ws_layout(dense, st, s).scores_off;
   const size_t need = topk_ws_bytes(*dense, n_shared, s->w);
-  if (need > 0 && (ws == nullptr || ws_bytes < need)) return PUREKV_EWORKSPACE;
+  if (need > 0 && (ws == nullptr || ws_bytes < scores_off + need)) return PUREKV_EWORKSPACE;
+  ws = static_cast<char*>(ws) + scores_off;
   hipStream_t sm = static_cast<hipStream_t>(stream);
   const uint16_t* vb = static_cast<const uint16_t*>(v_all);
   const size_t c_stride = (size_t)g.Hkv * n_keys, idx_stride = (size_t)g.Hkv * n_keep;

@@ -107,7 +107,6 @@ int launch_append(const purekv_plan& p, const void* k_new, const void* v_new, vo
 // k_new, v_new null: attention only; else row n_cached - 1 comes from them and is stored into kc, vc
 int launch_decode(const purekv_plan& p, const void* q_new, const void* k_new, const void* v_new, void* kc, void* vc,
                   int32_t n_cached, int32_t cap, void* out, void* ws, hipStream_t st);
-int decode_counter_count(const purekv_plan& p);
 
 int launch_calib_mfma(const purekv_plan& p, int mix, int random_operands, int32_t iters, float* sink, uint64_t* ticks,
                       hipStream_t st);
@@ -117,6 +116,10 @@ int launch_calib_step(const purekv_plan& p, int rows_per_wavefront, int32_t iter
 double calib_step_flops(const purekv_plan& p, int32_t iters);
 
 size_t prefill_ws_bytes(const purekv_plan& p);
+// Arrival counters lead the prefill and decode workspaces: zero whenever no call is running on the workspace.
+size_t prefill_counter_region_bytes(const purekv_plan& p);
+int launch_prefill_ws_init(const purekv_plan& p, void* ws, hipStream_t st);
+int launch_decode_ws_init(const purekv_plan& p, void* ws, hipStream_t st);
 size_t topk_ws_bytes(const purekv_plan& p, int32_t n_layers, int32_t w);
 size_t decode_ws_bytes(const purekv_plan& p, int32_t cap);
 

@@ -12,8 +12,8 @@
 //   * the wavefronts are merged through LDS, the chunks through a workspace in global memory: each workgroup
 //     writes its (max, sum, unnormalised output), and the workgroup that arrives last at a per-(KV head, head block)
 //     counter merges all chunks in a fixed order and writes the result.  Nobody waits for anybody: a workgroup that is
-//     not the last simply ends.  The counters belong to the plan, are zero between calls (the last workgroup resets
-//     its counter) — calls that share a plan must not overlap on the GPU.
+//     not the last simply ends.  The counters lead the caller's workspace and are zero between calls (the last
+//     workgroup resets its counter): calls on different workspaces are independent of each other.
 // With k_new/v_new given, row n_cached - 1 of the cache is taken from them instead of the cache and the workgroup
 // that owns that key also stores it there (append and attention in one pass over the cache).
 #include "common.h"
@@ -340,11 +340,30 @@ __global__ __launch_bounds__(DEC_NT) void decode_kernel(const DecodeArgs a) {
 
 }  // namespace
 
-size_t decode_ws_bytes(const purekv_plan& p, int32_t cap) {
-  return (size_t)decode_splits(cap) * p.g.Hq * (p.g.d + 2) * sizeof(float);
+// Workspace: [arrival counters, padded to 256 bytes][partial outputs][their (max, sum)].
+static int decode_counter_count(const purekv_plan& p) { return p.g.Hkv * ((p.g.G + DEC_HB - 1) / DEC_HB); }
+static size_t decode_counter_bytes(const purekv_plan& p) {
+  return ((size_t)decode_counter_count(p) * sizeof(int32_t) + 255) / 256 * 256;
 }
 
-int decode_counter_count(const purekv_plan& p) { return p.g.Hkv * ((p.g.G + DEC_HB - 1) / DEC_HB); }
+size_t decode_ws_bytes(const purekv_plan& p, int32_t cap) {
+  return decode_counter_bytes(p) + (size_t)decode_splits(cap) * p.g.Hq * (p.g.d + 2) * sizeof(float);
+}
+
+namespace {
+__global__ void clear_decode_counters_kernel(int32_t* c, int n) {   // a kernel, not a memset: callers may be capturing
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) c[i] = 0;
+}
+}  // namespace
+
+int launch_decode_ws_init(const purekv_plan& p, void* ws, hipStream_t st) {
+  const int n = decode_counter_count(p);
+  hipLaunchKernelGGL(clear_decode_counters_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                     static_cast<int32_t*>(ws), n);
+  PUREKV_HIP_TRY(hipGetLastError());
+  return PUREKV_OK;
+}
 
 int launch_decode(const purekv_plan& p, const void* q_new, const void* k_new, const void* v_new, void* kc, void* vc,
                   int32_t n_cached, int32_t cap, void* out, void* ws, hipStream_t st) {
@@ -356,9 +375,9 @@ int launch_decode(const purekv_plan& p, const void* q_new, const void* k_new, co
   a.vc = static_cast<uint16_t*>(vc);
   a.out = static_cast<uint16_t*>(out);
   a.n_splits = decode_splits(n_cached);
-  a.ws_o = static_cast<float*>(ws);
+  a.counters = static_cast<int32_t*>(ws);
+  a.ws_o = reinterpret_cast<float*>(static_cast<char*>(ws) + decode_counter_bytes(p));
   a.ws_ml = a.ws_o + (size_t)decode_splits(cap) * p.g.Hq * p.g.d;
-  a.counters = p.d_counters;
   a.Hq = p.g.Hq;
   a.G = p.g.G;
   a.n_cached = n_cached;

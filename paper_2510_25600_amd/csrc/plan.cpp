@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cstddef>
+#include <cstdlib>
 #include <numeric>
 #include <utility>
 
@@ -177,7 +178,14 @@ void build_plan(purekv_plan& p, int n_cu) {
   // A tile of which every row block needs one 32-key half at most skips half of the score product; a unit
   // switch (write the finished rows, reset the state, first tile without a second product to overlap) costs
   // about one and a half steps.
-  constexpr double kHalfTileCost = 0.85, kUnitCost = 1.5;
+  // The slice that closes a split list (its workgroup runs it last, so it normally arrives last and combines the
+  // partial results of all slices) pays about two steps per slice for that (measured: a sweep of this constant on the 32-frame benchmark shape).
+#ifdef PUREKV_TUNING   // development builds: cost constants from the environment
+  const double kHalfTileCost = 0.85, kUnitCost = std::getenv("PUREKV_UNIT_COST") ? std::atof(std::getenv("PUREKV_UNIT_COST")) : 1.5,
+               kMergeCostPerSlice = std::getenv("PUREKV_MERGE_COST") ? std::atof(std::getenv("PUREKV_MERGE_COST")) : 2.0;
+#else
+  constexpr double kHalfTileCost = 0.85, kUnitCost = 1.5, kMergeCostPerSlice = 2.0;
+#endif
   std::vector<double> tile_cost(p.tiles.size());
   for (size_t i = 0; i < p.tiles.size(); ++i) {
     bool both = false;
@@ -196,7 +204,7 @@ void build_plan(purekv_plan& p, int n_cu) {
   for (int32_t qt = 0; qt < p.n_qtiles; ++qt) {
     const int32_t b = p.qtile_begin[qt], len = p.qtile_begin[qt + 1] - b;
     int32_t ns = 1;
-    if (2 * len > 3 * chunk) ns = (len + chunk - 1) / chunk;
+    if (2 * len > 3 * chunk) ns = std::min<int32_t>((len + chunk - 1) / chunk, kMaxSplits);
     if (ns == 1) {
       p.items.push_back({qt, b, len, 0, 1, -1});
       continue;
@@ -216,6 +224,8 @@ void build_plan(purekv_plan& p, int n_cu) {
   for (size_t it = 0; it < p.items.size(); ++it) {
     double c = kUnitCost;
     for (int32_t t = 0; t < p.items[it].n_tiles; ++t) c += tile_cost[p.items[it].list_begin + t];
+    if (p.items[it].n_splits > 1 && p.items[it].split == p.items[it].n_splits - 1)
+      c += kMergeCostPerSlice * p.items[it].n_splits;
     item_cost[it] = c;
   }
 
@@ -296,11 +306,21 @@ void build_plan(purekv_plan& p, int n_cu) {
       load[best_q] += item_cost[ui] - item_cost[vi];
     }
   }
-  // Longest units first within a queue (item indices ascend with decreasing length).
+  // Order within a queue: slices of split lists first, except the closing slice of a list, which goes last (when it
+  // ends, the other slices of its list, run first elsewhere, have normally long arrived: the workgroup that the
+  // cost model charged for combining them is then the one that does); whole lists in between, longest first (item
+  // indices ascend with decreasing length).
+  auto order_class = [&](int32_t it) {
+    const WorkItem& w = p.items[it];
+    return w.n_splits == 1 ? 1 : (w.split == w.n_splits - 1 ? 2 : 0);
+  };
   for (auto& qv : queues) {
     std::vector<std::pair<int32_t, int32_t>> pairs;
     for (size_t u = 0; u + 1 < qv.size(); u += 2) pairs.emplace_back(qv[u], qv[u + 1]);
-    std::stable_sort(pairs.begin(), pairs.end());
+    std::stable_sort(pairs.begin(), pairs.end(), [&](const std::pair<int32_t, int32_t>& x, const std::pair<int32_t, int32_t>& y) {
+      const int cx = order_class(x.first), cy = order_class(y.first);
+      return cx != cy ? cx < cy : x < y;
+    });
     for (size_t u = 0; u < pairs.size(); ++u) {
       qv[2 * u] = pairs[u].first;
       qv[2 * u + 1] = pairs[u].second;
@@ -323,6 +343,8 @@ void build_plan(purekv_plan& p, int n_cu) {
       un.head0 = head0;
       un.n_splits = w.n_splits;
       un.ws_row0 = w.slot >= 0 ? (w.slot * g.n_groups + grp) * (kWaves * kBlockRows) : -1;
+      un.ws_row_first = w.slot >= 0 ? ((w.slot - w.split) * g.n_groups + grp) * (kWaves * kBlockRows) : -1;
+      un.counter = w.slot >= 0 ? (w.slot - w.split) * g.n_groups + grp : -1;
       p.units.push_back(un);
       for (int32_t t = 0; t < w.n_tiles; ++t) {
         const TileRef& r = p.tiles[w.list_begin + t];

@@ -10,6 +10,7 @@ namespace purekv {
 constexpr int kWaves = PUREKV_WAVES;        // wavefronts per prefill workgroup
 constexpr int kBlockRows = PUREKV_BLOCK;    // query rows per wavefront
 constexpr int kBlockKeys = PUREKV_BLOCK;    // keys per mask block: a key tile (PUREKV_BK keys) holds two
+constexpr int kMaxSplits = 32;              // slices of one query tile's key list (the merge keeps 32 x kMaxSplits weights in LDS)
 
 // How the allowed pairs of one (row block, key block) pair are told apart from the others.
 enum BlockKind : uint32_t {
@@ -29,7 +30,8 @@ struct WorkItem {
   int32_t slot;        // partial-result slot when n_splits > 1, else -1
 };
 
-// A query tile whose list is split: the merge kernel combines slots [slot0, slot0 + n_splits).
+// A query tile whose list is split: the partial results in slots [slot0, slot0 + n_splits) are combined by the
+// workgroup whose slice arrives last (per head group), inside the prefill launch.
 struct MergeItem {
   int32_t qtile;
   int32_t slot0;
@@ -60,7 +62,11 @@ struct Unit {
   int32_t head0;       // first query head of the group (the group shares one KV head)
   int32_t n_splits;    // 1: the unit writes the output; > 1: it writes a partial result
   int32_t ws_row0;     // first row of the unit's partial result in the workspace (PUREKV_WAVES*32 rows), or -1
-  int32_t pad[4];
+  // slices only: first workspace row of slice 0 of the same (query tile, head group) -- slice s lies
+  // s * n_groups * PUREKV_WAVES * 32 rows further -- and the arrival counter of that (query tile, head group)
+  int32_t ws_row_first;
+  int32_t counter;
+  int32_t pad[2];
 };
 
 struct Geometry {
@@ -99,15 +105,12 @@ struct purekv_plan {
   purekv::Unit* d_units = nullptr;
   int32_t* d_queue_begin = nullptr;
   int32_t* d_queue_unit0 = nullptr;        // [n_queues + 1] first unit of each queue
-  purekv::MergeItem* d_merges = nullptr;
-  int32_t* d_counters = nullptr;           // arrival counters of the decode kernel, zero between calls
   float* d_static_scores = nullptr;        // the library's static score buffer on this plan's device (not owned)
   // Head subset (empty: every query head).  A plan over a subset lists units for the selected heads only and leaves
   // the other heads' rows of every output untouched; it keeps the stacked workgroup shape when the subset consists
   // of whole stacks, else it runs one head per workgroup (Gs = 1).
   std::vector<uint8_t> head_sel;           // [Hq], non-zero = selected
   int32_t n_heads_sel = 0;                 // selected heads (Hq when head_sel is empty)
-  uint8_t* d_head_sel = nullptr;
   int device = -1;
   int n_cu = 256;
 };

@@ -57,12 +57,12 @@ struct PrefillArgs {
   float* lse;
   float* ws_o;    // [n_slots, n_groups, WG_ROWS, D] normalised partial outputs
   float* ws_lse;  // [n_slots, n_groups, WG_ROWS, 2] log2-domain log-sum-exp of the partial: {merge weight, exact}
+  int32_t* counters;   // [n_slots, n_groups, PUREKV_WAVES] slices arrived per (split query tile, head group, wavefront);
+                       // zero on entry, zero again on exit
   const StreamEntry* stream;
   const Unit* units;
   const int32_t* queue_begin;   // [n_queues + 1] offsets into stream
   const int32_t* queue_unit0;   // [n_queues + 1] first unit of each queue (units are numbered in stream order)
-  const MergeItem* merges;
-  const uint8_t* head_sel;      // [Hq] or null: a plan over a head subset (one head per workgroup) merges only those
   int32_t N, Nv, P, Hq, Hkv;
   // byte strides of the (head, token) axes: Q, O per head and row, K/V per row (the head is in the stream entries)
   int64_t q_head_bytes, o_head_bytes;
@@ -74,6 +74,27 @@ struct PrefillArgs {
 
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) shortx4* LdsShortx4;
+
+// Device-scope ("agent") accesses for data that crosses workgroups inside one launch: buffer instructions with the
+// sc1 bit, which go through to memory instead of staying in (or being served from) the issuing XCD's L2.  The
+// compiler keeps track of their completion like of any other load or store.
+typedef __amdgpu_buffer_rsrc_t BufferRsrc;
+constexpr int kDeviceScope = 16;   // cache-policy operand of the buffer builtins: bit 4 = sc1
+__device__ __forceinline__ BufferRsrc make_rsrc(const void* base) {   // base must be wave-uniform
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+}
+__device__ __forceinline__ void store_device_16(BufferRsrc r, uint32_t off, floatx4 x) {
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, x), r, (int)off, 0, kDeviceScope);
+}
+__device__ __forceinline__ void store_device_8(BufferRsrc r, uint32_t off, floatx2 x) {
+  __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, x), r, (int)off, 0, kDeviceScope);
+}
+__device__ __forceinline__ floatx4 load_device_16(BufferRsrc r, uint32_t off) {
+  return __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, kDeviceScope));
+}
+__device__ __forceinline__ floatx2 load_device_8(BufferRsrc r, uint32_t off) {
+  return __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, kDeviceScope));
+}
 
 // V tile [BK][D] bf16 in LDS, row-major; the transpose read of a 16-lane group touches 4 consecutive rows x 32
 // bytes, two such groups run side by side: XOR-ing the 32-byte pair index with the row's low bits keeps them on
@@ -185,7 +206,8 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   auto next_buf = [](int b) { return b == NBUF - 1 ? 0 : b + 1; };
   // ---- per-unit state ----
   int hq = 0, row0 = 0, rowc = 0, a_i = 0, lo_i = 0, prev_j = -1, self_j = -1;
-  int u_nsplits = 1, u_ws_row0 = -1;
+  int u_nsplits = 1, u_ws_row0 = -1, u_unit = 0;
+  int unit_id = a.queue_unit0[blockIdx.x];   // unit of the tile on the score side (units are numbered in stream order)
   bf16x8 qf[KSTEPS];
   // m: reference maximum (log2 units); lacc: every element holds the sum of the bf16-rounded probabilities of
   // query n, accumulated by the matrix pipe: an output row is an exact convex combination of V rows (normalising
@@ -289,7 +311,9 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     const float lse2 = m_fin + __builtin_amdgcn_logf(l_tot);  // log2 domain; -inf when the slice saw no key
     const float lse2x = LSE ? m_fin + __builtin_amdgcn_logf(lx + other_half(lx)) : lse2;
     float* const Xf = reinterpret_cast<float*>(Xs);
-    float* wbase = a.ws_o + ((size_t)u_ws_row0 + wave * 32) * D;
+    // The partial result is read by another workgroup (possibly on another XCD, behind another L2) later in this
+    // launch: device-scope stores, which go through to memory.
+    const BufferRsrc wbuf = make_rsrc(a.ws_o + ((size_t)u_ws_row0 + wave * 32) * D);
 #pragma unroll
     for (int rnd = 0; rnd < D / 64; ++rnd) {
 #pragma unroll
@@ -313,22 +337,121 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
         for (int i = 0; i < 4; ++i) {
           int r, u;
           kunswz<128>((i0 + i) * 64 + ln, r, u);
-          *reinterpret_cast<floatx4*>(wbase + (size_t)r * D + 64 * rnd + 4 * u) = w[i];
+          store_device_16(wbuf, (uint32_t)(r * D + 64 * rnd + 4 * u) * 4u, w[i]);
         }
       }
     }
-    if (h == 0) {
-      const size_t prow = (size_t)u_ws_row0 + wave * 32 + n;
-      a.ws_lse[2 * prow] = lse2;
-      a.ws_lse[2 * prow + 1] = lse2x;
+    if (h == 0) store_device_8(make_rsrc(a.ws_lse + 2 * ((size_t)u_ws_row0 + wave * 32)), (uint32_t)n * 8u, floatx2{lse2, lse2x});
+  };
+  // Hand-off of a finished slice, wavefront by wavefront (wavefront w of every slice of a query tile holds the same
+  // 32 rows of the same head).  Arrival: once this wavefront's stores are acknowledged (device scope: they are in
+  // memory) it adds one to the counter of its (query tile, head group, wavefront index) -- nothing more inside the
+  // tile loop, whose registers are all taken.
+  auto slice_arrive = [&]() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    const u32x4 mu = units_c[2 * u_unit + 1];   // {first workspace row of slice 0, counter, -, -}
+    if (lane == 0)
+      (void)__hip_atomic_fetch_add(a.counters + (int)mu[1] * PUREKV_WAVES + wave, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  };
+  // Combination, at the end of the workgroup's queue (the pipeline's registers are free then): for every slice this
+  // wavefront ran, a counter that stands at n_splits means "all slices in memory, nobody has combined them yet";
+  // whoever moves it to n_splits + 1 (compare-and-swap: exactly one wavefront can) adds the partial results up in a
+  // fixed order (slice 0, 1, ...: reproducible bit for bit), writes the output rows and leaves the counter at zero
+  // for the next launch.  The wavefront whose slice arrived last always finds n_splits or a combination already
+  // claimed when it gets here, so every split tile is combined exactly once before the launch ends, and nobody ever
+  // waits for anybody.  The planner runs the closing slice of a list last in its queue and the other slices first
+  // in theirs: the workgroup it charged for the combination is then normally the one that does it.  Partial results
+  // and counters travel as device-scope accesses (they bypass the L2 of the issuing XCD), ordered by "stores
+  // acknowledged -> counter increment ... counter read -> loads".
+  auto merge_owed = [&](const u32x4 un, const u32x4 mu) {
+    const int ns = (int)un[2];
+    int32_t* const counter = a.counters + (int)mu[1] * PUREKV_WAVES + wave;
+    int claimed = 0;
+    if (lane == 0) {
+      int expected = ns;
+      claimed = __hip_atomic_compare_exchange_strong(counter, &expected, ns + 1, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
     }
+    if (!__builtin_amdgcn_readfirstlane(claimed)) return;
+    asm volatile("" ::: "memory");
+    const int hq = (int)un[1] + hl, row0 = (int)un[0] + rb * 32;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const uint32_t slice_rows = (uint32_t)a.n_groups * WG_ROWS;   // rows between consecutive slices' blocks
+    const float* const po = a.ws_o + ((size_t)mu[0] + wave * 32) * D;      // this wavefront's block in slice 0
+    const float* const pl = a.ws_lse + 2 * ((size_t)mu[0] + wave * 32);
+    float* const Wt = reinterpret_cast<float*>(Xs);   // [32 rows][ns]{merge weight, exact log-sum-exp}: <= 8 KB
+    // (row, slice) pairs over the lanes: one round trip fetches every slice's two log-sum-exp values of every row
+    for (int pb = 0; pb < 32 * ns; pb += 64) {
+      const int pr = min(pb + ln, 32 * ns - 1), r = pr & 31, sl = pr >> 5;
+      const floatx2 l2 = load_device_8(make_rsrc(pl), ((uint32_t)sl * slice_rows + (uint32_t)r) * 8u);
+      *reinterpret_cast<floatx2*>(Wt + 2 * (r * ns + sl)) = l2;
+    }
+    {  // lane (n, h): row n (both halves compute the same): maxima, weights normalised to sum 1, exact log-sum-exp
+      const int n = ln & 31;
+      float mx = -INFINITY, mxx = -INFINITY;
+      for (int sl = 0; sl < ns; ++sl) {
+        const floatx2 l2 = *reinterpret_cast<const floatx2*>(Wt + 2 * (n * ns + sl));
+        mx = fmaxf(mx, l2[0]);
+        mxx = fmaxf(mxx, l2[1]);
+      }
+      float wsum = 0.f, xsum = 0.f;
+      for (int sl = 0; sl < ns; ++sl) {
+        const floatx2 l2 = *reinterpret_cast<const floatx2*>(Wt + 2 * (n * ns + sl));
+        wsum += __builtin_amdgcn_exp2f(l2[0] - mx);
+        xsum += __builtin_amdgcn_exp2f(l2[1] - mxx);
+      }
+      const float inv = 1.f / wsum;
+      for (int sl = 0; sl < ns; ++sl) {
+        const float wgt = __builtin_amdgcn_exp2f(Wt[2 * (n * ns + sl)] - mx) * inv;
+        if ((ln >> 5) == 0) Wt[2 * (n * ns + sl)] = wgt;
+      }
+      if (LSE && (ln >> 5) == 0 && row0 + n < a.N)
+        a.lse[(size_t)hq * a.N + row0 + n] = (mxx + __builtin_amdgcn_logf(xsum)) * kLn2;
+    }
+    // Weighted sum, PB 16-byte pieces (4 columns of one row each) per lane at a time, the pieces of up to four
+    // slices in flight together (the pipeline's registers are free here): what this costs is round trips to memory.
+    constexpr int CH = D / 4, NI = 32 * CH / 64, PB = 8;   // pieces per row; pieces per lane; pieces per batch
+    static_assert(NI % PB == 0, "batches cover the block");
+    char* const otile = reinterpret_cast<char*>(a.out) + (int64_t)hq * a.o_head_bytes + (int64_t)row0 * a.o_row_bytes;
+    const int rows_left = a.N - row0;
+#pragma unroll 1
+    for (int i0 = 0; i0 < NI; i0 += PB) {
+      floatx4 acc[PB];
+#pragma unroll
+      for (int i = 0; i < PB; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+      for (int s0 = 0; s0 < ns; s0 += 4) {
+        floatx4 x[4][PB];
+#pragma unroll
+        for (int ss = 0; ss < 4; ++ss) {
+          const int sl = min(s0 + ss, ns - 1);   // slices past the end repeat the last one (weight 0 below)
+          const BufferRsrc pbuf = make_rsrc(po + (size_t)sl * slice_rows * D);
+#pragma unroll
+          for (int i = 0; i < PB; ++i) x[ss][i] = load_device_16(pbuf, (uint32_t)((i0 + i) * 64 + ln) * 16u);
+        }
+#pragma unroll
+        for (int ss = 0; ss < 4; ++ss)
+#pragma unroll
+          for (int i = 0; i < PB; ++i) {
+            const int r = ((i0 + i) * 64 + ln) / CH;
+            const float wgt = s0 + ss < ns ? Wt[2 * (r * ns + min(s0 + ss, ns - 1))] : 0.f;
+            acc[i] += x[ss][i] * wgt;
+          }
+      }
+#pragma unroll
+      for (int i = 0; i < PB; ++i) {
+        const int r = ((i0 + i) * 64 + ln) / CH, c4 = ((i0 + i) * 64 + ln) % CH;
+        u32x2 w2;
+        w2[0] = pack_bf16(acc[i][0], acc[i][1]);
+        w2[1] = pack_bf16(acc[i][2], acc[i][3]);
+        if (r < rows_left) *reinterpret_cast<u32x2*>(otile + (uint32_t)r * a.o_row_bytes + 8 * c4) = w2;
+      }
+    }
+    if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
   };
   // Finish of a unit that holds a whole key list: normalise, round, stage, store.
   auto finish_unit = [&]() {
-    if (u_nsplits != 1) {
-      finish_slice();
-      return;
-    }
     if (active) {
       int ln = lane;
       asm volatile("" : "+v"(ln));
@@ -439,11 +562,12 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   bf16x8 pf[4];       // probabilities of the tile whose second product comes next
   float alpha = 1.f;  // pending rescale of the accumulators (the reference maximum moved)
   bool resc = false;
-  int q_hq = 0, q_row0 = 0, q_nsplits = 1, q_ws_row0 = -1;   // unit of the tile on the score side
+  int q_hq = 0, q_row0 = 0, q_nsplits = 1, q_ws_row0 = -1, q_unit = 0;   // unit of the tile on the score side
   auto begin_qk_unit = [&](const u32x4 un) {
     q_hq = (int)un[1] + hl;
     q_nsplits = (int)un[2];
     q_ws_row0 = (int)un[3];
+    q_unit = unit_id;
     q_row0 = (int)un[0] + rb * 32;
     rowc = min(q_row0 + n, a.N - 1);
     const bool sparse_row = ST && a.pattern != 0u && rowc < a.Nv;
@@ -458,6 +582,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     row0 = q_row0;
     u_nsplits = q_nsplits;
     u_ws_row0 = q_ws_row0;
+    u_unit = q_unit;
     lx = 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) lacc[i] = 0.f;
@@ -508,7 +633,6 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 
   Step e_prev = fetch_step(t_begin), e_cur = fetch_step(t_begin + 1), e_n1 = fetch_step(t_begin + 2),
        e_n2 = fetch_step(t_begin + 3);
-  int unit_id = a.queue_unit0[blockIdx.x];
   u32x4 un_next = units_c[2 * unit_id];   // the first entry of a queue always starts a unit
   bool q_pref = false;
   // Query rows of the next unit: requested one tile before the current unit's last one when it has that many
@@ -635,10 +759,12 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
       });
       update_reference(mt, first);
       if (lastp) {
-        if (u_nsplits == 1)
+        if (u_nsplits == 1) {
           finish_unit();
-        else
+        } else {
           finish_slice();
+          slice_arrive();
+        }
         adopt_unit();
       }
     }
@@ -655,56 +781,20 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     iteration(j + 1, S[0], S[1]);
     if (j + 1 == t_end) break;
   }
-}
-
-// Combines the partial results of a query tile whose key list was cut into slices.  One workgroup
-// handles 16 rows of one (query tile, head group, wavefront): thread -> (row, 4 consecutive output elements).
-constexpr int MERGE_ROWS = 16;
-template <int D>
-__global__ __launch_bounds__(256) void merge_kernel(const PrefillArgs a) {
-  constexpr int C4 = D / 4;
-  const int parts = 2 * a.Gs * a.R;   // 16-row halves of the active wavefronts
-  const int part = blockIdx.x % parts, grp = (blockIdx.x / parts) % a.n_groups, mid = blockIdx.x / (parts * a.n_groups);
-  const int wave = part >> 1, rb = wave / a.Gs, hl = wave - rb * a.Gs;
-  const MergeItem mi = a.merges[mid];
-  const int r = wave * 32 + (part & 1) * MERGE_ROWS + threadIdx.x / 16;   // row within the workgroup's partial
-  const int hq = grp * a.Gs + hl;
-  const int row = mi.qtile * (a.R * 32) + rb * 32 + (part & 1) * MERGE_ROWS + threadIdx.x / 16;
-  if (row >= a.N) return;
-  if (a.head_sel != nullptr && a.head_sel[hq] == 0) return;   // no slice of this head exists
-  float mx = -INFINITY, mxx = -INFINITY;
-  for (int s = 0; s < mi.n_splits; ++s) {
-    const size_t prow = ((size_t)(mi.slot0 + s) * a.n_groups + grp) * WG_ROWS + r;
-    mx = fmaxf(mx, a.ws_lse[2 * prow]);
-    mxx = fmaxf(mxx, a.ws_lse[2 * prow + 1]);
-  }
-  float wsum = 0.f, xsum = 0.f;
-  floatx4 acc[C4 / 16];
-#pragma unroll
-  for (int c = 0; c < C4 / 16; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < mi.n_splits; ++s) {
-    const size_t prow = ((size_t)(mi.slot0 + s) * a.n_groups + grp) * WG_ROWS + r;
-    const float w = __builtin_amdgcn_exp2f(a.ws_lse[2 * prow] - mx);
-    wsum += w;
-    xsum += __builtin_amdgcn_exp2f(a.ws_lse[2 * prow + 1] - mxx);
-#pragma unroll
-    for (int c = 0; c < C4 / 16; ++c) {
-      const int c4 = (threadIdx.x % 16) + 16 * c;
-      acc[c] += *reinterpret_cast<const floatx4*>(a.ws_o + prow * D + 4 * c4) * w;
+  // split lists whose slices this workgroup ran: combine those that are complete and still uncombined
+  if (active) {
+    const int u_end = a.queue_unit0[blockIdx.x + 1];
+    for (int u = a.queue_unit0[blockIdx.x]; u < u_end; ++u) {
+      const u32x4 un = units_c[2 * u];
+      if ((int)un[2] > 1) merge_owed(un, units_c[2 * u + 1]);
     }
   }
-  const float inv = 1.f / wsum;
-#pragma unroll
-  for (int c = 0; c < C4 / 16; ++c) {
-    const int c4 = (threadIdx.x % 16) + 16 * c;
-    u32x2 w2;
-    w2[0] = pack_bf16(acc[c][0] * inv, acc[c][1] * inv);
-    w2[1] = pack_bf16(acc[c][2] * inv, acc[c][3] * inv);
-    *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(a.out) + (int64_t)hq * a.o_head_bytes +
-                              (int64_t)row * a.o_row_bytes + 8 * c4) = w2;
-  }
-  if (a.lse != nullptr && (threadIdx.x % 16) == 0)
-    a.lse[(size_t)hq * a.N + row] = (mxx + __builtin_amdgcn_logf(xsum)) * kLn2;
+}
+
+// Clears the arrival counters of a prefill workspace (a kernel, not a memset: callers may be capturing a graph).
+__global__ void clear_counters_kernel(int32_t* c, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) c[i] = 0;
 }
 
 template <int D, bool ST, bool LSE>
@@ -725,8 +815,24 @@ hipError_t launch_variant(const PrefillArgs& a, dim3 grid, hipStream_t st) {
 
 }  // namespace
 
+// Workspace of a plan with split lists: [arrival counters, padded to 256 bytes][partial outputs][their log-sum-exps].
+static size_t prefill_counter_count(const purekv_plan& p) { return (size_t)p.n_slots * p.g.n_groups * PUREKV_WAVES; }
+static size_t prefill_counter_bytes(const purekv_plan& p) {
+  return (prefill_counter_count(p) * sizeof(int32_t) + 255) / 256 * 256;
+}
+size_t prefill_counter_region_bytes(const purekv_plan& p) { return prefill_counter_bytes(p); }
+
 size_t prefill_ws_bytes(const purekv_plan& p) {
-  return (size_t)p.n_slots * p.g.n_groups * WG_ROWS * (p.g.d + 2) * sizeof(float);
+  if (p.n_slots == 0) return 0;
+  return prefill_counter_bytes(p) + (size_t)p.n_slots * p.g.n_groups * WG_ROWS * (p.g.d + 2) * sizeof(float);
+}
+
+int launch_prefill_ws_init(const purekv_plan& p, void* ws, hipStream_t st) {
+  const int n = (int)prefill_counter_count(p);
+  if (n == 0) return PUREKV_OK;
+  hipLaunchKernelGGL(clear_counters_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, static_cast<int32_t*>(ws), n);
+  PUREKV_HIP_TRY(hipGetLastError());
+  return PUREKV_OK;
 }
 
 int launch_prefill(const purekv_plan& p, const void* q, const void* k, const void* v, void* out, float* lse,
@@ -737,14 +843,13 @@ int launch_prefill(const purekv_plan& p, const void* q, const void* k, const voi
   a.v = static_cast<const uint16_t*>(v);
   a.out = static_cast<uint16_t*>(out);
   a.lse = lse;
-  a.ws_o = static_cast<float*>(ws);
+  a.counters = static_cast<int32_t*>(ws);
+  a.ws_o = ws ? reinterpret_cast<float*>(static_cast<char*>(ws) + prefill_counter_bytes(p)) : nullptr;
   a.ws_lse = a.ws_o ? a.ws_o + (size_t)p.n_slots * p.g.n_groups * WG_ROWS * p.g.d : nullptr;
   a.stream = p.d_stream;
   a.units = p.d_units;
   a.queue_begin = p.d_queue_begin;
   a.queue_unit0 = p.d_queue_unit0;
-  a.merges = p.d_merges;
-  a.head_sel = p.d_head_sel;
   a.N = p.g.N;
   a.Nv = p.g.Nv;
   a.P = p.g.P;
@@ -760,21 +865,18 @@ int launch_prefill(const purekv_plan& p, const void* q, const void* k, const voi
   a.n_groups = p.g.n_groups;
   a.pattern = p.g.pattern;
   a.scale_log2 = p.g.scale * kLog2e;
-  const dim3 grid((unsigned)p.n_queues), block(256);
-  const dim3 mgrid((unsigned)(p.merges.size() * p.g.n_groups * 2 * p.g.Gs * p.g.R));
+  const dim3 grid((unsigned)p.n_queues);
   const bool sparse = p.g.pattern != PUREKV_PATTERN_DENSE;
   if (p.g.d == 128) {
     if (sparse)
       PUREKV_HIP_TRY((launch_variant<128, true>(a, grid, st)));
     else
       PUREKV_HIP_TRY((launch_variant<128, false>(a, grid, st)));
-    if (!p.merges.empty()) hipLaunchKernelGGL(merge_kernel<128>, mgrid, block, 0, st, a);
   } else {
     if (sparse)
       PUREKV_HIP_TRY((launch_variant<64, true>(a, grid, st)));
     else
       PUREKV_HIP_TRY((launch_variant<64, false>(a, grid, st)));
-    if (!p.merges.empty()) hipLaunchKernelGGL(merge_kernel<64>, mgrid, block, 0, st, a);
   }
   PUREKV_HIP_TRY(hipGetLastError());
   return PUREKV_OK;

@@ -349,14 +349,18 @@ def test_gpu_argument_errors():
     assert lib.purekv_stack_layer(dense_plan.handle, plan.handle, ctypes.byref(good), 4, *args) == pk.EINVAL
     assert lib.purekv_stack_layer(dense_plan.handle, plan.handle, ctypes.byref(good), 0, P(q), P(k), P(v), P(q), None,
                                   P(c), None, 0, None) == pk.EINVAL   # a layer that emits C needs the LSE scratch
-    assert lib.purekv_stack_select_compact(dense_plan.handle, ctypes.byref(good), P(c), P(k), P(v), 0, P(idx), P(k), P(v),
-                                           57, None, 0, None) == pk.EINVAL   # four layers need a layer stride
+    assert lib.purekv_stack_select_compact(dense_plan.handle, plan.handle, ctypes.byref(good), P(c), P(k), P(v), 0, P(idx),
+                                           P(k), P(v), 57, None, 0, None) == pk.EINVAL   # four layers need a layer stride
+    assert lib.purekv_workspace_init(plan.handle, 9, None, 0, 0, 0, 0, None) == pk.EINVAL
+    assert lib.purekv_workspace_init(plan.handle, pk.OP_DECODE, None, 0, 0, 0, 57, None) == pk.EWORKSPACE
+    assert lib.purekv_workspace_init(plan.handle, pk.OP_COMPACT, None, 0, 0, 0, 0, None) == pk.OK   # needs none
     assert lib.purekv_calib_mfma(plan.handle, 3, 0, 10, P(c), P(c), None) == pk.EINVAL
     assert lib.purekv_calib_mfma(plan.handle, 0, 0, 0, P(c), P(c), None) == pk.EINVAL
     assert lib.purekv_calib_mfma(plan.handle, 0, 0, 10, None, P(c), None) == pk.EINVAL
     long = pk.Plan.for_workload(SMALL["longtext_2f"], 3)
     assert long.workspace_bytes(pk.OP_PREFILL) > 0
     assert lib.purekv_st_spattn_prefill(long.handle, P(q), P(k), P(v), P(q), None, None, 0, None) == pk.EWORKSPACE
+    assert lib.purekv_workspace_init(long.handle, pk.OP_PREFILL, None, 0, 0, 0, 0, None) == pk.EWORKSPACE
     torch.cuda.synchronize()
 
 
@@ -573,3 +577,33 @@ def test_decode_random_shapes_sweep():
             assert np.array_equal(bits_of(kc), kc_h) and np.array_equal(bits_of(vc), vc_h)
             ref = orc.decode_attention(F64(q), F64(kc_h)[:, :n0 + t + 1], F64(vc_h)[:, :n0 + t + 1])
             check_attention(f64_of(out), ref, f"decode sweep {case} step {t}")
+
+
+def test_two_streams_share_one_plan():
+    """A plan holds no mutable device state: decode calls and prefill calls (with split lists) on two streams, each
+    with a workspace of its own, may overlap on the GPU.  Both streams' results against the oracle, several rounds."""
+    wl = SMALL["heads7_3f"]          # text rows split into slices: the prefill hands partial results over in its workspace
+    n, hq, hkv, d = wl.n_tokens, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+    plan = _plan(wl, 3)
+    assert plan.counts()["n_split_qtiles"] > 0
+    data = [generate(wl, seed=80 + i, decode_steps=1) for i in range(2)]
+    n_c = 1100                       # five chunks of cached keys: the decode kernel merges through its workspace
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    dev = [[to_dev(x) for x in (dt.q, dt.k, dt.v, dt.q_new[0])] for dt in data]
+    torch.cuda.synchronize()
+    outs, decs = [[], []], [[], []]
+    for rnd in range(6):
+        for i, s in enumerate(streams):
+            with torch.cuda.stream(s):
+                q, k, v, qn = dev[i]
+                outs[i].append(pk.purekv_st_spattn_prefill(plan, q, k, v))
+                decs[i].append(pk.purekv_decode_attn(plan, qn, k[:, :n_c].contiguous(), v[:, :n_c].contiguous(), n_c))
+    torch.cuda.synchronize()
+    for i, dt in enumerate(data):
+        ref, _ = orc.masked_attention(F64(dt.q), F64(dt.k), F64(dt.v), wl.n_frames, wl.patches, wl.n_text, 3)
+        dref = orc.decode_attention(F64(dt.q_new[0]), F64(dt.k)[:, :n_c], F64(dt.v)[:, :n_c])
+        for rnd in range(6):
+            check_attention(f64_of(outs[i][rnd]), ref, f"stream {i} round {rnd} prefill")
+            check_attention(f64_of(decs[i][rnd]), dref, f"stream {i} round {rnd} decode")
+            assert np.array_equal(bits_of(outs[i][rnd]), bits_of(outs[i][0]))   # and reproducible bit for bit
+            assert np.array_equal(bits_of(decs[i][rnd]), bits_of(decs[i][0]))

@@ -99,7 +99,9 @@ def test_compute_calls_validate_before_touching_the_gpu():
     assert lib.purekv_calib_mfma_flops(h, 10) == 2.0 * 32 * 32 * 16 * 16 * 10 * 8 * plan.counts()["n_workgroups"]
     stack = pk.Stack(4, 1, 2, 8, 4)
     assert lib.purekv_stack_layer(h, h, ctypes.byref(stack), 0, one, one, one, one, one, one, one, 1 << 20, None) == pk.EINVAL
-    assert lib.purekv_stack_select_compact(h, ctypes.byref(stack), one, one, one, 0, one, one, one, 16, one, 1 << 20,
+    assert lib.purekv_workspace_init(h, pk.OP_PREFILL, one, 1 << 20, 0, 0, 0, None) == pk.EINVAL
+    assert lib.purekv_stack_workspace_init(h, h, ctypes.byref(stack), one, 1 << 20, None) == pk.EINVAL
+    assert lib.purekv_stack_select_compact(h, h, ctypes.byref(stack), one, one, one, 0, one, one, one, 16, one, 1 << 20,
                                            None) == pk.EINVAL
     assert lib.purekv_stack_workspace_bytes(h, h, ctypes.byref(stack)) == 0
     assert lib.purekv_stack_workspace_bytes(None, None, None) == 0
@@ -210,6 +212,15 @@ def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern, n_wg=256):
     assert 1 <= c["n_workgroups"] <= n_wg
     units = [u for q in range(c["n_workgroups"]) for u in plan.queue(q)]
     assert sorted(units) == [(i, h0) for i in range(c["n_items"]) for h0 in range(0, hq, gs)]
+    # order inside a queue: slices of split lists first, whole lists next, the closing slice of a list last (the
+    # workgroup that runs it is the one the cost model charges for combining the list's partial results)
+    def order_class(i):
+        _, _, _, sp, ns, _ = items[i]
+        return 1 if ns == 1 else (2 if sp == ns - 1 else 0)
+    for q in range(c["n_workgroups"]):
+        classes = [order_class(i) for i, _ in plan.queue(q)]
+        assert classes == sorted(classes), (q, classes)
+    assert all(it[4] <= 32 for it in items)   # slices per list: what the combining wavefront's LDS table holds
     loads = [sum(items[i][2] for i, _ in plan.queue(q)) for q in range(c["n_workgroups"])]
     if len(units) >= 4 * c["n_workgroups"]:
         assert max(loads) <= 1.5 * (sum(loads) / len(loads)) + max(it[2] for it in items)
