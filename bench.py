@@ -64,6 +64,125 @@ def profiled_traffic_bytes():
         return None
 
 
+PMC_PASSES = [
+    "SQ_WAVES SQ_INSTS_VALU SQ_INSTS_SALU SQ_INSTS_LDS SQ_INSTS_SMEM SQ_INSTS_MFMA SQ_INSTS_BRANCH SQ_INSTS_VMEM",
+    "SQ_WAVE_CYCLES SQ_BUSY_CYCLES SQ_WAIT_INST_ANY SQ_WAIT_INST_LDS SQ_ACTIVE_INST_VALU SQ_ACTIVE_INST_LDS "
+    "SQ_VALU_MFMA_BUSY_CYCLES SQ_LDS_BANK_CONFLICT",
+    "SQ_ACTIVE_INST_ANY SQ_ACTIVE_INST_SCA SQ_WAIT_ANY SQ_LDS_IDX_ACTIVE SQ_LDS_ADDR_CONFLICT SQ_INSTS_VALU_MFMA_MOPS_BF16 "
+    "SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_TRANS_F32",
+]
+
+
+def profile_commands(stage: str, steps: int):
+    """The rocprofv3 commands whose output `--profile-summary` reads (run from /tmp with TMPDIR=/tmp; $R = repository
+    root, $D = the directory given to --profile-summary)."""
+    if stage == "whole_path":   # the benchmark command itself (as the driver runs it), kernel statistics only
+        return [f"rocprofv3 --kernel-trace --stats --output-format csv -d $D/stats -o s -- python3 $R/bench.py --steps {steps} "
+                "--warmup 5 --no-cpu-baseline"]
+    run = f"python3 $R/bench.py --only-stage {stage}"
+    cmds = [f"rocprofv3 --kernel-trace --stats --output-format csv -d $D/stats -o s -- {run} --steps {steps}",
+            f"rocprofv3 --pmc FETCH_SIZE --output-format csv -d $D/fetch -o p -- {run} --steps 5",
+            f"rocprofv3 --pmc WRITE_SIZE --output-format csv -d $D/write -o p -- {run} --steps 5"]
+    cmds += [f"rocprofv3 --pmc {c} --output-format csv -d $D/p{i + 1} -o p -- {run} --steps 3" for i, c in enumerate(PMC_PASSES)]
+    return cmds
+
+
+def write_profile_summary(src_dir: str, stage: str, name: str, title: str, steps: int) -> str:
+    """Turns the CSV files rocprofv3 wrote under `src_dir` (see profile_commands) into profiles/<name>.md: kernel
+    durations per (kernel, grid), HBM-side byte counters, and the SQ counter passes per kernel.  Text in, text out."""
+    import collections
+    import csv
+    import glob
+
+    def short(k):
+        k = k.replace("purekv::(anonymous namespace)::", "").replace("void ", "")
+        return k.split("(")[0] if "rocclr" not in k else k
+
+    def find(sub, pattern):
+        hits = sorted(glob.glob(os.path.join(src_dir, sub, "**", pattern), recursive=True))
+        return hits[0] if hits else None
+
+    out = [f"# {title}\n", "Commands (run from /tmp with TMPDIR=/tmp on the MI355X box; `$R` = repository root, `$D` = output "
+           "directory), then `python3 $R/bench.py --profile-summary $D --only-stage " + stage + " --profile-name " + name + "`:\n", "```"]
+    out += profile_commands(stage, steps) + ["```\n"]
+    if stage == "whole_path":
+        out.append(f"The benchmark command as the driver runs it ({steps} timed steps after the clock ramp and 5 warm-up steps; the "
+                   "graph replays, the back-to-back timings, the batched launches and the calibration loops of the same "
+                   "command are in the table too).  The profiler serialises dispatches, so gaps between kernels differ from "
+                   "an unprofiled run; kernel durations do not.\n")
+    else:
+        out.append(f"`--only-stage` runs one full warm-up step of the whole path (every kernel once, at its per-layer size) and "
+                   f"then the named stage {steps} times (fewer in the counter runs).  Rows are per (kernel, grid size), so the "
+                   "warm-up dispatches and the stage's own dispatches stay apart.\n")
+    trace = find("stats", "*kernel_trace.csv")
+    dur = collections.defaultdict(list)
+    if trace:
+        for r in csv.DictReader(open(trace)):
+            g = int(r["Grid_Size_X"]) * int(r["Grid_Size_Y"]) * int(r["Grid_Size_Z"])
+            dur[(short(r["Kernel_Name"]), g)].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+
+    def counters(sub):
+        d = collections.defaultdict(lambda: collections.defaultdict(list))
+        path = find(sub, "*counter_collection.csv")
+        if path:
+            for r in csv.DictReader(open(path)):
+                d[(short(r["Kernel_Name"]), int(r["Grid_Size"]))][r["Counter_Name"]].append(float(r["Counter_Value"]))
+        return d
+
+    fetch, write = counters("fetch"), counters("write")
+    out.append("## Kernel durations (kernel trace) and HBM-side byte counters (KiB per dispatch)\n")
+    out.append("| kernel | grid (work-items) | dispatches | avg us | min us | max us | FETCH_SIZE KiB | WRITE_SIZE KiB |")
+    out.append("|---|---|---|---|---|---|---|---|")
+    for (k, g), v in sorted(dur.items(), key=lambda kv: -sum(kv[1])):
+        if "at::native" in k or ("rocclr" in k and stage != "copy_calib"):
+            continue
+        fv, wv = fetch.get((k, g), {}).get("FETCH_SIZE"), write.get((k, g), {}).get("WRITE_SIZE")
+        fs = f"{sum(fv) / len(fv):.1f}" if fv else "-"
+        ws = f"{sum(wv) / len(wv):.1f}" if wv else "-"
+        out.append(f"| `{k[:64]}` | {g} | {len(v)} | {sum(v) / len(v):.2f} | {min(v):.2f} | {max(v):.2f} | {fs} | {ws} |")
+    stats = find("stats", "*kernel_stats.csv")
+    if stats:
+        out.append("\n## rocprofv3 --stats summary (all dispatches of a kernel pooled)\n")
+        out.append("| kernel | calls | avg us | min us | max us | % of GPU time |")
+        out.append("|---|---|---|---|---|---|")
+        for r in csv.DictReader(open(stats)):
+            nm = short(r["Name"])
+            if "at::native" in nm:
+                continue
+            out.append(f"| `{nm[:64]}` | {r['Calls']} | {float(r['AverageNs']) / 1e3:.2f} | {float(r['MinNs']) / 1e3:.2f} | "
+                       f"{float(r['MaxNs']) / 1e3:.2f} | {float(r['Percentage']):.2f} |")
+    sq = collections.defaultdict(dict)
+    for i in range(len(PMC_PASSES)):
+        for key, cs in counters(f"p{i + 1}").items():
+            for cname, vals in cs.items():
+                sq[key][cname] = sum(vals) / len(vals)
+    if sq:
+        out.append("\n## SQ counters per dispatch (sums over the whole chip; three passes of 8 counters)\n")
+        biggest = sorted(sq, key=lambda key: -sq[key].get("SQ_WAVE_CYCLES", sq[key].get("SQ_INSTS_VALU", 0)))[:3]
+        names = sorted({c for key in biggest for c in sq[key]})
+        out.append("| counter | " + " | ".join(f"`{k[:40]}` grid {g}" for k, g in biggest) + " |")
+        out.append("|---|" + "---|" * len(biggest))
+        for c in names:
+            out.append(f"| {c} | " + " | ".join(f"{sq[key].get(c, float('nan')):.0f}" for key in biggest) + " |")
+        out.append("\nDerived, per kernel (plain ratios of the rows above):\n")
+        for key in biggest:
+            c = sq[key]
+            def ratio(a, b):
+                return f"{c[a] / c[b]:.3f}" if a in c and c.get(b) else "n/a"
+            out.append(f"* `{key[0][:48]}`: instructions per wavefront: vector {ratio('SQ_INSTS_VALU', 'SQ_WAVES')} "
+                       f"(of them MFMA {ratio('SQ_INSTS_MFMA', 'SQ_WAVES')}, transcendental {ratio('SQ_INSTS_VALU_TRANS_F32', 'SQ_WAVES')}), "
+                       f"scalar {ratio('SQ_INSTS_SALU', 'SQ_WAVES')}, LDS {ratio('SQ_INSTS_LDS', 'SQ_WAVES')}, vector memory "
+                       f"{ratio('SQ_INSTS_VMEM', 'SQ_WAVES')}, branch {ratio('SQ_INSTS_BRANCH', 'SQ_WAVES')}; of a wavefront's "
+                       f"cycles: an instruction active {ratio('SQ_ACTIVE_INST_ANY', 'SQ_WAVE_CYCLES')}, waiting for an issue slot "
+                       f"{ratio('SQ_WAIT_INST_ANY', 'SQ_WAVE_CYCLES')}, waiting at a counter or barrier {ratio('SQ_WAIT_ANY', 'SQ_WAVE_CYCLES')}; "
+                       f"MFMA-busy cycles / wavefront cycles {ratio('SQ_VALU_MFMA_BUSY_CYCLES', 'SQ_WAVE_CYCLES')}; "
+                       f"LDS bank-conflict cycles / LDS active cycles {ratio('SQ_LDS_BANK_CONFLICT', 'SQ_LDS_IDX_ACTIVE')}")
+    os.makedirs(os.path.join(ROOT, "profiles"), exist_ok=True)
+    path = os.path.join(ROOT, "profiles", name + ".md")
+    open(path, "w").write("\n".join(out) + "\n")
+    return path
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,9 +203,28 @@ def main() -> int:
     ap.add_argument("--stack-layers", type=int, default=0, help="layers of the --stack run (default: the workload's)")
     ap.add_argument("--stack-dense", type=int, default=0, help="dense low layers of the --stack run (default: the "
                     "workload's, else 1); the last of them estimates the importance")
-    ap.add_argument("--only-stage", default=None, choices=STAGES + ["copy_calib", "topk_batched", "compact_batched", "mfma_calib"],
+    ap.add_argument("--only-stage", default=None,
+                    choices=STAGES + ["copy_calib", "topk_batched", "compact_batched", "mfma_calib", "whole_path"],
                     help="profiling aid: after one full warm-up step run only this stage --steps times and exit")
+    ap.add_argument("--profile-summary", default=None, metavar="DIR",
+                    help="no GPU work: turn the rocprofv3 CSV output under DIR (produced by the commands this prints with "
+                         "--profile-commands for the stage given with --only-stage) into profiles/<--profile-name>.md")
+    ap.add_argument("--profile-name", default=None)
+    ap.add_argument("--profile-title", default=None)
+    ap.add_argument("--profile-commands", action="store_true", help="print the rocprofv3 commands of a stage's profile and exit")
     args = ap.parse_args()
+    if args.profile_commands or args.profile_summary:
+        stage = args.only_stage or "st_prefill"
+        steps = args.steps if args.steps != 200 else 30
+        if stage == "whole_path" and args.steps == 200:
+            steps = 20
+        if args.profile_commands:
+            print("\n".join(profile_commands(stage, steps)))
+            return 0
+        name = args.profile_name or f"{stage}_{args.workload}"
+        title = args.profile_title or f"{stage}, workload {args.workload}"
+        print("wrote", write_profile_summary(args.profile_summary, stage, name, title, steps))
+        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
         return 2
@@ -424,18 +562,40 @@ def main() -> int:
     }
 
     if not args.no_cpu_baseline:
+        # The oracle as it stands, on the host cores, for the same step the GPU line reports: the metric's kernel
+        # (ST-SpAttn attention, every head and row) gives `value`; the other stages' seconds stand beside it.
         from oracle import purekv_oracle as orc
         heads = list(range(0, hq, max(1, hq // args.cpu_heads)))[:args.cpu_heads]
         qf, kf, vf = (orc.bf16_bits_to_f64(x) for x in (high.q, high.k, high.v))
-        t0 = time.perf_counter()
-        orc.masked_attention(qf, kf, vf, wl.n_frames, wl.patches, wl.n_text, 3, heads=heads)
-        t_cpu = time.perf_counter() - t0
+        secs = {}
+
+        def timed(name, fn):
+            t0 = time.perf_counter()
+            r = fn()
+            secs[name] = round(time.perf_counter() - t0, 3)
+            return r
+
+        timed("st_prefill", lambda: orc.masked_attention(qf, kf, vf, wl.n_frames, wl.patches, wl.n_text, 3, heads=heads))
+        t_cpu = secs["st_prefill"]
+        if len(heads) == hq:   # the rest of the step (skipped when only a sample of the heads was asked for)
+            ql, kl, vl = (orc.bf16_bits_to_f64(x) for x in (low.q, low.k, low.v))
+            timed("dense_prefill", lambda: orc.masked_attention(ql, kl, vl, wl.n_frames, wl.patches, wl.n_text, 0))
+            c_ref = timed("importance", lambda: orc.window_column_sums(ql, kl, wl.n_frames, wl.patches, wl.n_text, 0, w))
+            idx_l = timed("topk_low", lambda: orc.topk_select(orc.vnorm_scores(c_ref, vl), h, n, w))
+            timed("compact_low", lambda: orc.compact(low.k, low.v, idx_l))
+            idx_h = timed("topk_high", lambda: orc.topk_select(orc.vnorm_scores(c_ref, vf), h, n, w))
+            kr, vr = timed("compact_high", lambda: orc.compact(high.k, high.v, idx_h))
+            kcat = np.concatenate([orc.bf16_bits_to_f64(kr), orc.bf16_bits_to_f64(high.k_new[0])[:, None]], 1)
+            vcat = np.concatenate([orc.bf16_bits_to_f64(vr), orc.bf16_bits_to_f64(high.v_new[0])[:, None]], 1)
+            timed("append_decode", lambda: orc.decode_attention(orc.bf16_bits_to_f64(high.q_new[0]), kcat, vcat))
         sample_flops = mask_flops * len(heads) / hq
         result["cpu_baseline"] = {
             "value": round(sample_flops / t_cpu / 1e12, 5), "unit": "TFLOP/s", "cores": blas_threads(),
             "kind": "oracle",
             "sample": f"ST-SpAttn attention of {len(heads)} of {hq} query heads, all {n} rows, NumPy fp64 dense "
                       f"scores under the boolean mask; flops counted on allowed pairs only; {t_cpu:.1f} s",
+            "oracle_seconds_per_stage": secs,
+            "oracle_seconds_whole_step": round(sum(secs.values()), 2) if len(secs) > 1 else None,
         }
     print(json.dumps(result))
     return 0

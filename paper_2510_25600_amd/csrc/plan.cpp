@@ -243,7 +243,21 @@ void build_plan(purekv_plan& p, int n_cu) {
   };
   std::vector<std::vector<int32_t>> queues(p.n_queues);  // flat (item, group) pairs
   std::vector<double> load(p.n_queues, 0.0);
-  for (size_t it = 0; it < p.items.size(); ++it) {
+#ifdef PUREKV_TUNING
+  const bool row_order = std::getenv("PUREKV_DEAL") && std::getenv("PUREKV_DEAL")[0] == 'r';
+#else
+  constexpr bool row_order = false;
+#endif
+  std::vector<size_t> deal_order(p.items.size());
+  std::iota(deal_order.begin(), deal_order.end(), size_t(0));
+  if (row_order)   // slices first (longest first), then whole lists by query tile
+    std::stable_sort(deal_order.begin(), deal_order.end(), [&](size_t x, size_t y) {
+      const bool sx = p.items[x].n_splits > 1, sy = p.items[y].n_splits > 1;
+      if (sx != sy) return sx;
+      if (sx) return x < y;
+      return p.items[x].qtile < p.items[y].qtile;
+    });
+  for (size_t it : deal_order) {
     for (int32_t grp = 0; grp < g.n_groups; ++grp) {
       if (!group_selected(grp)) continue;
       const int32_t kvh = grp * g.Gs / g.G;
@@ -319,7 +333,10 @@ void build_plan(purekv_plan& p, int n_cu) {
     for (size_t u = 0; u + 1 < qv.size(); u += 2) pairs.emplace_back(qv[u], qv[u + 1]);
     std::stable_sort(pairs.begin(), pairs.end(), [&](const std::pair<int32_t, int32_t>& x, const std::pair<int32_t, int32_t>& y) {
       const int cx = order_class(x.first), cy = order_class(y.first);
-      return cx != cy ? cx < cy : x < y;
+      if (cx != cy) return cx < cy;
+      if (row_order && cx == 1 && p.items[x.first].qtile != p.items[y.first].qtile)
+        return p.items[x.first].qtile < p.items[y.first].qtile;
+      return x < y;
     });
     for (size_t u = 0; u < pairs.size(); ++u) {
       qv[2 * u] = pairs[u].first;
