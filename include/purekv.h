@@ -179,6 +179,17 @@ PUREKV_API int purekv_st_spattn_prefill(const purekv_plan_t* plan, const void* q
                              void* out, float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The same prefill that also emits, at no extra pass over V, what the V-norm weighting of Eq. 3 / Eq. 4 needs of this
+ * layer's values: vnorm2[kv, j] = sum_c v[kv, j, c]^2 for every key (fp32 [Hkv, N], packed), computed from the V tiles
+ * while they sit in on-chip memory for the second product (every key tile has one owner step in the plan's
+ * schedule).  purekv_topk_select_vnorm then weighs C with these norms instead of streaming V again.  With a plan
+ * over a head subset, rows of KV heads none of whose query heads belong to the plan are left untouched.
+ */
+PUREKV_API int purekv_st_spattn_prefill_vnorm(const purekv_plan_t* plan, const void* q, const void* k, const void* v,
+                                              void* out, float* lse, float* vnorm2, void* ws, size_t ws_bytes,
+                                              void* stream);
+
+/*
  * Recent-window column sums (Eq. 2), summed over the query heads of each KV group:
  *   c_out[kv, j] = sum_{hq in group kv} sum_{i = N-w}^{N-1} exp(q_i . k_j * scale - lse[hq, i]),  0 <= j < N-w,
  * over the pairs (i, j) the plan's pattern allows.  `lse` is the one written by the prefill call of the
@@ -202,6 +213,15 @@ PUREKV_API int purekv_lowlayer_importance(const purekv_plan_t* plan, const void*
 PUREKV_API int purekv_topk_select(const purekv_plan_t* plan, const float* c, const void* v, int64_t v_layer_stride,
                        int32_t n_layers, int32_t w, int32_t h, int32_t* idx_out, float* s_out,
                        void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * purekv_topk_select with the squared norms purekv_st_spattn_prefill_vnorm emitted instead of V (Eq. 3 / Eq. 4):
+ *   s[l, kv, j] = c[kv, j] * sqrt(vnorm2[l, kv, j]),  vnorm2: fp32, layer l at + l * vn_layer_stride elements, each
+ *   [Hkv, N]; everything else as for purekv_topk_select (the workspace holds the scores when s_out is NULL).
+ */
+PUREKV_API int purekv_topk_select_vnorm(const purekv_plan_t* plan, const float* c, const float* vnorm2,
+                                        int64_t vn_layer_stride, int32_t n_layers, int32_t w, int32_t h,
+                                        int32_t* idx_out, float* s_out, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * purekv_topk_select for callers that cannot allocate or hold a workspace (code under HIP graph capture, tight

@@ -63,6 +63,8 @@ def _load() -> ctypes.CDLL:
         "purekv_workspace_init": (c_int, [P, c_int, P, c_size_t, c_int32, c_int32, c_int32, P]),
         "purekv_stack_workspace_init": (c_int, [P, P, P, P, c_size_t, P]),
         "purekv_st_spattn_prefill": (c_int, [P, P, P, P, P, P, P, c_size_t, P]),
+        "purekv_st_spattn_prefill_vnorm": (c_int, [P, P, P, P, P, P, P, P, c_size_t, P]),
+        "purekv_topk_select_vnorm": (c_int, [P, P, P, c_int64, c_int32, c_int32, c_int32, P, P, P, c_size_t, P]),
         "purekv_lowlayer_importance": (c_int, [P, P, P, P, c_int32, P, P, c_size_t, P]),
         "purekv_topk_select": (c_int, [P, P, P, c_int64, c_int32, c_int32, c_int32, P, P, P, c_size_t, P]),
         "purekv_topk_select_static": (c_int, [P, P, P, c_int64, c_int32, c_int32, c_int32, P, P]),
@@ -94,7 +96,7 @@ EXPORTS = (
     "purekv_plan_create", "purekv_plan_create_host", "purekv_plan_destroy", "purekv_plan_create_heads",
     "purekv_plan_create_heads_host", "purekv_plan_counts",
     "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_workspace_bytes", "purekv_workspace_init",
-    "purekv_stack_workspace_init", "purekv_st_spattn_prefill",
+    "purekv_stack_workspace_init", "purekv_st_spattn_prefill", "purekv_st_spattn_prefill_vnorm", "purekv_topk_select_vnorm",
     "purekv_lowlayer_importance", "purekv_topk_select", "purekv_topk_select_static", "purekv_kv_compact", "purekv_kv_append",
     "purekv_decode_attn", "purekv_decode_step", "purekv_stack_workspace_bytes", "purekv_stack_layer",
     "purekv_stack_select_compact", "purekv_budget", "purekv_plan_kept_tile_flops", "purekv_plan_mask_flops",
@@ -269,7 +271,8 @@ class Plan:
 
 def purekv_st_spattn_prefill(plan: Plan, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
                              out: Optional[torch.Tensor] = None, want_lse: bool = False,
-                             lse: Optional[torch.Tensor] = None):
+                             lse: Optional[torch.Tensor] = None, vnorm2: Optional[torch.Tensor] = None):
+    """vnorm2: optional fp32 [Hkv, N] output: the call becomes purekv_st_spattn_prefill_vnorm and fills it."""
     _strided_bf16(q, "q", plan.Hq, plan.N, plan.d, plan.q_strides)
     _strided_bf16(k, "k", plan.Hkv, plan.N, plan.d, plan.kv_strides)
     _strided_bf16(v, "v", plan.Hkv, plan.N, plan.d, plan.kv_strides)
@@ -280,8 +283,14 @@ def purekv_st_spattn_prefill(plan: Plan, q: torch.Tensor, k: torch.Tensor, v: to
         lse = torch.empty((plan.Hq, plan.N), dtype=torch.float32, device=q.device)
     nb = plan.workspace_bytes(OP_PREFILL)
     ws = plan._workspace(OP_PREFILL, nb, q.device)
-    _check(_lib.purekv_st_spattn_prefill(plan.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
-                                         _ptr(lse), _ptr(ws), nb, _stream()), "purekv_st_spattn_prefill")
+    if vnorm2 is not None:
+        assert vnorm2.dtype == torch.float32 and vnorm2.is_contiguous() and vnorm2.shape == (plan.Hkv, plan.N)
+        _check(_lib.purekv_st_spattn_prefill_vnorm(plan.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                                   _ptr(lse), vnorm2.data_ptr(), _ptr(ws), nb, _stream()),
+               "purekv_st_spattn_prefill_vnorm")
+    else:
+        _check(_lib.purekv_st_spattn_prefill(plan.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                             _ptr(lse), _ptr(ws), nb, _stream()), "purekv_st_spattn_prefill")
     return (out, lse) if (want_lse or lse is not None) else out
 
 
@@ -314,6 +323,29 @@ def purekv_topk_select(plan: Plan, c: torch.Tensor, v: Optional[torch.Tensor], w
     ws = plan._workspace(OP_TOPK, nb, c.device)
     _check(_lib.purekv_topk_select(plan.handle, c.data_ptr(), _ptr(v), stride, n_layers, w, h, idx_out.data_ptr(),
                                    _ptr(s_out), _ptr(ws), nb, _stream()), "purekv_topk_select")
+    if not layered:
+        idx_out = idx_out[0]
+        s_out = None if s_out is None else s_out[0]
+    return (idx_out, s_out) if want_scores else idx_out
+
+
+def purekv_topk_select_vnorm(plan: Plan, c: torch.Tensor, vnorm2: torch.Tensor, w: int, h: int,
+                             want_scores: bool = False, idx_out: Optional[torch.Tensor] = None):
+    """vnorm2: fp32 [Hkv, N] or [L, Hkv, N] (layers share c), as purekv_st_spattn_prefill_vnorm emits it."""
+    assert c.dtype == torch.float32 and c.is_contiguous() and c.is_cuda
+    assert vnorm2.dtype == torch.float32 and vnorm2.is_cuda and vnorm2.shape[-2:] == (plan.Hkv, plan.N)
+    assert vnorm2[0].is_contiguous() if vnorm2.dim() == 3 else vnorm2.is_contiguous()
+    layered = vnorm2.dim() == 3
+    n_layers = vnorm2.shape[0] if layered else 1
+    stride = vnorm2.stride(0) if layered else 0
+    if idx_out is None:
+        idx_out = torch.empty((n_layers, plan.Hkv, h + w), dtype=torch.int32, device=c.device)
+    s_out = torch.empty((n_layers, plan.Hkv, plan.N - w), dtype=torch.float32, device=c.device) if want_scores else None
+    nb = plan.workspace_bytes(OP_TOPK, n_layers, w) if s_out is None else 0
+    ws = plan._workspace(OP_TOPK, nb, c.device)
+    _check(_lib.purekv_topk_select_vnorm(plan.handle, c.data_ptr(), vnorm2.data_ptr(), stride, n_layers, w, h,
+                                         idx_out.data_ptr(), _ptr(s_out), _ptr(ws), nb, _stream()),
+           "purekv_topk_select_vnorm")
     if not layered:
         idx_out = idx_out[0]
         s_out = None if s_out is None else s_out[0]

@@ -262,7 +262,31 @@ int purekv_st_spattn_prefill(const purekv_plan_t* p, const void* q, const void* 
   if (!launchable(p) || q == nullptr || k == nullptr || v == nullptr || out == nullptr) return PUREKV_EINVAL;
   const size_t need = prefill_ws_bytes(*p);
   if (need > 0 && (ws == nullptr || ws_bytes < need)) return PUREKV_EWORKSPACE;
-  return launch_prefill(*p, q, k, v, out, lse, ws, static_cast<hipStream_t>(stream));
+  return launch_prefill(*p, q, k, v, out, lse, nullptr, ws, static_cast<hipStream_t>(stream));
+}
+
+int purekv_st_spattn_prefill_vnorm(const purekv_plan_t* p, const void* q, const void* k, const void* v, void* out,
+                                   float* lse, float* vnorm2, void* ws, size_t ws_bytes, void* stream) {
+  if (!launchable(p) || q == nullptr || k == nullptr || v == nullptr || out == nullptr || vnorm2 == nullptr)
+    return PUREKV_EINVAL;
+  const size_t need = prefill_ws_bytes(*p);
+  if (need > 0 && (ws == nullptr || ws_bytes < need)) return PUREKV_EWORKSPACE;
+  return launch_prefill(*p, q, k, v, out, lse, vnorm2, ws, static_cast<hipStream_t>(stream));
+}
+
+int purekv_topk_select_vnorm(const purekv_plan_t* p, const float* c, const float* vnorm2, int64_t vn_layer_stride,
+                             int32_t n_layers, int32_t w, int32_t h, int32_t* idx_out, float* s_out, void* ws,
+                             size_t ws_bytes, void* stream) {
+  if (!launchable(p) || idx_out == nullptr || vnorm2 == nullptr || n_layers < 1) return PUREKV_EINVAL;
+  if (w < 1 || w > p->g.N || h < 0 || h > p->g.N - w) return PUREKV_EINVAL;
+  if (c == nullptr && w < p->g.N) return PUREKV_EINVAL;
+  if (n_layers > 1 && vn_layer_stride < (int64_t)p->g.Hkv * p->g.N) return PUREKV_EINVAL;
+  if (s_out == nullptr) {
+    const size_t need = topk_ws_bytes(*p, n_layers, w);
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return PUREKV_EWORKSPACE;
+  }
+  return launch_topk_norms(*p, c, vnorm2, vn_layer_stride, n_layers, w, h, idx_out, s_out, ws,
+                           static_cast<hipStream_t>(stream));
 }
 
 int purekv_lowlayer_importance(const purekv_plan_t* p, const void* q, const void* k, const float* lse, int32_t w,
@@ -407,7 +431,7 @@ int purekv_stack_layer(const purekv_plan_t* dense, const purekv_plan_t* st, cons
   if (lay.total > 0 && (ws == nullptr || ws_bytes < lay.total)) return PUREKV_EWORKSPACE;
   if (ws != nullptr && sparse) ws = static_cast<char*>(ws) + lay.st_off;
   hipStream_t sm = static_cast<hipStream_t>(stream);
-  const int rp = launch_prefill(*p, q, k, v, out, emits_c ? lse : nullptr, ws, sm);
+  const int rp = launch_prefill(*p, q, k, v, out, emits_c ? lse : nullptr, nullptr, ws, sm);
   if (rp != PUREKV_OK || !emits_c) return rp;
   return launch_importance(*p, q, k, lse, s->w, c_all + (size_t)layer * p->g.Hkv * n_keys, sm);
 }

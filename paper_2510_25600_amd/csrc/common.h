@@ -92,11 +92,16 @@ int note_hip_error(hipError_t e);
 
 // Kernel launchers (one per translation unit); all arguments validated by the caller.
 int launch_prefill(const purekv_plan& p, const void* q, const void* k, const void* v, void* out, float* lse,
-                   void* ws, hipStream_t st);
+                   float* vnorm2, void* ws, hipStream_t st);
 int launch_importance(const purekv_plan& p, const void* q, const void* k, const float* lse, int32_t w,
                       float* c_out, hipStream_t st);
 int launch_topk(const purekv_plan& p, const float* c, const void* v, int64_t v_layer_stride, int32_t n_layers,
                 int32_t w, int32_t h, int32_t* idx_out, float* s_out, void* ws, hipStream_t st);
+// vnorm2[kv, j] = sum_c v[kv, j, c]^2 for all N keys, as a pass of its own over V
+int launch_vnorm2(const purekv_plan& p, const void* v, float* vnorm2, hipStream_t st);
+// the same with the squared norms of the V rows ([n_layers][Hkv, N] fp32, as the prefill emits them) instead of V
+int launch_topk_norms(const purekv_plan& p, const float* c, const float* vnorm2, int64_t vn_layer_stride,
+                      int32_t n_layers, int32_t w, int32_t h, int32_t* idx_out, float* s_out, void* ws, hipStream_t st);
 // Library-owned score buffer of the current device (looked up once per device) and its capacity in floats.
 int static_score_buffer(int device, float** out);
 size_t topk_static_capacity_floats();

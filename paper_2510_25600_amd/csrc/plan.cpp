@@ -6,7 +6,6 @@
 
 #include <algorithm>
 #include <cstddef>
-#include <cstdlib>
 #include <numeric>
 #include <utility>
 
@@ -180,12 +179,7 @@ void build_plan(purekv_plan& p, int n_cu) {
   // about one and a half steps.
   // The slice that closes a split list (its workgroup runs it last, so it normally arrives last and combines the
   // partial results of all slices) pays about two steps per slice for that (measured: a sweep of this constant on the 32-frame benchmark shape).
-#ifdef PUREKV_TUNING   // development builds: cost constants from the environment
-  const double kHalfTileCost = 0.85, kUnitCost = std::getenv("PUREKV_UNIT_COST") ? std::atof(std::getenv("PUREKV_UNIT_COST")) : 1.5,
-               kMergeCostPerSlice = std::getenv("PUREKV_MERGE_COST") ? std::atof(std::getenv("PUREKV_MERGE_COST")) : 2.0;
-#else
   constexpr double kHalfTileCost = 0.85, kUnitCost = 1.5, kMergeCostPerSlice = 2.0;
-#endif
   std::vector<double> tile_cost(p.tiles.size());
   for (size_t i = 0; i < p.tiles.size(); ++i) {
     bool both = false;
@@ -243,21 +237,7 @@ void build_plan(purekv_plan& p, int n_cu) {
   };
   std::vector<std::vector<int32_t>> queues(p.n_queues);  // flat (item, group) pairs
   std::vector<double> load(p.n_queues, 0.0);
-#ifdef PUREKV_TUNING
-  const bool row_order = std::getenv("PUREKV_DEAL") && std::getenv("PUREKV_DEAL")[0] == 'r';
-#else
-  constexpr bool row_order = false;
-#endif
-  std::vector<size_t> deal_order(p.items.size());
-  std::iota(deal_order.begin(), deal_order.end(), size_t(0));
-  if (row_order)   // slices first (longest first), then whole lists by query tile
-    std::stable_sort(deal_order.begin(), deal_order.end(), [&](size_t x, size_t y) {
-      const bool sx = p.items[x].n_splits > 1, sy = p.items[y].n_splits > 1;
-      if (sx != sy) return sx;
-      if (sx) return x < y;
-      return p.items[x].qtile < p.items[y].qtile;
-    });
-  for (size_t it : deal_order) {
+  for (size_t it = 0; it < p.items.size(); ++it) {
     for (int32_t grp = 0; grp < g.n_groups; ++grp) {
       if (!group_selected(grp)) continue;
       const int32_t kvh = grp * g.Gs / g.G;
@@ -333,10 +313,7 @@ void build_plan(purekv_plan& p, int n_cu) {
     for (size_t u = 0; u + 1 < qv.size(); u += 2) pairs.emplace_back(qv[u], qv[u + 1]);
     std::stable_sort(pairs.begin(), pairs.end(), [&](const std::pair<int32_t, int32_t>& x, const std::pair<int32_t, int32_t>& y) {
       const int cx = order_class(x.first), cy = order_class(y.first);
-      if (cx != cy) return cx < cy;
-      if (row_order && cx == 1 && p.items[x.first].qtile != p.items[y.first].qtile)
-        return p.items[x.first].qtile < p.items[y.first].qtile;
-      return x < y;
+      return cx != cy ? cx < cy : x < y;
     });
     for (size_t u = 0; u < pairs.size(); ++u) {
       qv[2 * u] = pairs[u].first;
@@ -344,6 +321,7 @@ void build_plan(purekv_plan& p, int n_cu) {
     }
   }
 
+  std::vector<uint8_t> owned(size_t(g.Hkv) * size_t(n_ktiles), 0);   // (KV head, key tile) pairs that have an owner step
   p.units.clear();
   p.stream.clear();
   p.queue_begin.assign(1, 0);
@@ -368,8 +346,10 @@ void build_plan(purekv_plan& p, int n_cu) {
         StreamEntry e;
         e.kv_off = uint32_t((int64_t(kvh) * g.kv_sh + int64_t(r.tile) * BK * g.kv_st) * 2);
         const int32_t k0 = r.tile * BK, rows = std::min(BK, g.N - k0);
+        uint8_t& own = owned[size_t(kvh) * size_t(n_ktiles) + size_t(r.tile)];
         e.need = r.need | ((t == w.n_tiles - 1) ? (1u << 16) : 0u) | ((t == 0) ? (1u << 17) : 0u) |
-                 (uint32_t(rows - 1) << 18);
+                 (uint32_t(rows - 1) << 18) | (own ? 0u : (1u << 24));
+        own = 1;
         e.kinds = r.kinds;
         e.k0 = k0;
         p.stream.push_back(e);

@@ -50,8 +50,10 @@ struct TileRef {
 // One step of a persistent workgroup's stream: stage this key tile, compute it for the row blocks that need it.
 struct StreamEntry {
   uint32_t kv_off;     // byte offset of the tile's first row within the K (and V) tensor: (kvh*kv_sh + k0*kv_st)*2
-  uint32_t need;       // TileRef::need | last << 16 | first << 17 | (rows - 1) << 18: last / first step of its
-                       // unit (units are numbered in stream order); rows = keys of the tile that exist (1..64)
+  uint32_t need;       // TileRef::need | last << 16 | first << 17 | (rows - 1) << 18 | owner << 24: last / first step
+                       // of its unit (units are numbered in stream order); rows = keys of the tile that exist
+                       // (1..64); owner: this step is the one step of the launch that also emits the squared
+                       // norms of the tile's V rows (every (KV head, key tile) has exactly one owner step)
   uint32_t kinds;      // TileRef::kinds
   int32_t k0;          // first key of the tile
 };

@@ -31,6 +31,8 @@
 // and V(j+1), whose buffers were last read in iteration j-1.  Every wavefront waits for its own loads at the top
 // of an iteration, before the barrier; the loads are written as assembly so that these are the only waits (the
 // compiler cannot tell which buffer a load of the builtin form fills and waits for all of them before LDS reads).
+#include <type_traits>
+
 #include "common.h"
 
 namespace purekv {
@@ -55,6 +57,7 @@ struct PrefillArgs {
   const uint16_t* v;
   uint16_t* out;
   float* lse;
+  float* vnorm2;  // [Hkv, N] squared L2 norms of the V rows (VN variants), or null
   float* ws_o;    // [n_slots, n_groups, WG_ROWS, D] normalised partial outputs
   float* ws_lse;  // [n_slots, n_groups, WG_ROWS, 2] log2-domain log-sum-exp of the partial: {merge weight, exact}
   int32_t* counters;   // [n_slots, n_groups, PUREKV_WAVES] slices arrived per (split query tile, head group, wavefront);
@@ -63,7 +66,7 @@ struct PrefillArgs {
   const Unit* units;
   const int32_t* queue_begin;   // [n_queues + 1] offsets into stream
   const int32_t* queue_unit0;   // [n_queues + 1] first unit of each queue (units are numbered in stream order)
-  int32_t N, Nv, P, Hq, Hkv;
+  int32_t N, Nv, P, Hq, Hkv, G;
   // byte strides of the (head, token) axes: Q, O per head and row, K/V per row (the head is in the stream entries)
   int64_t q_head_bytes, o_head_bytes;
   uint32_t q_row_bytes, kv_row_bytes, o_row_bytes;
@@ -128,7 +131,10 @@ struct Step {
 // key tile: all wavefronts load it, the wavefronts whose row block needs it multiply the 32-key halves they
 // need.  Units (query tile slice x head group) follow each other in the stream without draining the K/V
 // pipeline; the query rows of the next unit are fetched while the last tile of the current one is finished.
-template <int D, bool ST, bool LSE>
+// VN  = true : for plans that leave the last wavefront without rows (seven stacked heads): that wavefront emits the
+//              squared norms of the V rows of every tile this step owns (Eq. 3 / Eq. 4 need ||V||: the tile is in
+//              LDS anyway).  Plans that keep all eight wavefronts busy get the norms from a pass of their own.
+template <int D, bool ST, bool LSE, bool VN>
 __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
   constexpr int KSTEPS = D / 16;        // MFMA k-steps of the score product
   constexpr int DBLK = D / 32;          // 32-row blocks of O^T
@@ -684,6 +690,41 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     update_reference(mt, true);
   }
 
+  // Squared norms of the V rows of an owned tile (V ring buffer `buf`, stream entry e, unit `unit`): LPR lanes per
+  // row, 16 bytes each (the swizzle permutes a row's pieces, the sum does not care), RPP rows per pass.
+  auto vnorm_tile = [&](const Step& e, int buf, int unit) {
+    constexpr int LPR = D / 8, RPP = 64 / LPR, NP = BK / RPP;
+    const u32x4 un = units_c[2 * unit];
+    const int kvh = (int)un[1] / a.G, rv = (int)((e.need >> 18) & 63u);
+    const uint16_t* Vs = Vs_base + buf * (BK * D);
+    float* const dst = a.vnorm2 + (size_t)kvh * a.N + e.k0;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    // sum over the LPR lanes of a row on the DPP path of the vector ALU (lane ^ 1, lane ^ 2, mirror of 8, mirror of
+    // 16): the wavefront must be back at the tile barrier long before the others, a chain of LDS shuffles is not
+    auto dpp_add = [](float x, auto ctrl) {
+      return x + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), decltype(ctrl)::value,
+                                                                          0xf, 0xf, false));
+    };
+#pragma unroll 4
+    for (int pass = 0; pass < NP; ++pass) {
+      const int r = pass * RPP + ln / LPR;
+      const u32x4 x = *reinterpret_cast<const u32x4*>(Vs + r * D + (ln % LPR) * 8);
+      float ss = 0.f;
+#pragma unroll
+      for (int wd = 0; wd < 4; ++wd) {
+        const uint32_t word = x[wd];   // (a bit_cast applied directly to a vector element picks element 0 with this compiler)
+        const bf16x2 pr = __builtin_bit_cast(bf16x2, word);
+        ss = __builtin_amdgcn_fdot2_f32_bf16(pr, pr, ss, false);
+      }
+      ss = dpp_add(ss, std::integral_constant<int, 0xB1>{});    // quad_perm [1, 0, 3, 2]
+      ss = dpp_add(ss, std::integral_constant<int, 0x4E>{});    // quad_perm [2, 3, 0, 1]
+      ss = dpp_add(ss, std::integral_constant<int, 0x141>{});   // row_half_mirror: lane i <-> 7 - i of each 8
+      if (LPR == 16) ss = dpp_add(ss, std::integral_constant<int, 0x140>{});   // row_mirror: lane i <-> 15 - i
+      if ((ln % LPR) == 0 && r <= rv) dst[r] = ss;
+    }
+  };
+
   int bj = 1;   // ring buffer of tile j
   // One iteration; Sn receives the scores of tile j, Sp holds those of tile j-1.
   auto iteration = [&](int j, floatx16 (&Sn)[2], floatx16 (&Sp)[2]) {
@@ -703,6 +744,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
       resc = false;
     }
     const float neg_m = (m == -INFINITY) ? 0.f : -m;   // m: reference after tile j-1, until this tile's maximum is in
+    const int unit_prev = unit_id;   // unit of tile j-1
     if (first) {
       load_q_frags();   // frees the private tile, which the finished unit's rows leave through
       ++unit_id;
@@ -721,6 +763,10 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     if (!active) {
       if (j + 2 < t_end) issue_k(e_n2, b_prev);
       if (j + 1 < t_end) issue_v(e_n1, b_next);
+      // (only here: the same few lines inside the computing wavefronts' path cost them half their speed)
+      if (VN) {
+        if (((e_prev.need >> 24) & 1u) && wave == PUREKV_WAVES - 1) vnorm_tile(e_prev, b_prev, unit_prev);
+      }
     }
     if (active) {
       // ---- score product of tile j, exponentials of tile j-1 ----
@@ -797,20 +843,22 @@ __global__ void clear_counters_kernel(int32_t* c, int n) {
   if (i < n) c[i] = 0;
 }
 
-template <int D, bool ST, bool LSE>
+template <int D, bool ST, bool LSE, bool VN>
 hipError_t launch_one(const PrefillArgs& a, dim3 grid, hipStream_t st) {
   // 3 K buffers + 3 V buffers + one private tile per wavefront
   constexpr unsigned lds_bytes = (6u * BK * D + PUREKV_WAVES * kXTile) * sizeof(uint16_t);
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel<D, ST, LSE>),
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel<D, ST, LSE, VN>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL((prefill_kernel<D, ST, LSE>), grid, dim3(512), lds_bytes, st, a);
+  hipLaunchKernelGGL((prefill_kernel<D, ST, LSE, VN>), grid, dim3(512), lds_bytes, st, a);
   return hipSuccess;
 }
 
 template <int D, bool ST>
 hipError_t launch_variant(const PrefillArgs& a, dim3 grid, hipStream_t st) {
-  return a.lse != nullptr ? launch_one<D, ST, true>(a, grid, st) : launch_one<D, ST, false>(a, grid, st);
+  if (a.vnorm2 != nullptr && a.Gs * a.R < PUREKV_WAVES)
+    return a.lse != nullptr ? launch_one<D, ST, true, true>(a, grid, st) : launch_one<D, ST, false, true>(a, grid, st);
+  return a.lse != nullptr ? launch_one<D, ST, true, false>(a, grid, st) : launch_one<D, ST, false, false>(a, grid, st);
 }
 
 }  // namespace
@@ -836,8 +884,10 @@ int launch_prefill_ws_init(const purekv_plan& p, void* ws, hipStream_t st) {
 }
 
 int launch_prefill(const purekv_plan& p, const void* q, const void* k, const void* v, void* out, float* lse,
-                   void* ws, hipStream_t st) {
+                   float* vnorm2, void* ws, hipStream_t st) {
   PrefillArgs a{};
+  a.vnorm2 = vnorm2;
+  a.G = p.g.G;
   a.q = static_cast<const uint16_t*>(q);
   a.k = static_cast<const uint16_t*>(k);
   a.v = static_cast<const uint16_t*>(v);
@@ -879,6 +929,8 @@ int launch_prefill(const purekv_plan& p, const void* q, const void* k, const voi
       PUREKV_HIP_TRY((launch_variant<64, false>(a, grid, st)));
   }
   PUREKV_HIP_TRY(hipGetLastError());
+  // every wavefront of this plan's workgroups has rows: the norms come from a stream over V of their own
+  if (vnorm2 != nullptr && p.g.Gs * p.g.R >= PUREKV_WAVES) return launch_vnorm2(p, v, vnorm2, st);
   return PUREKV_OK;
 }
 

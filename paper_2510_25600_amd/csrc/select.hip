@@ -97,6 +97,49 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ c,
   }
 }
 
+// Squared norms of all V rows of one layer, as a pass of its own (same access pattern as the score kernel).
+template <int D>
+__global__ __launch_bounds__(256) void vnorm2_kernel(const uint16_t* __restrict__ v, int64_t v_head_stride,
+                                                     int64_t v_tok_stride, float* __restrict__ n2_out, int32_t N,
+                                                     int32_t kvh0) {
+  constexpr int LPR = D / 8, RPB = 256 / LPR;
+  const int sub = threadIdx.x % LPR, rslot = threadIdx.x / LPR;
+  const int kvh = kvh0 + blockIdx.y;
+  const uint16_t* vh = v + (int64_t)kvh * v_head_stride;
+  const int j0 = blockIdx.x * (RPB * SCORE_UNROLL) + rslot;
+  u32x4 x[SCORE_UNROLL];
+#pragma unroll
+  for (int u = 0; u < SCORE_UNROLL; ++u) {
+    const int j = min(j0 + u * RPB, N - 1);
+    x[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vh + (int64_t)j * v_tok_stride + sub * 8));
+  }
+#pragma unroll
+  for (int u = 0; u < SCORE_UNROLL; ++u) {
+    float ss = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float lo = bf16_lo(x[u][w]), hi = bf16_hi(x[u][w]);
+      ss += lo * lo + hi * hi;
+    }
+#pragma unroll
+    for (int o = 1; o < LPR; o <<= 1) ss += __shfl_xor(ss, o, 64);
+    const int j = j0 + u * RPB;
+    if (sub == 0 && j < N) n2_out[(int64_t)kvh * N + j] = ss;
+  }
+}
+
+// The same scores from squared norms that already exist (the prefill kernel emits them while the V tiles are in
+// LDS): S[l, kv, j] = C[kv, j] * sqrt(n2[l, kv, j]).  4 bytes per key instead of a V row.
+__global__ __launch_bounds__(256) void score_from_norms_kernel(const float* __restrict__ c, const float* __restrict__ n2,
+                                                               int64_t n2_layer_stride, float* __restrict__ s_out,
+                                                               int32_t N, int32_t n_keys, int32_t Hkv) {
+  const int lk = blockIdx.y, layer = lk / Hkv, kvh = lk - layer * Hkv;
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= n_keys) return;
+  const float x = n2[(int64_t)layer * n2_layer_stride + (int64_t)kvh * N + j];
+  s_out[(int64_t)lk * n_keys + j] = c[(int64_t)kvh * n_keys + j] * __builtin_sqrtf(x);
+}
+
 // Block-wide exclusive scan of two counters (1024 threads = 16 wavefronts).
 __device__ __forceinline__ void block_scan2(uint32_t& a, uint32_t& b, uint32_t* lds /* 34 words */) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -397,6 +440,48 @@ size_t topk_ws_bytes(const purekv_plan& p, int32_t n_layers, int32_t w) {
   return n_keys > 0 ? (size_t)n_layers * p.g.Hkv * n_keys * sizeof(float) : 0;
 }
 
+static int launch_select(const purekv_plan& p, const float* scores, int32_t n_layers, int32_t w, int32_t h,
+                         int32_t* idx_out, hipStream_t st);
+
+int launch_vnorm2(const purekv_plan& p, const void* v, float* vnorm2, hipStream_t st) {
+  const int rows_per_block = (256 / (p.g.d / 8)) * SCORE_UNROLL;
+  const unsigned gx = (unsigned)((p.g.N + rows_per_block - 1) / rows_per_block);
+  auto launch = [&](int kvh0, int count) {
+    const dim3 grid(gx, (unsigned)count);
+    if (p.g.d == 128)
+      hipLaunchKernelGGL(vnorm2_kernel<128>, grid, dim3(256), 0, st, static_cast<const uint16_t*>(v), p.g.kv_sh,
+                         p.g.kv_st, vnorm2, p.g.N, kvh0);
+    else
+      hipLaunchKernelGGL(vnorm2_kernel<64>, grid, dim3(256), 0, st, static_cast<const uint16_t*>(v), p.g.kv_sh,
+                         p.g.kv_st, vnorm2, p.g.N, kvh0);
+  };
+  if (p.head_sel.empty()) {
+    launch(0, p.g.Hkv);
+  } else {   // a plan over a head subset: only the KV heads it reads
+    for (int kvh = 0; kvh < p.g.Hkv; ++kvh) {
+      bool any = false;
+      for (int gq = 0; gq < p.g.G; ++gq) any |= p.head_sel[(size_t)kvh * p.g.G + gq] != 0;
+      if (any) launch(kvh, 1);
+    }
+  }
+  PUREKV_HIP_TRY(hipGetLastError());
+  return PUREKV_OK;
+}
+
+int launch_topk_norms(const purekv_plan& p, const float* c, const float* vnorm2, int64_t vn_layer_stride,
+                      int32_t n_layers, int32_t w, int32_t h, int32_t* idx_out, float* s_out, void* ws, hipStream_t st) {
+  const int32_t n_keys = p.g.N - w;
+  const float* scores = c;
+  if (n_keys > 0) {
+    float* sbuf = s_out ? s_out : static_cast<float*>(ws);
+    const dim3 grid((unsigned)((n_keys + 255) / 256), (unsigned)(n_layers * p.g.Hkv));
+    hipLaunchKernelGGL(score_from_norms_kernel, grid, dim3(256), 0, st, c, vnorm2, vn_layer_stride, sbuf, p.g.N, n_keys,
+                       p.g.Hkv);
+    scores = sbuf;
+  }
+  return launch_select(p, scores, n_layers, w, h, idx_out, st);
+}
+
 int launch_topk(const purekv_plan& p, const float* c, const void* v, int64_t v_layer_stride, int32_t n_layers,
                 int32_t w, int32_t h, int32_t* idx_out, float* s_out, void* ws, hipStream_t st) {
   const int32_t n_keys = p.g.N - w;
@@ -415,6 +500,12 @@ int launch_topk(const purekv_plan& p, const float* c, const void* v, int64_t v_l
   } else if (s_out != nullptr && n_keys > 0) {
     PUREKV_HIP_TRY(hipMemcpyAsync(s_out, c, (size_t)p.g.Hkv * n_keys * sizeof(float), hipMemcpyDeviceToDevice, st));
   }
+  return launch_select(p, scores, n_layers, w, h, idx_out, st);
+}
+
+static int launch_select(const purekv_plan& p, const float* scores, int32_t n_layers, int32_t w, int32_t h,
+                         int32_t* idx_out, hipStream_t st) {
+  const int32_t n_keys = p.g.N - w;
   const dim3 sgrid((unsigned)(n_layers * p.g.Hkv)), sblock(SEL_THREADS);
   const int chunk = (n_keys + SEL_THREADS - 1) / SEL_THREADS;
   if (chunk <= 8) {

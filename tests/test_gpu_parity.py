@@ -607,3 +607,74 @@ def test_two_streams_share_one_plan():
             check_attention(f64_of(decs[i][rnd]), dref, f"stream {i} round {rnd} decode")
             assert np.array_equal(bits_of(outs[i][rnd]), bits_of(outs[i][0]))   # and reproducible bit for bit
             assert np.array_equal(bits_of(decs[i][rnd]), bits_of(decs[i][0]))
+
+
+@pytest.mark.parametrize("pattern", [0, 3])
+@pytest.mark.parametrize("name", ["tiny_4f", "ragged_3f", "straddle_3f", "heads7_3f", "heads3_4f", "manyunits_g7",
+                                  "manyunits_g1", "single_token", "longtext_2f"])
+def test_prefill_emits_squared_v_norms(name, pattern):
+    """The V-norm weighting without a second pass over V (Eq. 3 / Eq. 4): the prefill call that also emits
+    ||v_j||^2 for every key writes every entry exactly once (NaN-filled buffer), equal to the oracle's norms, and
+    leaves the attention output bit for bit what the plain call gives; the selection from C and these norms is the
+    oracle's."""
+    wl = SMALL[name]
+    inp = generate(wl, seed=33)
+    n, w = wl.n_tokens, min(wl.window if wl.window else 1, wl.n_tokens)
+    w = max(w, 1)
+    print(f"[case] prefill+vnorm {name} pattern={pattern}", flush=True)
+    plan = _plan(wl, pattern)
+    q, k, v = to_dev(inp.q), to_dev(inp.k), to_dev(inp.v)
+    out_plain, lse_plain = pk.purekv_st_spattn_prefill(plan, q, k, v, want_lse=True)
+    vn2 = torch.full((wl.n_kv_heads, n), float("nan"), dtype=torch.float32, device="cuda")
+    out, lse = pk.purekv_st_spattn_prefill(plan, q, k, v, want_lse=True, vnorm2=vn2)
+    out_nolse = pk.purekv_st_spattn_prefill(plan, q, k, v, vnorm2=torch.empty_like(vn2))
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(out), bits_of(out_plain)) and torch.equal(lse, lse_plain)
+    assert np.array_equal(bits_of(out_nolse), bits_of(out_plain))
+    vf = F64(inp.v)
+    ref = (vf * vf).sum(2)
+    got = f64_of(vn2)
+    assert np.isfinite(got).all()
+    assert np.all(np.abs(got - ref) <= 2e-6 * ref + 1e-30), f"worst rel {np.max(np.abs(got - ref) / np.maximum(ref, 1e-30)):.3g}"
+    if n - w >= 1:
+        h = max(1, orc.budget(n, w, 0.3)) if n - w >= 2 else 1
+        h = min(h, n - w)
+        c = np.random.default_rng(5).random((wl.n_kv_heads, n - w)).astype(np.float32)
+        idx, s = pk.purekv_topk_select_vnorm(plan, torch.from_numpy(c).cuda(), vn2, w, h, want_scores=True)
+        idx2 = pk.purekv_topk_select_vnorm(plan, torch.from_numpy(c).cuda(), vn2, w, h)   # workspace path
+        torch.cuda.synchronize()
+        assert torch.equal(idx, idx2)
+        s_ref = orc.vnorm_scores(c.astype(np.float64), vf)
+        assert np.all(np.abs(f64_of(s) - s_ref) <= 2e-6 * np.abs(s_ref) + 1e-30)
+        check_kept_sets(idx.cpu().numpy(), orc.topk_select(s_ref, h, n, w), s_ref, h)
+
+
+def test_prefill_vnorm_layers_and_head_subsets():
+    """Layered norms [L, Hkv, N] through one batched selection, and a plan over a head subset: the KV heads none of
+    whose query heads it covers keep what the buffer held."""
+    wl = SMALL["heads3_4f"]       # 6 query heads on 2 KV heads
+    n, w = wl.n_tokens, wl.window
+    h = orc.budget(n, w, 0.4)
+    layers = [generate(wl, seed=90 + l) for l in range(3)]
+    plan = _plan(wl, 3)
+    vn_all = torch.empty((3, wl.n_kv_heads, n), dtype=torch.float32, device="cuda")
+    for l, x in enumerate(layers):
+        pk.purekv_st_spattn_prefill(plan, to_dev(x.q), to_dev(x.k), to_dev(x.v), vnorm2=vn_all[l])
+    c = np.random.default_rng(6).random((wl.n_kv_heads, n - w)).astype(np.float32)
+    idx = pk.purekv_topk_select_vnorm(plan, torch.from_numpy(c).cuda(), vn_all, w, h)
+    v_all = torch.stack([to_dev(x.v) for x in layers])
+    idx_v = pk.purekv_topk_select(plan, torch.from_numpy(c).cuda(), v_all, w, h)
+    torch.cuda.synchronize()
+    for l, x in enumerate(layers):
+        s_ref = orc.vnorm_scores(c.astype(np.float64), F64(x.v))
+        check_kept_sets(idx[l].cpu().numpy(), orc.topk_select(s_ref, h, n, w), s_ref, h)
+        check_kept_sets(idx_v[l].cpu().numpy(), orc.topk_select(s_ref, h, n, w), s_ref, h)
+    sub = pk.Plan(wl.n_frames, wl.patch_h, wl.patch_w, wl.n_text, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, 3,
+                  head_mask=[0, 0, 0, 1, 0, 1])            # query heads 3 and 5: KV head 1 only
+    x = layers[0]
+    vn = torch.full((wl.n_kv_heads, n), -7.0, dtype=torch.float32, device="cuda")
+    pk.purekv_st_spattn_prefill(sub, to_dev(x.q), to_dev(x.k), to_dev(x.v), vnorm2=vn)
+    torch.cuda.synchronize()
+    vf = F64(x.v)
+    assert torch.all(vn[0] == -7.0)
+    assert np.all(np.abs(f64_of(vn[1]) - (vf[1] ** 2).sum(1)) <= 2e-6 * (vf[1] ** 2).sum(1))

@@ -84,6 +84,8 @@ def test_compute_calls_validate_before_touching_the_gpu():
     one = ctypes.c_void_p(16)  # never dereferenced: validation fails first
     assert lib.purekv_st_spattn_prefill(h, one, one, one, one, None, None, 0, None) == pk.EINVAL
     assert lib.purekv_st_spattn_prefill(None, one, one, one, one, None, None, 0, None) == pk.EINVAL
+    assert lib.purekv_st_spattn_prefill_vnorm(h, one, one, one, one, None, one, None, 0, None) == pk.EINVAL
+    assert lib.purekv_topk_select_vnorm(h, one, one, 0, 1, 8, 4, one, None, None, 0, None) == pk.EINVAL
     assert lib.purekv_lowlayer_importance(h, one, one, one, 8, one, None, 0, None) == pk.EINVAL
     assert lib.purekv_topk_select(h, one, None, 0, 1, 8, 4, one, None, None, 0, None) == pk.EINVAL
     assert lib.purekv_topk_select_static(h, one, one, 0, 1, 8, 4, one, None) == pk.EINVAL
