@@ -195,6 +195,10 @@ def main() -> int:
                     help="untimed clock ramp before the warm-up steps: the board's calibration loop (tile-step skeleton) is "
                          "run for about this many milliseconds so that the shader clock has left its idle state, as it "
                          "has inside the prefill of a whole model; reported as `clock_ramp`; 0 disables it")
+    ap.add_argument("--layout", default="packed", choices=["packed", "token_major"],
+                    help="layout of Q, K, V, O in the per-layer step: packed [H, N, d], or token-major views of one "
+                         "[N, (Hq + 2 Hkv) d] buffer as a decoder's QKV projection writes it (O as [N, Hq d]); the layer-"
+                         "batched selection and compaction always read packed layers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=28, help="query heads in the oracle's timed sample")
     ap.add_argument("--stack", action="store_true",
@@ -249,10 +253,34 @@ def main() -> int:
     q0, k0, v0 = to_dev(low.q), to_dev(low.k), to_dev(low.v)
     q1, k1, v1 = to_dev(high.q), to_dev(high.k), to_dev(high.v)
     q_new, k_new, v_new = to_dev(high.q_new[0]), to_dev(high.k_new[0]), to_dev(high.v_new[0])
-    dense = pk.Plan.for_workload(wl, pk.PATTERN_DENSE)
-    st = pk.Plan.for_workload(wl, pk.PATTERN_ST)
+    calib_src = q0   # 4 MiB of finite bf16 values for the calibration loops
+    st_packed = pk.Plan.for_workload(wl, pk.PATTERN_ST)   # the layer-batched calls read packed [L, Hkv, N, d] layers
+    if args.layout == "token_major":
+        row = (hq + 2 * hkv) * d
 
-    out0, out1 = torch.empty_like(q0), torch.empty_like(q1)
+        def fuse(q_, k_, v_):
+            buf = torch.empty((n, row), dtype=torch.bfloat16, device=dev)
+            buf[:, :hq * d] = q_.permute(1, 0, 2).reshape(n, hq * d)
+            buf[:, hq * d:(hq + hkv) * d] = k_.permute(1, 0, 2).reshape(n, hkv * d)
+            buf[:, (hq + hkv) * d:] = v_.permute(1, 0, 2).reshape(n, hkv * d)
+            return (buf[:, :hq * d].view(n, hq, d).permute(1, 0, 2), buf[:, hq * d:(hq + hkv) * d].view(n, hkv, d).permute(1, 0, 2),
+                    buf[:, (hq + hkv) * d:].view(n, hkv, d).permute(1, 0, 2))
+
+        v1_packed = v1
+        k1_packed = k1
+        q0, k0, v0 = fuse(q0, k0, v0)
+        q1, k1, v1 = fuse(q1, k1, v1)
+        strides = dict(q_strides=(d, row), kv_strides=(d, row), o_strides=(d, hq * d))
+        dense = pk.Plan.for_workload(wl, pk.PATTERN_DENSE, **strides)
+        st = pk.Plan.for_workload(wl, pk.PATTERN_ST, **strides)
+        out0, out1 = dense.empty_out(dev), st.empty_out(dev)
+        layout = f"token-major: Q, K, V views of one [N, {row}] buffer (head stride {d}, token stride {row}), O [N, {hq * d}]"
+    else:
+        v1_packed, k1_packed = v1, k1
+        dense = pk.Plan.for_workload(wl, pk.PATTERN_DENSE)
+        st = st_packed
+        out0, out1 = torch.empty_like(q0), torch.empty_like(q1)
+        layout = "packed [H, N, d] (head stride N*d, token stride d)"
     lse = torch.empty((hq, n), dtype=torch.float32, device=dev)
     c = torch.empty((hkv, n - w), dtype=torch.float32, device=dev)
     idx0 = torch.empty((1, hkv, n_keep), dtype=torch.int32, device=dev)
@@ -284,6 +312,9 @@ def main() -> int:
         mark(8)
 
     if args.stack:
+        if args.layout != "packed":
+            print("bench.py: --stack runs on packed layers", file=sys.stderr)
+            return 2
         L = args.stack_layers or max(wl.n_layers, 2)
         st_layer = max(1, min(args.stack_dense or wl.n_dense_layers or 1, L))
         clie = st_layer - 1
@@ -342,8 +373,8 @@ def main() -> int:
         v_all = torch.empty((L, hkv, n, d), dtype=torch.bfloat16, device=dev)
         k_all = torch.empty_like(v_all)
         for l in range(L):
-            v_all[l] = v1.roll(l, dims=1)
-            k_all[l] = k1.roll(l, dims=1)
+            v_all[l] = v1_packed.roll(l, dims=1)
+            k_all[l] = k1_packed.roll(l, dims=1)
         idx_all = torch.empty((L, hkv, n_keep), dtype=torch.int32, device=dev)
         kc_all = torch.empty((L, hkv, n_keep, d), dtype=torch.bfloat16, device=dev)
         vc_all = torch.empty_like(kc_all)
@@ -365,10 +396,10 @@ def main() -> int:
     def step_calib(rows, iters=12000):
         """Tile-step skeleton (see purekv_calib_tile_step): one warm launch, one timed.  (TFLOP/s, us per step, GHz)"""
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        pk.purekv_calib_tile_step(st, rows, iters, q0)
+        pk.purekv_calib_tile_step(st, rows, iters, calib_src)
         torch.cuda.synchronize()
         a.record()
-        flops, ticks = pk.purekv_calib_tile_step(st, rows, iters, q0)
+        flops, ticks = pk.purekv_calib_tile_step(st, rows, iters, calib_src)
         b.record()
         torch.cuda.synchronize()
         cyc, ref = (int(x) for x in ticks.tolist())
@@ -395,7 +426,7 @@ def main() -> int:
         torch.cuda.synchronize()
         if args.only_stage in ("topk_batched", "compact_batched"):
             v_all, k_all, idx_all, kc_all, vc_all = make_batched(args.batched_layers)
-            pk.purekv_topk_select(st, c, v_all, w, h, idx_out=idx_all)
+            pk.purekv_topk_select(st_packed, c, v_all, w, h, idx_out=idx_all)
         if args.only_stage == "copy_calib":
             calib_src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
             calib_dst = torch.empty_like(calib_src)
@@ -410,8 +441,8 @@ def main() -> int:
             "append_decode": lambda: pk.purekv_decode_step(st, q_new, k_new, v_new, kc1, vc1, n_keep, out=o_dec),
             # plain device copy of a known size (256 MiB read + 256 MiB written): scale for the HBM byte counters
             "copy_calib": lambda: calib_dst.copy_(calib_src),
-            "topk_batched": lambda: pk.purekv_topk_select(st, c, v_all, w, h, idx_out=idx_all),
-            "compact_batched": lambda: pk.purekv_kv_compact(st, k_all, v_all, idx_all, kc=kc_all, vc=vc_all),
+            "topk_batched": lambda: pk.purekv_topk_select(st_packed, c, v_all, w, h, idx_out=idx_all),
+            "compact_batched": lambda: pk.purekv_kv_compact(st_packed, k_all, v_all, idx_all, kc=kc_all, vc=vc_all),
         }
         one = stages[args.only_stage]
         for _ in range(args.steps):
@@ -430,7 +461,7 @@ def main() -> int:
         r0.record()
         per_launch_ms, launches = 23.0, 0
         while launches * per_launch_ms < args.ramp_ms:
-            pk.purekv_calib_tile_step(st, 32, 12000, q0)
+            pk.purekv_calib_tile_step(st, 32, 12000, calib_src)
             launches += 1
         r1.record()
         torch.cuda.synchronize()
@@ -481,8 +512,8 @@ def main() -> int:
     # batched over the high layers (Eq. 4: every high layer scores with the same C and its own V)
     L = args.batched_layers
     v_all, k_all, idx_all, kc_all, vc_all = make_batched(L)
-    topk_b_ms = time_calls(lambda: pk.purekv_topk_select(st, c, v_all, w, h, idx_out=idx_all))
-    comp_b_ms = time_calls(lambda: pk.purekv_kv_compact(st, k_all, v_all, idx_all, kc=kc_all, vc=vc_all))
+    topk_b_ms = time_calls(lambda: pk.purekv_topk_select(st_packed, c, v_all, w, h, idx_out=idx_all))
+    comp_b_ms = time_calls(lambda: pk.purekv_kv_compact(st_packed, k_all, v_all, idx_all, kc=kc_all, vc=vc_all))
     del v_all, k_all, kc_all, vc_all
 
     # what the board sustains for the bare matrix instruction, constant and random operands (power limit)
@@ -509,7 +540,7 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4),
         "ms_per_step_graph_replay": round(ms_per_step_graph, 4),
         "clock_ramp": ramp,
-        "layout": "packed [H, N, d] (head stride N*d, token stride d)",
+        "layout": layout,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
