@@ -31,6 +31,12 @@
 // and V(j+1), whose buffers were last read in iteration j-1.  Every wavefront waits for its own loads at the top
 // of an iteration, before the barrier; the loads are written as assembly so that these are the only waits (the
 // compiler cannot tell which buffer a load of the builtin form fills and waits for all of them before LDS reads).
+//
+// Query tiles whose key list is long (the text rows, which see every key) are cut into slices run by different
+// workgroups; every slice leaves a normalised fp32 partial result and its log-sum-exp in the workspace, and the
+// slices are combined INSIDE the launch: wavefront by wavefront they count themselves in at a counter in the
+// workspace, and at the end of its queue a workgroup adds up every list it took part in that is complete and not
+// yet combined (compare-and-swap on the counter: exactly once, nobody waits).  One launch per call.
 #include <type_traits>
 
 #include "common.h"
@@ -123,6 +129,120 @@ struct Step {
   uint32_t kinds;
   int32_t k0;        // first key of the tile
 };
+
+// Combination, at the end of the workgroup's queue (the pipeline's registers are free then): for every slice this
+// wavefront ran, a counter that stands at n_splits means "all slices in memory, nobody has combined them yet";
+// whoever moves it to n_splits + 1 (compare-and-swap: exactly one wavefront can) adds the partial results up in a
+// fixed order (slice 0, 1, ...: reproducible bit for bit), writes the output rows and leaves the counter at zero
+// for the next launch.  The wavefront whose slice arrived last always finds n_splits or a combination already
+// claimed when it gets here, so every split tile is combined exactly once before the launch ends, and nobody ever
+// waits for anybody.  The planner runs the closing slice of a list last in its queue and the other slices first
+// in theirs: the workgroup it charged for the combination is then normally the one that does it.  Partial results
+// and counters travel as device-scope accesses (they bypass the L2 of the issuing XCD), ordered by "stores
+// acknowledged -> counter increment ... counter read -> loads".
+// Kept out of line (and called after the tile loop only): inlined, its registers and branches changed the
+// allocation of the loop itself and cost the dense kernel, which never combines anything, 3.5 %.
+typedef __attribute__((address_space(3))) float LdsFloat;
+typedef __attribute__((address_space(3))) floatx2 LdsFloatx2;
+struct CombineCall {
+  int32_t* counters;
+  const float* ws_o;
+  const float* ws_lse;
+  uint16_t* out;
+  float* lse;
+  LdsFloat* xs;   // this wavefront's private 8 KB of LDS (an LDS pointer: the table below is read with LDS instructions)
+  int64_t o_head_bytes;
+  uint32_t o_row_bytes;
+  int32_t N, n_groups, wave, hl, rb;
+};
+template <int D, bool LSE>
+__device__ __noinline__ void combine_slices(const CombineCall c, const u32x4 un, const u32x4 mu) {
+  const int ns = (int)un[2];
+  int32_t* const counter = c.counters + (int)mu[1] * PUREKV_WAVES + c.wave;
+  int claimed = 0;
+  if ((threadIdx.x & 63) == 0) {
+    int expected = ns;
+    claimed = __hip_atomic_compare_exchange_strong(counter, &expected, ns + 1, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (!__builtin_amdgcn_readfirstlane(claimed)) return;
+  asm volatile("" ::: "memory");
+  const int hq = (int)un[1] + c.hl, row0 = (int)un[0] + c.rb * 32;
+  int ln = threadIdx.x & 63;
+  asm volatile("" : "+v"(ln));
+  const uint32_t slice_rows = (uint32_t)c.n_groups * WG_ROWS;   // rows between consecutive slices' blocks
+  const float* const po = c.ws_o + ((size_t)mu[0] + c.wave * 32) * D;      // this wavefront's block in slice 0
+  const float* const pl = c.ws_lse + 2 * ((size_t)mu[0] + c.wave * 32);
+  LdsFloat* const Wt = c.xs;   // [32 rows][ns]{merge weight, exact log-sum-exp}: <= 8 KB
+  // (row, slice) pairs over the lanes: one round trip fetches every slice's two log-sum-exp values of every row
+  for (int pb = 0; pb < 32 * ns; pb += 64) {
+    const int pr = min(pb + ln, 32 * ns - 1), r = pr & 31, sl = pr >> 5;
+    const floatx2 l2 = load_device_8(make_rsrc(pl), ((uint32_t)sl * slice_rows + (uint32_t)r) * 8u);
+    *(LdsFloatx2*)(Wt + 2 * (r * ns + sl)) = l2;
+  }
+  {  // lane (n, h): row n (both halves compute the same): maxima, weights normalised to sum 1, exact log-sum-exp
+    const int n = ln & 31;
+    float mx = -INFINITY, mxx = -INFINITY;
+    for (int sl = 0; sl < ns; ++sl) {
+      const floatx2 l2 = *(const LdsFloatx2*)(Wt + 2 * (n * ns + sl));
+      mx = fmaxf(mx, l2[0]);
+      mxx = fmaxf(mxx, l2[1]);
+    }
+    float wsum = 0.f, xsum = 0.f;
+    for (int sl = 0; sl < ns; ++sl) {
+      const floatx2 l2 = *(const LdsFloatx2*)(Wt + 2 * (n * ns + sl));
+      wsum += __builtin_amdgcn_exp2f(l2[0] - mx);
+      xsum += __builtin_amdgcn_exp2f(l2[1] - mxx);
+    }
+    const float inv = 1.f / wsum;
+    for (int sl = 0; sl < ns; ++sl) {
+      const float wgt = __builtin_amdgcn_exp2f(Wt[2 * (n * ns + sl)] - mx) * inv;
+      if ((ln >> 5) == 0) Wt[2 * (n * ns + sl)] = wgt;
+    }
+    if (LSE && (ln >> 5) == 0 && row0 + n < c.N)
+      c.lse[(size_t)hq * c.N + row0 + n] = (mxx + __builtin_amdgcn_logf(xsum)) * kLn2;
+  }
+  // Weighted sum, PB 16-byte pieces (4 columns of one row each) per lane at a time, the pieces of up to four
+  // slices in flight together (the pipeline's registers are free here): what this costs is round trips to memory.
+  constexpr int CH = D / 4, NI = 32 * CH / 64, PB = 8;   // pieces per row; pieces per lane; pieces per batch
+  static_assert(NI % PB == 0, "batches cover the block");
+  char* const otile = reinterpret_cast<char*>(c.out) + (int64_t)hq * c.o_head_bytes + (int64_t)row0 * c.o_row_bytes;
+  const int rows_left = c.N - row0;
+#pragma unroll 1
+  for (int i0 = 0; i0 < NI; i0 += PB) {
+    floatx4 acc[PB];
+#pragma unroll
+    for (int i = 0; i < PB; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+    for (int s0 = 0; s0 < ns; s0 += 4) {
+      floatx4 x[4][PB];
+#pragma unroll
+      for (int ss = 0; ss < 4; ++ss) {
+        const int sl = min(s0 + ss, ns - 1);   // slices past the end repeat the last one (weight 0 below)
+        const BufferRsrc pbuf = make_rsrc(po + (size_t)sl * slice_rows * D);
+#pragma unroll
+        for (int i = 0; i < PB; ++i) x[ss][i] = load_device_16(pbuf, (uint32_t)((i0 + i) * 64 + ln) * 16u);
+      }
+#pragma unroll
+      for (int ss = 0; ss < 4; ++ss)
+#pragma unroll
+        for (int i = 0; i < PB; ++i) {
+          const int r = ((i0 + i) * 64 + ln) / CH;
+          const float wgt = s0 + ss < ns ? Wt[2 * (r * ns + min(s0 + ss, ns - 1))] : 0.f;
+          acc[i] += x[ss][i] * wgt;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+      const int r = ((i0 + i) * 64 + ln) / CH, c4 = ((i0 + i) * 64 + ln) % CH;
+      u32x2 w2;
+      w2[0] = pack_bf16(acc[i][0], acc[i][1]);
+      w2[1] = pack_bf16(acc[i][2], acc[i][3]);
+      if (r < rows_left) *reinterpret_cast<u32x2*>(otile + (uint32_t)r * c.o_row_bytes + 8 * c4) = w2;
+    }
+  }
+  if ((threadIdx.x & 63) == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+}
 
 // ST  = false: dense causal pattern only (block kinds full and causal); true: any pattern.
 // LSE = true : also keeps the exact fp32 row sum for the log-sum-exp output.
@@ -358,103 +478,6 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     const u32x4 mu = units_c[2 * u_unit + 1];   // {first workspace row of slice 0, counter, -, -}
     if (lane == 0)
       (void)__hip_atomic_fetch_add(a.counters + (int)mu[1] * PUREKV_WAVES + wave, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  };
-  // Combination, at the end of the workgroup's queue (the pipeline's registers are free then): for every slice this
-  // wavefront ran, a counter that stands at n_splits means "all slices in memory, nobody has combined them yet";
-  // whoever moves it to n_splits + 1 (compare-and-swap: exactly one wavefront can) adds the partial results up in a
-  // fixed order (slice 0, 1, ...: reproducible bit for bit), writes the output rows and leaves the counter at zero
-  // for the next launch.  The wavefront whose slice arrived last always finds n_splits or a combination already
-  // claimed when it gets here, so every split tile is combined exactly once before the launch ends, and nobody ever
-  // waits for anybody.  The planner runs the closing slice of a list last in its queue and the other slices first
-  // in theirs: the workgroup it charged for the combination is then normally the one that does it.  Partial results
-  // and counters travel as device-scope accesses (they bypass the L2 of the issuing XCD), ordered by "stores
-  // acknowledged -> counter increment ... counter read -> loads".
-  auto merge_owed = [&](const u32x4 un, const u32x4 mu) {
-    const int ns = (int)un[2];
-    int32_t* const counter = a.counters + (int)mu[1] * PUREKV_WAVES + wave;
-    int claimed = 0;
-    if (lane == 0) {
-      int expected = ns;
-      claimed = __hip_atomic_compare_exchange_strong(counter, &expected, ns + 1, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-    }
-    if (!__builtin_amdgcn_readfirstlane(claimed)) return;
-    asm volatile("" ::: "memory");
-    const int hq = (int)un[1] + hl, row0 = (int)un[0] + rb * 32;
-    int ln = lane;
-    asm volatile("" : "+v"(ln));
-    const uint32_t slice_rows = (uint32_t)a.n_groups * WG_ROWS;   // rows between consecutive slices' blocks
-    const float* const po = a.ws_o + ((size_t)mu[0] + wave * 32) * D;      // this wavefront's block in slice 0
-    const float* const pl = a.ws_lse + 2 * ((size_t)mu[0] + wave * 32);
-    float* const Wt = reinterpret_cast<float*>(Xs);   // [32 rows][ns]{merge weight, exact log-sum-exp}: <= 8 KB
-    // (row, slice) pairs over the lanes: one round trip fetches every slice's two log-sum-exp values of every row
-    for (int pb = 0; pb < 32 * ns; pb += 64) {
-      const int pr = min(pb + ln, 32 * ns - 1), r = pr & 31, sl = pr >> 5;
-      const floatx2 l2 = load_device_8(make_rsrc(pl), ((uint32_t)sl * slice_rows + (uint32_t)r) * 8u);
-      *reinterpret_cast<floatx2*>(Wt + 2 * (r * ns + sl)) = l2;
-    }
-    {  // lane (n, h): row n (both halves compute the same): maxima, weights normalised to sum 1, exact log-sum-exp
-      const int n = ln & 31;
-      float mx = -INFINITY, mxx = -INFINITY;
-      for (int sl = 0; sl < ns; ++sl) {
-        const floatx2 l2 = *reinterpret_cast<const floatx2*>(Wt + 2 * (n * ns + sl));
-        mx = fmaxf(mx, l2[0]);
-        mxx = fmaxf(mxx, l2[1]);
-      }
-      float wsum = 0.f, xsum = 0.f;
-      for (int sl = 0; sl < ns; ++sl) {
-        const floatx2 l2 = *reinterpret_cast<const floatx2*>(Wt + 2 * (n * ns + sl));
-        wsum += __builtin_amdgcn_exp2f(l2[0] - mx);
-        xsum += __builtin_amdgcn_exp2f(l2[1] - mxx);
-      }
-      const float inv = 1.f / wsum;
-      for (int sl = 0; sl < ns; ++sl) {
-        const float wgt = __builtin_amdgcn_exp2f(Wt[2 * (n * ns + sl)] - mx) * inv;
-        if ((ln >> 5) == 0) Wt[2 * (n * ns + sl)] = wgt;
-      }
-      if (LSE && (ln >> 5) == 0 && row0 + n < a.N)
-        a.lse[(size_t)hq * a.N + row0 + n] = (mxx + __builtin_amdgcn_logf(xsum)) * kLn2;
-    }
-    // Weighted sum, PB 16-byte pieces (4 columns of one row each) per lane at a time, the pieces of up to four
-    // slices in flight together (the pipeline's registers are free here): what this costs is round trips to memory.
-    constexpr int CH = D / 4, NI = 32 * CH / 64, PB = 8;   // pieces per row; pieces per lane; pieces per batch
-    static_assert(NI % PB == 0, "batches cover the block");
-    char* const otile = reinterpret_cast<char*>(a.out) + (int64_t)hq * a.o_head_bytes + (int64_t)row0 * a.o_row_bytes;
-    const int rows_left = a.N - row0;
-#pragma unroll 1
-    for (int i0 = 0; i0 < NI; i0 += PB) {
-      floatx4 acc[PB];
-#pragma unroll
-      for (int i = 0; i < PB; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-      for (int s0 = 0; s0 < ns; s0 += 4) {
-        floatx4 x[4][PB];
-#pragma unroll
-        for (int ss = 0; ss < 4; ++ss) {
-          const int sl = min(s0 + ss, ns - 1);   // slices past the end repeat the last one (weight 0 below)
-          const BufferRsrc pbuf = make_rsrc(po + (size_t)sl * slice_rows * D);
-#pragma unroll
-          for (int i = 0; i < PB; ++i) x[ss][i] = load_device_16(pbuf, (uint32_t)((i0 + i) * 64 + ln) * 16u);
-        }
-#pragma unroll
-        for (int ss = 0; ss < 4; ++ss)
-#pragma unroll
-          for (int i = 0; i < PB; ++i) {
-            const int r = ((i0 + i) * 64 + ln) / CH;
-            const float wgt = s0 + ss < ns ? Wt[2 * (r * ns + min(s0 + ss, ns - 1))] : 0.f;
-            acc[i] += x[ss][i] * wgt;
-          }
-      }
-#pragma unroll
-      for (int i = 0; i < PB; ++i) {
-        const int r = ((i0 + i) * 64 + ln) / CH, c4 = ((i0 + i) * 64 + ln) % CH;
-        u32x2 w2;
-        w2[0] = pack_bf16(acc[i][0], acc[i][1]);
-        w2[1] = pack_bf16(acc[i][2], acc[i][3]);
-        if (r < rows_left) *reinterpret_cast<u32x2*>(otile + (uint32_t)r * a.o_row_bytes + 8 * c4) = w2;
-      }
-    }
-    if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
   };
   // Finish of a unit that holds a whole key list: normalise, round, stage, store.
   auto finish_unit = [&]() {
@@ -832,7 +855,23 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
     const int u_end = a.queue_unit0[blockIdx.x + 1];
     for (int u = a.queue_unit0[blockIdx.x]; u < u_end; ++u) {
       const u32x4 un = units_c[2 * u];
-      if ((int)un[2] > 1) merge_owed(un, units_c[2 * u + 1]);
+      if ((int)un[2] > 1) {
+        CombineCall cc;
+        cc.counters = a.counters;
+        cc.ws_o = a.ws_o;
+        cc.ws_lse = a.ws_lse;
+        cc.out = a.out;
+        cc.lse = a.lse;
+        cc.xs = (LdsFloat*)reinterpret_cast<float*>(Xs);
+        cc.o_head_bytes = a.o_head_bytes;
+        cc.o_row_bytes = a.o_row_bytes;
+        cc.N = a.N;
+        cc.n_groups = a.n_groups;
+        cc.wave = wave;
+        cc.hl = hl;
+        cc.rb = rb;
+        combine_slices<D, LSE>(cc, un, units_c[2 * u + 1]);
+      }
     }
   }
 }
