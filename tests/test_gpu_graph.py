@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 
 
 def test_captured_step_replays_bit_exactly():
-    # 7 stacked heads, text rows split into slices (the merge kernel runs), decode spans several chunks
+    # 7 stacked heads, text rows split into slices (combined inside the launch), decode spans several chunks
     wl = small_variant("graph_3f", n_frames=3, patch_h=10, patch_w=10, n_text=900, n_q_heads=7, n_kv_heads=1,
                        head_dim=128)
     n, w, d, hq, hkv = wl.n_tokens, 64, wl.head_dim, wl.n_q_heads, wl.n_kv_heads

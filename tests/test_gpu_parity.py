@@ -453,7 +453,7 @@ def test_tile_step_skeleton_runs(rows):
 
 
 @pytest.mark.parametrize("name,patterns", [
-    ("longtext_2f", [3, 1]),                         # split text rows: the merge kernel must skip the other head
+    ("longtext_2f", [3, 1]),                         # split text rows: the combination must leave the other head alone
     ("heads7_3f", [1, 2, 1, 2, 3, 3, 0]),            # all four patterns inside one KV group
     ("heads3_4f", [2, 2, 1, 1, 1, 2]),               # d = 64, two KV heads
     ("heads3_4f", [1, 1, 1, 3, 3, 3]),               # whole KV groups: the subset plans keep the stacked shape
