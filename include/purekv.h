@@ -153,6 +153,14 @@ PUREKV_API int purekv_plan_item(const purekv_plan_t* plan, int32_t it, int32_t i
 /* Copies the units of persistent workgroup `wg`, in execution order, into units[0 .. 2*cap): pairs {work
  * item, first query head of the group}.  Returns the number of units (may exceed cap) or a negative status. */
 PUREKV_API int purekv_plan_queue(const purekv_plan_t* plan, int32_t wg, int32_t* units, int32_t cap);
+/* Copies the steps of persistent workgroup `wg`, in execution order, into steps[0 .. 4*cap): one record of four
+ * values per step: {byte offset of the key tile's first row in K and V, need bits | last << 16 | first << 17 |
+ * (rows of the tile that exist - 1) << 18 | owner << 24, kind bits, first key of the tile}.  A step stages one key
+ * tile of its unit's list (Sec. 3.2: the lists are the pattern's block indices); `first` / `last` mark the ends of a
+ * unit, units follow each other in the order purekv_plan_queue reports; `owner` marks the one step of the launch
+ * that also emits the squared norms of the tile's V rows.  Returns the number of steps (may exceed cap) or a
+ * negative status. */
+PUREKV_API int purekv_plan_steps(const purekv_plan_t* plan, int32_t wg, int32_t* steps, int32_t cap);
 
 /* Device workspace bytes needed by `op` for this plan.  `n_layers`, `w` and `cap` are read by the ops
  * that take them (TOPK: n_layers, w; DECODE: cap); pass 0 otherwise.  What lives there: PREFILL, the partial

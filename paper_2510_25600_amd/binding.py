@@ -59,6 +59,7 @@ def _load() -> ctypes.CDLL:
         "purekv_plan_qtile_list": (c_int, [P, c_int32, POINTER(c_int32), c_int32]),
         "purekv_plan_item": (c_int, [P, c_int32, POINTER(c_int32)]),
         "purekv_plan_queue": (c_int, [P, c_int32, POINTER(c_int32), c_int32]),
+        "purekv_plan_steps": (c_int, [P, c_int32, POINTER(c_int32), c_int32]),
         "purekv_workspace_bytes": (c_size_t, [P, c_int, c_int32, c_int32, c_int32]),
         "purekv_workspace_init": (c_int, [P, c_int, P, c_size_t, c_int32, c_int32, c_int32, P]),
         "purekv_stack_workspace_init": (c_int, [P, P, P, P, c_size_t, P]),
@@ -95,7 +96,7 @@ _lib = _load()
 EXPORTS = (
     "purekv_plan_create", "purekv_plan_create_host", "purekv_plan_destroy", "purekv_plan_create_heads",
     "purekv_plan_create_heads_host", "purekv_plan_counts",
-    "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_workspace_bytes", "purekv_workspace_init",
+    "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_plan_steps", "purekv_workspace_bytes", "purekv_workspace_init",
     "purekv_stack_workspace_init", "purekv_st_spattn_prefill", "purekv_st_spattn_prefill_vnorm", "purekv_topk_select_vnorm",
     "purekv_lowlayer_importance", "purekv_topk_select", "purekv_topk_select_static", "purekv_kv_compact", "purekv_kv_append",
     "purekv_decode_attn", "purekv_decode_step", "purekv_stack_workspace_bytes", "purekv_stack_layer",
@@ -237,6 +238,16 @@ class Plan:
         buf = (c_int32 * max(2 * n, 1))()
         _lib.purekv_plan_queue(self._h, wg, buf, n)
         return [(buf[2 * i], buf[2 * i + 1]) for i in range(n)]
+
+    def steps(self, wg: int) -> list:
+        """Steps of persistent workgroup `wg`, in order: (kv_off, need | flags, kinds, k0) each."""
+        n = _lib.purekv_plan_steps(self._h, wg, None, 0)
+        if n < 0:
+            raise PureKVError(n, "purekv_plan_steps")
+        buf = (c_int32 * max(4 * n, 1))()
+        _lib.purekv_plan_steps(self._h, wg, buf, n)
+        return [(buf[4 * i] & 0xFFFFFFFF, buf[4 * i + 1] & 0xFFFFFFFF, buf[4 * i + 2] & 0xFFFFFFFF, buf[4 * i + 3])
+                for i in range(n)]
 
     def item(self, it: int) -> Tuple[int, ...]:
         buf = (c_int32 * 6)()

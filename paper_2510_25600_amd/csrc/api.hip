@@ -208,6 +208,17 @@ int purekv_plan_queue(const purekv_plan_t* p, int32_t wg, int32_t* units, int32_
   return len;
 }
 
+int purekv_plan_steps(const purekv_plan_t* p, int32_t wg, int32_t* steps, int32_t cap) {
+  if (p == nullptr || wg < 0 || wg >= p->n_queues || cap < 0 || (cap > 0 && steps == nullptr)) return PUREKV_EINVAL;
+  const int32_t b = p->queue_begin[wg], len = p->queue_begin[wg + 1] - b;
+  for (int32_t i = 0; i < len && i < cap; ++i) {
+    const StreamEntry& e = p->stream[b + i];
+    const int32_t rec[4] = {(int32_t)e.kv_off, (int32_t)e.need, (int32_t)e.kinds, e.k0};
+    for (int k = 0; k < 4; ++k) steps[4 * i + k] = rec[k];
+  }
+  return len;
+}
+
 int purekv_plan_item(const purekv_plan_t* p, int32_t it, int32_t item[6]) {
   if (p == nullptr || item == nullptr || it < 0 || it >= (int32_t)p->items.size()) return PUREKV_EINVAL;
   const WorkItem& w = p->items[it];

@@ -109,6 +109,20 @@ static void inspect(purekv_plan_t* p, const purekv_shape_t& s, int n_wg, const u
   CHECK((int64_t)seen.size() == n_items * groups_sel);
   for (const auto& kv : seen) CHECK(kv.second == 1);
   CHECK(purekv_plan_queue(p, (int32_t)n_queues, nullptr, 0) == PUREKV_EINVAL);
+  // steps: one record of four values each; a short buffer receives only what fits
+  std::vector<int32_t> steps;
+  for (int64_t q = 0; q < n_queues; ++q) {
+    const int len = purekv_plan_steps(p, (int32_t)q, nullptr, 0);
+    CHECK(len >= 1);
+    steps.assign(4 * (size_t)len, -1);
+    CHECK(purekv_plan_steps(p, (int32_t)q, steps.data(), len) == len);
+    CHECK(((steps[1] >> 17) & 1) == 1 && ((steps[4 * (size_t)(len - 1) + 1] >> 16) & 1) == 1);
+    for (int i = 0; i < len; ++i) CHECK(steps[4 * (size_t)i + 3] >= 0 && steps[4 * (size_t)i + 3] < n);
+    int32_t one[4] = {-7, -7, -7, -7};
+    CHECK(purekv_plan_steps(p, (int32_t)q, one, 1) == len && one[3] == steps[3]);
+  }
+  CHECK(purekv_plan_steps(p, (int32_t)n_queues, nullptr, 0) == PUREKV_EINVAL && purekv_plan_steps(p, -1, nullptr, 0) == PUREKV_EINVAL);
+  CHECK(purekv_plan_steps(p, 0, nullptr, 1) == PUREKV_EINVAL);
   // sizes and counts the callers allocate by
   for (int op = -1; op <= 5; ++op)
     for (int32_t layers : {0, 1, 26})

@@ -223,10 +223,49 @@ def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern, n_wg=256):
         classes = [order_class(i) for i, _ in plan.queue(q)]
         assert classes == sorted(classes), (q, classes)
     assert all(it[4] <= 32 for it in items)   # slices per list: what the combining wavefront's LDS table holds
+    _check_steps_against_lists(plan, c, items, hq, hkv, d, n, R, gs)
     loads = [sum(items[i][2] for i, _ in plan.queue(q)) for q in range(c["n_workgroups"])]
     if len(units) >= 4 * c["n_workgroups"]:
         assert max(loads) <= 1.5 * (sum(loads) / len(loads)) + max(it[2] for it in items)
     plan.close()
+
+
+def _check_steps_against_lists(plan, c, items, hq, hkv, d, n, R, gs, kv_strides=None):
+    """The steps a workgroup executes against the lists they were made from: every unit runs, once and in order, the
+    tiles of its slice of its query tile's list, with the addresses, first/last marks and row counts the kernel relies
+    on, and every (KV head, key tile) has exactly one owner step."""
+    g = hq // hkv
+    kv_sh, kv_st = kv_strides if kv_strides else (n * d, d)
+    owners = set()
+    for q in range(c["n_workgroups"]):
+        steps = plan.steps(q)
+        pos = 0
+        for it, head0 in plan.queue(q):
+            qt, lb, nt, sp, ns, slot = items[it]
+            kvh = head0 // g
+            first_pos = lb - _list_begin(plan, c, qt)
+            want = plan.qtile_list(qt)[first_pos:first_pos + nt]
+            for i, (t, need, kinds) in enumerate(want):
+                kv_off, flags, got_kinds, k0 = steps[pos + i]
+                assert k0 == t * pk.BK and kv_off == ((kvh * kv_sh + k0 * kv_st) * 2) % 2**32
+                assert flags & 0xFFFF == need and got_kinds == kinds
+                assert (flags >> 17) & 1 == (i == 0) and (flags >> 16) & 1 == (i == nt - 1)
+                assert ((flags >> 18) & 63) + 1 == min(pk.BK, n - k0)
+                if (flags >> 24) & 1:
+                    assert (kvh, t) not in owners
+                    owners.add((kvh, t))
+            pos += nt
+        assert pos == len(steps), q
+    n_ktiles = (n + pk.BK - 1) // pk.BK
+    heads_run = sorted({h0 // g for q in range(c["n_workgroups"]) for _, h0 in plan.queue(q)})
+    assert sorted(owners) == [(kvh, t) for kvh in heads_run for t in range(n_ktiles)]
+
+
+def _list_begin(plan, c, qt):
+    """First position of query tile qt's list in the flat tile list (work items address lists by flat position)."""
+    if not hasattr(plan, "_list_begin"):
+        plan._list_begin = np.concatenate([[0], np.cumsum([len(plan.qtile_list(q)) for q in range(c["n_qtiles"])])])
+    return int(plan._list_begin[qt])
 
 
 @pytest.mark.parametrize("pattern", [0, 1, 2, 3])
