@@ -271,13 +271,14 @@ def main() -> int:
         q0, k0, v0 = fuse(q0, k0, v0)
         q1, k1, v1 = fuse(q1, k1, v1)
         strides = dict(q_strides=(d, row), kv_strides=(d, row), o_strides=(d, hq * d))
-        dense = pk.Plan.for_workload(wl, pk.PATTERN_DENSE, **strides)
+        dense = pk.Plan.for_workload(wl, pk.PATTERN_DENSE, lse_window=w, **strides)
         st = pk.Plan.for_workload(wl, pk.PATTERN_ST, **strides)
         out0, out1 = dense.empty_out(dev), st.empty_out(dev)
         layout = f"token-major: Q, K, V views of one [N, {row}] buffer (head stride {d}, token stride {row}), O [N, {hq * d}]"
     else:
         v1_packed, k1_packed = v1, k1
-        dense = pk.Plan.for_workload(wl, pk.PATTERN_DENSE)
+        # the designated low layer: a window plan (Eq. 2 reads the log-sum-exp of the last w rows only)
+        dense = pk.Plan.for_workload(wl, pk.PATTERN_DENSE, lse_window=w)
         st = st_packed
         out0, out1 = torch.empty_like(q0), torch.empty_like(q1)
         layout = "packed [H, N, d] (head stride N*d, token stride d)"
@@ -558,6 +559,7 @@ def main() -> int:
         "mask_tflops": round(mask_flops / (st_call_ms * 1e-3) / 1e12, 2),
         "dense_prefill_ms_per_layer": round(dense_ms, 4),
         "dense_prefill_tflops": round(dense_kept / (dense_ms * 1e-3) / 1e12, 2),
+        "dense_prefill_lse": f"last {w} rows (window plan: workgroups {dense.counts()['lse_queue0']}..255 keep the exact row sum)",
         "stage_ms_in_step": {k_: round(v_, 4) for k_, v_ in stage_ms.items()},
         "per_layer_gbps": {
             "topk": round(topk_bytes / (stage_ms["topk_high"] * 1e-3) / 1e9, 1),

@@ -137,11 +137,23 @@ PUREKV_API int purekv_plan_create_heads(const purekv_shape_t* shape, const uint8
 PUREKV_API int purekv_plan_create_heads_host(const purekv_shape_t* shape, const uint8_t* head_mask, int32_t n_workgroups,
                                              purekv_plan_t** out);
 
+/* Window plans, for the designated low layer (Sec. 3.1): Eq. 2 reads the attention probabilities of the last w
+ * query rows only (the recent window), so only those rows' log-sum-exp is needed from the prefill.  On such a plan
+ * a prefill call with `lse` given writes lse[h, i] for i >= N - w only and leaves every other element of `lse`
+ * untouched, and only the workgroups that own those rows carry the exact row sum through their tile loop (it costs
+ * the loop about 8 %); everything else -- outputs, workspaces, every other call -- is as for purekv_plan_create.
+ * purekv_lowlayer_importance on such a plan refuses a window larger than w (PUREKV_EINVAL).  1 <= w <= N, else
+ * PUREKV_EINVAL. */
+PUREKV_API int purekv_plan_create_window(const purekv_shape_t* shape, int32_t w, purekv_plan_t** out, void* stream);
+PUREKV_API int purekv_plan_create_window_host(const purekv_shape_t* shape, int32_t w, int32_t n_workgroups,
+                                              purekv_plan_t** out);
+
 /* Plan inspection (host memory).  counts[0..15] = N, number of query tiles, number of work items,
  * number of (query tile, key tile) references, number of (row block, 32-key block) pairs computed per
  * query head, number of query tiles whose list is split, number of persistent workgroups, R (row blocks
  * per query tile), Gs (stacked heads), number of head groups (Hq / Gs), then the computed pairs by kind
- * (full, causal, prev, general), then two zeros. */
+ * (full, causal, prev, general), then the window w of a window plan (0 for any other plan) and the first persistent
+ * workgroup of those that own the window's rows (0 when the plan is not divided). */
 PUREKV_API int purekv_plan_counts(const purekv_plan_t* plan, int64_t counts[16]);
 /* Copies the key-tile list of query tile `qt` into refs[0 .. 3*cap): triples {key tile index, need bits,
  * kind bits}.  Returns the list length (may exceed cap; then only cap triples are written) or a negative

@@ -55,6 +55,8 @@ def _load() -> ctypes.CDLL:
         "purekv_plan_destroy": (c_int, [P]),
         "purekv_plan_create_heads": (c_int, [POINTER(Shape), P, POINTER(c_void_p), P]),
         "purekv_plan_create_heads_host": (c_int, [POINTER(Shape), P, c_int32, POINTER(c_void_p)]),
+        "purekv_plan_create_window": (c_int, [POINTER(Shape), c_int32, POINTER(c_void_p), P]),
+        "purekv_plan_create_window_host": (c_int, [POINTER(Shape), c_int32, c_int32, POINTER(c_void_p)]),
         "purekv_plan_counts": (c_int, [P, POINTER(c_int64)]),
         "purekv_plan_qtile_list": (c_int, [P, c_int32, POINTER(c_int32), c_int32]),
         "purekv_plan_item": (c_int, [P, c_int32, POINTER(c_int32)]),
@@ -95,7 +97,7 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 EXPORTS = (
     "purekv_plan_create", "purekv_plan_create_host", "purekv_plan_destroy", "purekv_plan_create_heads",
-    "purekv_plan_create_heads_host", "purekv_plan_counts",
+    "purekv_plan_create_heads_host", "purekv_plan_create_window", "purekv_plan_create_window_host", "purekv_plan_counts",
     "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_plan_steps", "purekv_workspace_bytes", "purekv_workspace_init",
     "purekv_stack_workspace_init", "purekv_st_spattn_prefill", "purekv_st_spattn_prefill_vnorm", "purekv_topk_select_vnorm",
     "purekv_lowlayer_importance", "purekv_topk_select", "purekv_topk_select_static", "purekv_kv_compact", "purekv_kv_append",
@@ -154,15 +156,26 @@ class Plan:
     def __init__(self, n_frames: int, patch_h: int, patch_w: int, n_text: int, n_q_heads: int, n_kv_heads: int,
                  head_dim: int, pattern: int = PATTERN_ST, softmax_scale: float = 0.0, host_only: bool = False,
                  n_workgroups: int = 256, head_mask=None, q_strides: Tuple[int, int] = (0, 0),
-                 kv_strides: Tuple[int, int] = (0, 0), o_strides: Tuple[int, int] = (0, 0)):
+                 kv_strides: Tuple[int, int] = (0, 0), o_strides: Tuple[int, int] = (0, 0), lse_window: int = 0):
         """head_mask: optional sequence of n_q_heads truth values: the plan covers those query heads only.
+        lse_window: w > 0 makes a window plan (the prefill writes the log-sum-exp of the last w rows only).
         q_strides, kv_strides, o_strides: (head stride, token stride) in elements of Q, of K and V, of O;
         (0, 0) = packed [H, N, d]."""
         self.shape = Shape(n_frames, patch_h, patch_w, n_text, n_q_heads, n_kv_heads, head_dim, pattern,
                            softmax_scale, q_strides[0], q_strides[1], kv_strides[0], kv_strides[1],
                            o_strides[0], o_strides[1])
         self._h = c_void_p()
-        if head_mask is not None:
+        self.lse_window = lse_window
+        if lse_window and head_mask is not None:
+            raise ValueError("a window plan covers every head")
+        if lse_window:
+            if host_only:
+                _check(_lib.purekv_plan_create_window_host(byref(self.shape), lse_window, n_workgroups, byref(self._h)),
+                       "purekv_plan_create_window_host")
+            else:
+                _check(_lib.purekv_plan_create_window(byref(self.shape), lse_window, byref(self._h), _stream()),
+                       "purekv_plan_create_window")
+        elif head_mask is not None:
             if len(head_mask) != n_q_heads:
                 raise ValueError("head_mask needs one entry per query head")
             hm = (ctypes.c_uint8 * n_q_heads)(*[1 if x else 0 for x in head_mask])
@@ -187,9 +200,9 @@ class Plan:
 
     @classmethod
     def for_workload(cls, wl, pattern: int = PATTERN_ST, host_only: bool = False, n_workgroups: int = 256,
-                     **strides) -> "Plan":
+                     **more) -> "Plan":
         return cls(wl.n_frames, wl.patch_h, wl.patch_w, wl.n_text, wl.n_q_heads, wl.n_kv_heads, wl.head_dim,
-                   pattern, 0.0, host_only, n_workgroups, **strides)
+                   pattern, 0.0, host_only, n_workgroups, **more)
 
     def empty_out(self, device) -> torch.Tensor:
         """An output tensor laid out by the plan's O strides, as a (Hq, N, d) view."""
@@ -219,7 +232,8 @@ class Plan:
         _check(_lib.purekv_plan_counts(self._h, c), "purekv_plan_counts")
         return dict(N=c[0], n_qtiles=c[1], n_items=c[2], n_tile_refs=c[3], n_blocks=c[4], n_split_qtiles=c[5],
                     n_workgroups=c[6], row_blocks=c[7], stacked_heads=c[8], n_head_groups=c[9],
-                    n_full_blocks=c[10], n_causal_blocks=c[11], n_prev_blocks=c[12], n_general_blocks=c[13])
+                    n_full_blocks=c[10], n_causal_blocks=c[11], n_prev_blocks=c[12], n_general_blocks=c[13],
+                    lse_window=c[14], lse_queue0=c[15])
 
     def qtile_list(self, qt: int) -> list:
         """[(key tile, need bits, kind bits)] of query tile `qt`: need bit 2*rb + kb, kind bits 4*rb + 2*kb."""

@@ -51,10 +51,12 @@ static int check_shape(const purekv_shape_t* s) {
   return rc;
 }
 
-static int make_plan(const purekv_shape_t* s, purekv_plan_t** out, int n_cu, const uint8_t* head_mask = nullptr) {
+static int make_plan(const purekv_shape_t* s, purekv_plan_t** out, int n_cu, const uint8_t* head_mask = nullptr,
+                     int32_t lse_rows = 0) {
   if (out == nullptr) return PUREKV_EINVAL;
   const int rc = check_shape(s);
   if (rc != PUREKV_OK) return rc;
+  if (lse_rows < 0 || lse_rows > (int64_t)s->patch_h * s->patch_w * s->n_frames + s->n_text) return PUREKV_EINVAL;
   if (head_mask != nullptr) {   // at least one head
     bool any = false;
     for (int32_t hq = 0; hq < s->n_q_heads; ++hq) any |= head_mask[hq] != 0;
@@ -68,6 +70,7 @@ static int make_plan(const purekv_shape_t* s, purekv_plan_t** out, int n_cu, con
     delete p;
     return PUREKV_ENOMEM;
   }
+  p->lse_rows = lse_rows;
   Geometry& g = p->g;
   g.F = s->n_frames;
   g.P = s->patch_h * s->patch_w;
@@ -106,15 +109,26 @@ int purekv_plan_create_host(const purekv_shape_t* shape, int32_t n_workgroups, p
   return make_plan(shape, out, n_workgroups);
 }
 
-static int create_on_device(const purekv_shape_t* shape, const uint8_t* head_mask, purekv_plan_t** out, void* stream);
+static int create_on_device(const purekv_shape_t* shape, const uint8_t* head_mask, int32_t lse_rows, purekv_plan_t** out,
+                            void* stream);
 
 int purekv_plan_create(const purekv_shape_t* shape, purekv_plan_t** out, void* stream) {
-  return create_on_device(shape, nullptr, out, stream);
+  return create_on_device(shape, nullptr, 0, out, stream);
+}
+
+int purekv_plan_create_window(const purekv_shape_t* shape, int32_t w, purekv_plan_t** out, void* stream) {
+  if (w < 1) return PUREKV_EINVAL;
+  return create_on_device(shape, nullptr, w, out, stream);
+}
+
+int purekv_plan_create_window_host(const purekv_shape_t* shape, int32_t w, int32_t n_workgroups, purekv_plan_t** out) {
+  if (w < 1 || n_workgroups < 1 || n_workgroups > 65536) return PUREKV_EINVAL;
+  return make_plan(shape, out, n_workgroups, nullptr, w);
 }
 
 int purekv_plan_create_heads(const purekv_shape_t* shape, const uint8_t* head_mask, purekv_plan_t** out, void* stream) {
   if (head_mask == nullptr) return PUREKV_EINVAL;
-  return create_on_device(shape, head_mask, out, stream);
+  return create_on_device(shape, head_mask, 0, out, stream);
 }
 
 int purekv_plan_create_heads_host(const purekv_shape_t* shape, const uint8_t* head_mask, int32_t n_workgroups,
@@ -123,7 +137,8 @@ int purekv_plan_create_heads_host(const purekv_shape_t* shape, const uint8_t* he
   return make_plan(shape, out, n_workgroups, head_mask);
 }
 
-static int create_on_device(const purekv_shape_t* shape, const uint8_t* head_mask, purekv_plan_t** out, void* stream) {
+static int create_on_device(const purekv_shape_t* shape, const uint8_t* head_mask, int32_t lse_rows, purekv_plan_t** out,
+                            void* stream) {
   if (out == nullptr) return PUREKV_EINVAL;
   int rc = check_shape(shape);
   if (rc != PUREKV_OK) return rc;
@@ -131,7 +146,7 @@ static int create_on_device(const purekv_shape_t* shape, const uint8_t* head_mas
   PUREKV_HIP_TRY(hipGetDevice(&dev));
   PUREKV_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
   purekv_plan_t* p = nullptr;
-  rc = make_plan(shape, &p, n_cu > 0 ? n_cu : 256, head_mask);
+  rc = make_plan(shape, &p, n_cu > 0 ? n_cu : 256, head_mask, lse_rows);
   if (rc != PUREKV_OK) return rc;
   p->device = dev;
   rc = static_score_buffer(dev, &p->d_static_scores);
@@ -183,7 +198,8 @@ int purekv_plan_counts(const purekv_plan_t* p, int64_t counts[16]) {
   counts[8] = p->g.Gs;
   counts[9] = p->g.n_groups;
   for (int k = 0; k < 4; ++k) counts[10 + k] = p->n_kind[k];
-  counts[14] = counts[15] = 0;
+  counts[14] = p->lse_rows;
+  counts[15] = p->lse_queue0;
   return PUREKV_OK;
 }
 
@@ -306,6 +322,7 @@ int purekv_lowlayer_importance(const purekv_plan_t* p, const void* q, const void
   (void)ws_bytes;
   if (!launchable(p) || q == nullptr || k == nullptr || lse == nullptr) return PUREKV_EINVAL;
   if (w < 1 || w > p->g.N) return PUREKV_EINVAL;
+  if (p->lse_rows > 0 && w > p->lse_rows) return PUREKV_EINVAL;   // a window plan's prefill wrote fewer rows of lse
   if (c_out == nullptr && w < p->g.N) return PUREKV_EINVAL;
   return launch_importance(*p, q, k, lse, w, c_out, static_cast<hipStream_t>(stream));
 }

@@ -5,6 +5,7 @@
 #include "plan.h"
 
 #include <algorithm>
+#include <cmath>
 #include <cstddef>
 #include <numeric>
 #include <utility>
@@ -192,6 +193,65 @@ void build_plan(purekv_plan& p, int n_cu) {
   // Slice length: 0.8 of the average load of a workgroup (measured on the 32-frame benchmark shape: shorter
   // slices balance no better after the refinement pass below and double the partial results to merge).
   const int32_t chunk = std::max<int32_t>(8, static_cast<int32_t>(0.8 * total_steps / std::max(1, n_cu) + 0.5));
+
+  // ---- window plans: the query tiles whose rows want the log-sum-exp get workgroups of their own ----
+  // Only the last lse_rows rows are asked for their log-sum-exp (the recent window of Eq. 2).  Keeping the exact row
+  // sum costs the tile loop about 8 % (two more vector instructions per pair of scores), so the query tiles that
+  // hold such rows ("window tiles") are dealt to a set of workgroups of their own, sized by their share of the work,
+  // and only those workgroups run the variant of the loop that keeps the sum.  A set of few workgroups needs units
+  // small enough to be balanced over it: the window tiles' lists are cut into the number of slices that minimises an
+  // estimate of the set's longest queue (equal units dealt evenly, a unit switch per unit, the combination charged
+  // to the queue that closes a list), and the set is made large enough not to be the last to finish.
+  auto window_tile = [&](int32_t qt) {
+    return p.lse_rows > 0 && int64_t(qt + 1) * rows_per_qtile > int64_t(g.N) - p.lse_rows;
+  };
+  // measured on the 32-frame benchmark shape: a step that keeps the exact sum takes 1.10 of one that does not; a
+  // slice costs its workgroup about three steps more than a whole list does (partial result through to memory,
+  // arrival, the look at its list's counter at the end of the queue), on top of the combination itself
+  constexpr double kExactSumCost = 1.10, kSliceCost = 3.0;
+  int32_t n_window_queues = 0, window_slices = 1;
+  {
+    double steps_w = 0;
+    int64_t lists_w = 0;
+    int32_t shortest = INT32_MAX;
+    for (int32_t qt = 0; qt < p.n_qtiles; ++qt)
+      if (window_tile(qt)) {
+        const int32_t len = p.qtile_begin[qt + 1] - p.qtile_begin[qt];
+        steps_w += len;
+        ++lists_w;
+        shortest = std::min(shortest, len);
+      }
+    const double cost_w = kExactSumCost * steps_w * n_groups_sel, cost_rest = (double(p.tiles.size()) - steps_w) * n_groups_sel;
+    // (not when the window tiles are a large share of the work -- text rows under a sparse pattern: units cut fine
+    // enough to balance a large set pay more in unit switches and combinations than the other set saves)
+    if (lists_w > 0 && 4 * cost_w <= cost_w + cost_rest && n_cu >= 2 &&
+        (p.n_qtiles - lists_w) * int64_t(n_groups_sel) >= n_cu) {
+      const int64_t units_w = lists_w * n_groups_sel, units_rest = (p.n_qtiles - lists_w) * int64_t(n_groups_sel);
+      const double len = steps_w / double(lists_w);
+      // longest queue of a set of nq workgroups, and the number of slices per list that gives it
+      auto window_set = [&](int32_t nq, int32_t& slices) {
+        double best = 0;
+        for (int32_t ns = 1; ns <= std::min<int32_t>(kMaxSplits, std::max(1, shortest / 8)); ++ns) {
+          const int64_t per_queue = (units_w * ns + nq - 1) / nq;
+          const double longest = double(per_queue) * (len / ns + kUnitCost + (ns > 1 ? kSliceCost : 0.0)) +
+                                 (ns > 1 ? kMergeCostPerSlice * ns : 0.0);
+          if (ns == 1 || longest < best) best = longest, slices = ns;
+        }
+        return kExactSumCost * best;
+      };
+      auto rest_set = [&](int32_t nq) { return (cost_rest + kUnitCost * double(units_rest)) / double(n_cu - nq); };
+      // smallest set, from the window tiles' share of the work on, whose longest queue ends no later than the
+      // other set's average one; failing that, the size with the smallest later end of the two
+      const int32_t nq0 = std::max<int32_t>(1, static_cast<int32_t>(cost_w / (cost_w + cost_rest) * n_cu));
+      double best_end = 0;
+      for (int32_t nq = nq0; nq <= std::min<int32_t>(n_cu - 1, 2 * nq0 + 8); ++nq) {
+        int32_t slices = 1;
+        const double end_w = window_set(nq, slices), end_r = rest_set(nq), end = std::max(end_w, end_r);
+        if (n_window_queues == 0 || end < best_end) best_end = end, n_window_queues = nq, window_slices = slices;
+        if (end_w <= end_r) break;
+      }
+    }
+  }
   p.items.clear();
   p.merges.clear();
   p.n_slots = 0;
@@ -199,6 +259,7 @@ void build_plan(purekv_plan& p, int n_cu) {
     const int32_t b = p.qtile_begin[qt], len = p.qtile_begin[qt + 1] - b;
     int32_t ns = 1;
     if (2 * len > 3 * chunk) ns = std::min<int32_t>((len + chunk - 1) / chunk, kMaxSplits);
+    if (n_window_queues > 0 && window_tile(qt)) ns = std::min(window_slices, std::max(1, len / 8));
     if (ns == 1) {
       p.items.push_back({qt, b, len, 0, 1, -1});
       continue;
@@ -228,77 +289,97 @@ void build_plan(purekv_plan& p, int n_cu) {
   // KV head stay on a fixed set of XCDs so that each L2 holds the K/V of few KV heads.
   const int64_t n_units = int64_t(p.items.size()) * n_groups_sel;
   p.n_queues = static_cast<int32_t>(std::min<int64_t>(std::max(1, n_cu), std::max<int64_t>(1, n_units)));
+  auto item_class = [&](int32_t it) { return (n_window_queues > 0 && window_tile(p.items[it].qtile)) ? 1 : 0; };
+  if (n_window_queues > 0) {
+    int64_t units_w = 0;
+    for (size_t it = 0; it < p.items.size(); ++it) units_w += item_class(static_cast<int32_t>(it)) * n_groups_sel;
+    n_window_queues = static_cast<int32_t>(std::min<int64_t>(n_window_queues, units_w));
+  }
+  // queues [0, lse_queue0): units of the other tiles; [lse_queue0, n_queues): units of the window tiles.  A plan
+  // without a window keeps one class: every workgroup keeps the exact sum when the log-sum-exp is asked for.
+  p.lse_queue0 = n_window_queues > 0 ? p.n_queues - n_window_queues : 0;
   // (not for a head subset: its KV heads may be few, and every queue has to receive a unit)
   const bool affinity = p.head_sel.empty() && (p.n_queues % 8 == 0) && (g.Hkv % 8 == 0 || 8 % g.Hkv == 0);
-  auto allowed = [&](int32_t q, int32_t kvh) {
-    if (!affinity) return true;
-    const int32_t x = q % 8;
-    return (g.Hkv >= 8) ? (x == kvh % 8) : (x % g.Hkv == kvh);
-  };
   std::vector<std::vector<int32_t>> queues(p.n_queues);  // flat (item, group) pairs
   std::vector<double> load(p.n_queues, 0.0);
-  for (size_t it = 0; it < p.items.size(); ++it) {
-    for (int32_t grp = 0; grp < g.n_groups; ++grp) {
-      if (!group_selected(grp)) continue;
-      const int32_t kvh = grp * g.Gs / g.G;
-      int32_t best = -1;
-      for (int32_t q = 0; q < p.n_queues; ++q)
-        if (allowed(q, kvh) && (best < 0 || load[q] < load[best])) best = q;
-      queues[best].push_back(static_cast<int32_t>(it));
-      queues[best].push_back(grp);
-      load[best] += item_cost[it];
+  auto deal_class = [&](int cls, int32_t q_lo, int32_t q_hi) {
+    // the affinity wants the same number of queues on every XCD
+    const bool aff = affinity && (q_hi - q_lo) % 8 == 0;
+    auto allowed = [&](int32_t q, int32_t kvh) {
+      if (!aff) return true;
+      const int32_t x = q % 8;
+      return (g.Hkv >= 8) ? (x == kvh % 8) : (x % g.Hkv == kvh);
+    };
+    for (size_t it = 0; it < p.items.size(); ++it) {
+      if (item_class(static_cast<int32_t>(it)) != cls) continue;
+      for (int32_t grp = 0; grp < g.n_groups; ++grp) {
+        if (!group_selected(grp)) continue;
+        const int32_t kvh = grp * g.Gs / g.G;
+        int32_t best = -1;
+        for (int32_t q = q_lo; q < q_hi; ++q)
+          if (allowed(q, kvh) && (best < 0 || load[q] < load[best])) best = q;
+        queues[best].push_back(static_cast<int32_t>(it));
+        queues[best].push_back(grp);
+        load[best] += item_cost[it];
+      }
     }
-  }
-  // Refinement: while it lowers the larger of the two loads, move a unit from the fullest queue to the emptiest
-  // queue that may run it, or exchange a unit of each.
-  for (int32_t round = 0; round < 8 * p.n_queues; ++round) {
-    const int32_t qa = static_cast<int32_t>(std::max_element(load.begin(), load.end()) - load.begin());
-    double best_gain = 1e-9;
-    int32_t best_q = -1;
-    size_t best_u = 0, best_v = SIZE_MAX;
-    for (size_t u = 0; u + 1 < queues[qa].size(); u += 2) {
-      const double cu = item_cost[queues[qa][u]];
-      const int32_t kvh = queues[qa][u + 1] * g.Gs / g.G;
-      for (int32_t qb = 0; qb < p.n_queues; ++qb) {
-        if (qb == qa || !allowed(qb, kvh)) continue;
-        // move u: new pair maximum = max(load[qa] - cu, load[qb] + cu)
-        double gain = load[qa] - std::max(load[qa] - cu, load[qb] + cu);
-        if (gain > best_gain) {
-          best_gain = gain;
-          best_q = qb;
-          best_u = u;
-          best_v = SIZE_MAX;
-        }
-        for (size_t v = 0; v + 1 < queues[qb].size(); v += 2) {
-          const double cv = item_cost[queues[qb][v]];
-          if (cv >= cu || !allowed(qa, queues[qb][v + 1] * g.Gs / g.G)) continue;
-          gain = load[qa] - std::max(load[qa] - cu + cv, load[qb] + cu - cv);
+    // Refinement: while it lowers the larger of the two loads, move a unit from the fullest queue to the emptiest
+    // queue that may run it, or exchange a unit of each.
+    for (int32_t round = 0; round < 8 * (q_hi - q_lo); ++round) {
+      const int32_t qa = static_cast<int32_t>(std::max_element(load.begin() + q_lo, load.begin() + q_hi) - load.begin());
+      double best_gain = 1e-9;
+      int32_t best_q = -1;
+      size_t best_u = 0, best_v = SIZE_MAX;
+      for (size_t u = 0; u + 1 < queues[qa].size(); u += 2) {
+        const double cu = item_cost[queues[qa][u]];
+        const int32_t kvh = queues[qa][u + 1] * g.Gs / g.G;
+        for (int32_t qb = q_lo; qb < q_hi; ++qb) {
+          if (qb == qa || !allowed(qb, kvh)) continue;
+          // move u: new pair maximum = max(load[qa] - cu, load[qb] + cu)
+          double gain = load[qa] - std::max(load[qa] - cu, load[qb] + cu);
           if (gain > best_gain) {
             best_gain = gain;
             best_q = qb;
             best_u = u;
-            best_v = v;
+            best_v = SIZE_MAX;
+          }
+          for (size_t v = 0; v + 1 < queues[qb].size(); v += 2) {
+            const double cv = item_cost[queues[qb][v]];
+            if (cv >= cu || !allowed(qa, queues[qb][v + 1] * g.Gs / g.G)) continue;
+            gain = load[qa] - std::max(load[qa] - cu + cv, load[qb] + cu - cv);
+            if (gain > best_gain) {
+              best_gain = gain;
+              best_q = qb;
+              best_u = u;
+              best_v = v;
+            }
           }
         }
       }
+      if (best_q < 0) break;
+      const int32_t ui = queues[qa][best_u], ug = queues[qa][best_u + 1];
+      if (best_v == SIZE_MAX) {
+        queues[qa].erase(queues[qa].begin() + best_u, queues[qa].begin() + best_u + 2);
+        queues[best_q].push_back(ui);
+        queues[best_q].push_back(ug);
+        load[qa] -= item_cost[ui];
+        load[best_q] += item_cost[ui];
+      } else {
+        const int32_t vi = queues[best_q][best_v], vg = queues[best_q][best_v + 1];
+        queues[qa][best_u] = vi;
+        queues[qa][best_u + 1] = vg;
+        queues[best_q][best_v] = ui;
+        queues[best_q][best_v + 1] = ug;
+        load[qa] += item_cost[vi] - item_cost[ui];
+        load[best_q] += item_cost[ui] - item_cost[vi];
+      }
     }
-    if (best_q < 0) break;
-    const int32_t ui = queues[qa][best_u], ug = queues[qa][best_u + 1];
-    if (best_v == SIZE_MAX) {
-      queues[qa].erase(queues[qa].begin() + best_u, queues[qa].begin() + best_u + 2);
-      queues[best_q].push_back(ui);
-      queues[best_q].push_back(ug);
-      load[qa] -= item_cost[ui];
-      load[best_q] += item_cost[ui];
-    } else {
-      const int32_t vi = queues[best_q][best_v], vg = queues[best_q][best_v + 1];
-      queues[qa][best_u] = vi;
-      queues[qa][best_u + 1] = vg;
-      queues[best_q][best_v] = ui;
-      queues[best_q][best_v + 1] = ug;
-      load[qa] += item_cost[vi] - item_cost[ui];
-      load[best_q] += item_cost[ui] - item_cost[vi];
-    }
+  };
+  if (n_window_queues > 0) {
+    deal_class(0, 0, p.lse_queue0);
+    deal_class(1, p.lse_queue0, p.n_queues);
+  } else {
+    deal_class(0, 0, p.n_queues);
   }
   // Order within a queue: slices of split lists first, except the closing slice of a list, which goes last (when it
   // ends, the other slices of its list, run first elsewhere, have normally long arrived: the workgroup that the

@@ -98,6 +98,11 @@ struct purekv_plan {
   std::vector<int32_t> queue_units;        // (item, first head) pairs per queue, for inspection
   std::vector<int32_t> queue_units_begin;  // [n_queues + 1] offsets into queue_units (in pairs)
   int32_t n_queues = 0;
+  // Window plans: only the last lse_rows rows are asked for their log-sum-exp (0: every row).  Queues
+  // [lse_queue0, n_queues) hold the units of the query tiles with such rows, the others hold none of them; a plan
+  // without a window (or too small to be divided) has lse_queue0 = 0.
+  int32_t lse_rows = 0;
+  int32_t lse_queue0 = 0;
   int32_t n_slots = 0;
   int64_t n_blocks = 0;                    // (row block, key block) pairs computed, per query head
   int64_t n_kind[4] = {0, 0, 0, 0};        // of those, per BlockKind
@@ -118,7 +123,7 @@ struct purekv_plan {
 };
 
 namespace purekv {
-// Fills every host field of `p` from p.g (all but Gs, R, n_groups, which it chooses); `n_cu` = number of
-// persistent workgroups (one per compute unit).
+// Fills every host field of `p` from p.g (all but Gs, R, n_groups, which it chooses), p.head_sel and p.lse_rows;
+// `n_cu` = number of persistent workgroups (one per compute unit).
 void build_plan(purekv_plan& p, int n_cu);
 }  // namespace purekv

@@ -37,6 +37,7 @@
 // slices are combined INSIDE the launch: wavefront by wavefront they count themselves in at a counter in the
 // workspace, and at the end of its queue a workgroup adds up every list it took part in that is complete and not
 // yet combined (compare-and-swap on the counter: exactly once, nobody waits).  One launch per call.
+#include <algorithm>
 #include <type_traits>
 
 #include "common.h"
@@ -79,6 +80,9 @@ struct PrefillArgs {
   int32_t Gs, R, n_groups;   // workgroup shape: wavefront w -> row block w / Gs, head w % Gs
   uint32_t pattern;
   float scale_log2;  // softmax scale * log2(e)
+  // Window plans: the log-sum-exp is written for rows >= lse_row0 only, and only the workgroups from lse_queue0 on
+  // run units with such rows (the window kernel: only they keep the exact row sum).  Else 0 and 0.
+  int32_t lse_row0, lse_queue0;
 };
 
 typedef short shortx4 __attribute__((ext_vector_type(4)));
@@ -153,7 +157,7 @@ struct CombineCall {
   LdsFloat* xs;   // this wavefront's private 8 KB of LDS (an LDS pointer: the table below is read with LDS instructions)
   int64_t o_head_bytes;
   uint32_t o_row_bytes;
-  int32_t N, n_groups, wave, hl, rb;
+  int32_t N, n_groups, wave, hl, rb, lse_row0;
 };
 template <int D, bool LSE>
 __device__ __noinline__ void combine_slices(const CombineCall c, const u32x4 un, const u32x4 mu) {
@@ -199,7 +203,7 @@ __device__ __noinline__ void combine_slices(const CombineCall c, const u32x4 un,
       const float wgt = __builtin_amdgcn_exp2f(Wt[2 * (n * ns + sl)] - mx) * inv;
       if ((ln >> 5) == 0) Wt[2 * (n * ns + sl)] = wgt;
     }
-    if (LSE && (ln >> 5) == 0 && row0 + n < c.N)
+    if (LSE && (ln >> 5) == 0 && row0 + n < c.N && row0 + n >= c.lse_row0)
       c.lse[(size_t)hq * c.N + row0 + n] = (mxx + __builtin_amdgcn_logf(xsum)) * kLn2;
   }
   // Weighted sum, PB 16-byte pieces (4 columns of one row each) per lane at a time, the pieces of up to four
@@ -255,7 +259,7 @@ __device__ __noinline__ void combine_slices(const CombineCall c, const u32x4 un,
 //              squared norms of the V rows of every tile this step owns (Eq. 3 / Eq. 4 need ||V||: the tile is in
 //              LDS anyway).  Plans that keep all eight wavefronts busy get the norms from a pass of their own.
 template <int D, bool ST, bool LSE, bool VN>
-__global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
+__device__ __forceinline__ void prefill_body(const PrefillArgs& a) {
   constexpr int KSTEPS = D / 16;        // MFMA k-steps of the score product
   constexpr int DBLK = D / 32;          // 32-row blocks of O^T
   constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
@@ -424,7 +428,8 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
         if (rows_left >= 32 || r < rows_left) *reinterpret_cast<u32x4*>(otile + off) = w[i];
       }
     }
-    if (LSE && (ln >> 5) == 0 && (ln & 31) < rows_left) a.lse[(size_t)hq * a.N + row0 + (ln & 31)] = fin_lse;
+    if (LSE && (ln >> 5) == 0 && (ln & 31) < rows_left && row0 + (ln & 31) >= a.lse_row0)
+      a.lse[(size_t)hq * a.N + row0 + (ln & 31)] = fin_lse;
   };
   // fp32 partial result of a slice: 64 columns (256 bytes a row) per round through the same tile
   auto finish_slice = [&]() {
@@ -870,10 +875,29 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
         cc.wave = wave;
         cc.hl = hl;
         cc.rb = rb;
+        cc.lse_row0 = a.lse_row0;
         combine_slices<D, LSE>(cc, un, units_c[2 * u + 1]);
       }
     }
   }
+}
+
+template <int D, bool ST, bool LSE, bool VN>
+__global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
+  prefill_body<D, ST, LSE, VN>(a);
+}
+
+// Window plans with the log-sum-exp asked for: the workgroups before lse_queue0 run no unit that wants it and take
+// the loop without the exact row sum (about 8 % faster), the others the loop with it.  Two copies of the loop in one
+// kernel; written with the early return, the first copy comes out of the compiler as it does alone (with a plain
+// if / else it ran 2.5 % slower).
+template <int D, bool ST>
+__global__ __launch_bounds__(512, 1) void prefill_window_kernel(const PrefillArgs a) {
+  if (__builtin_expect((int)blockIdx.x < a.lse_queue0, 1)) {
+    prefill_body<D, ST, false, false>(a);
+    return;
+  }
+  prefill_body<D, ST, true, false>(a);
 }
 
 // Clears the arrival counters of a prefill workspace (a kernel, not a memset: callers may be capturing a graph).
@@ -894,7 +918,19 @@ hipError_t launch_one(const PrefillArgs& a, dim3 grid, hipStream_t st) {
 }
 
 template <int D, bool ST>
+hipError_t launch_window(const PrefillArgs& a, dim3 grid, hipStream_t st) {
+  constexpr unsigned lds_bytes = (6u * BK * D + PUREKV_WAVES * kXTile) * sizeof(uint16_t);
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_window_kernel<D, ST>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL((prefill_window_kernel<D, ST>), grid, dim3(512), lds_bytes, st, a);
+  return hipSuccess;
+}
+
+template <int D, bool ST>
 hipError_t launch_variant(const PrefillArgs& a, dim3 grid, hipStream_t st) {
+  // a window plan whose log-sum-exp is wanted: the divided kernel (the V norms, if wanted too, come from their own pass)
+  if (a.lse != nullptr && a.lse_queue0 > 0) return launch_window<D, ST>(a, grid, st);
   if (a.vnorm2 != nullptr && a.Gs * a.R < PUREKV_WAVES)
     return a.lse != nullptr ? launch_one<D, ST, true, true>(a, grid, st) : launch_one<D, ST, false, true>(a, grid, st);
   return a.lse != nullptr ? launch_one<D, ST, true, false>(a, grid, st) : launch_one<D, ST, false, false>(a, grid, st);
@@ -954,6 +990,10 @@ int launch_prefill(const purekv_plan& p, const void* q, const void* k, const voi
   a.n_groups = p.g.n_groups;
   a.pattern = p.g.pattern;
   a.scale_log2 = p.g.scale * kLog2e;
+  a.lse_row0 = p.lse_rows > 0 ? std::max(0, p.g.N - p.lse_rows) : 0;
+  a.lse_queue0 = p.lse_queue0;
+  const bool window_launch = lse != nullptr && p.lse_queue0 > 0;
+  if (window_launch) a.vnorm2 = nullptr;
   const dim3 grid((unsigned)p.n_queues);
   const bool sparse = p.g.pattern != PUREKV_PATTERN_DENSE;
   if (p.g.d == 128) {
@@ -969,7 +1009,7 @@ int launch_prefill(const purekv_plan& p, const void* q, const void* k, const voi
   }
   PUREKV_HIP_TRY(hipGetLastError());
   // every wavefront of this plan's workgroups has rows: the norms come from a stream over V of their own
-  if (vnorm2 != nullptr && p.g.Gs * p.g.R >= PUREKV_WAVES) return launch_vnorm2(p, v, vnorm2, st);
+  if (vnorm2 != nullptr && (p.g.Gs * p.g.R >= PUREKV_WAVES || window_launch)) return launch_vnorm2(p, v, vnorm2, st);
   return PUREKV_OK;
 }
 

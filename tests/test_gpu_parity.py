@@ -92,6 +92,61 @@ def test_prefill_matches_oracle(name, pattern):
         assert max(len(plan.queue(g)) for g in range(c["n_workgroups"])) >= 2  # some queue switches units
 
 
+@pytest.mark.parametrize("pattern", [0, 3])
+@pytest.mark.parametrize("name,w", [("manyunits_g7", 190), ("manyunits_g7", 37), ("manyunits_g2", 120), ("manyunits_g2", 1),
+                                    ("manyunits_g1", 100), ("manyunits_g1", 300), ("tiny_4f", 32), ("longtext_2f", 64)])
+def test_window_plan_prefill_and_importance(name, w, pattern):
+    """A window plan: outputs as for any plan; the log-sum-exp of the last w rows only, every other element of the
+    buffer untouched; the importance read from it.  The larger shapes have more units than workgroups, so their
+    plans are divided and the kernel with both copies of the tile loop runs."""
+    wl = SMALL[name]
+    inp = generate(wl, seed=21)
+    n = wl.n_tokens
+    print(f"[case] window plan {name} pattern={pattern} w={w} N={n}", flush=True)
+    plan = pk.Plan.for_workload(wl, pattern, lse_window=w)
+    c = plan.counts()
+    # these are the cases meant to exercise the divided kernel, at both head dimensions (the planner leaves a plan whole
+    # when the window's tiles are more than a quarter of the work, or when there are fewer units than workgroups)
+    if (name, w, pattern) in {("manyunits_g7", 37, 0), ("manyunits_g7", 37, 3), ("manyunits_g2", 120, 0),
+                              ("manyunits_g2", 1, 0), ("manyunits_g2", 1, 3)}:
+        assert c["lse_queue0"] > 0, "this case is meant to exercise the divided kernel"
+    q, k, v = to_dev(inp.q), to_dev(inp.k), to_dev(inp.v)
+    sentinel = -12345.0
+    lse = torch.full((wl.n_q_heads, n), sentinel, dtype=torch.float32, device="cuda")
+    out, _ = pk.purekv_st_spattn_prefill(plan, q, k, v, lse=lse)
+    torch.cuda.synchronize()
+    qf, kf, vf = F64(inp.q), F64(inp.k), F64(inp.v)
+    ref, ref_lse = orc.masked_attention(qf, kf, vf, wl.n_frames, wl.patches, wl.n_text, pattern)
+    check_attention(f64_of(out), ref, f"window {name}/p{pattern}/w{w}")
+    got_lse = f64_of(lse)
+    assert np.all(got_lse[:, :n - w] == sentinel), "rows before the window were written"
+    assert np.abs(got_lse[:, n - w:] - ref_lse[:, n - w:]).max() < 2e-3
+    # the same call without the log-sum-exp, and again with it: same output bits (the division changes who runs what,
+    # never what is computed for a row)
+    out2 = pk.purekv_st_spattn_prefill(plan, q, k, v)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(out), bits_of(out2))
+    cs = pk.purekv_lowlayer_importance(plan, q, k, lse, w)
+    torch.cuda.synchronize()
+    ref_c = orc.window_column_sums(qf, kf, wl.n_frames, wl.patches, wl.n_text, pattern, w)
+    got_c = f64_of(cs)
+    if ref_c.size:
+        assert np.all(np.abs(got_c - ref_c) <= IMPORTANCE_REL * np.maximum(np.abs(ref_c), 1e-12))
+    # a window wider than the plan's is refused: those rows of lse were never written
+    if w < n:
+        with pytest.raises(pk.PureKVError) as e:
+            pk.purekv_lowlayer_importance(plan, q, k, lse, w + 1)
+        assert e.value.status == pk.EINVAL
+    # the V norms asked for together with the window's log-sum-exp come from their own pass: same values
+    vn = torch.zeros((wl.n_kv_heads, n), dtype=torch.float32, device="cuda")
+    lse3 = torch.full_like(lse, sentinel)
+    out3, _ = pk.purekv_st_spattn_prefill(plan, q, k, v, lse=lse3, vnorm2=vn)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(out), bits_of(out3)) and torch.equal(lse, lse3)
+    ref_vn = (vf * vf).sum(-1)
+    assert np.abs(f64_of(vn) - ref_vn).max() <= 2e-6 * max(1.0, ref_vn.max())
+
+
 def test_prefill_is_deterministic_and_output_buffer_reuse():
     wl = SMALL["straddle_3f"]
     inp = generate(wl, seed=3)

@@ -134,12 +134,16 @@ def test_budget_matches_oracle_rule():
     assert pk.purekv_budget(100, 10, 1.0) == 90 and pk.purekv_budget(100, 10, 0.0) == 0
 
 
-def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern, n_wg=256):
+def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern, n_wg=256, window=0):
     """Tile lists, need bits and block kinds against the oracle's boolean mask; slices, units and queues are a
-    partition of the work."""
+    partition of the work.  window > 0: a window plan (the last `window` rows want their log-sum-exp): the units of
+    the query tiles that hold such rows, and no others, run on the workgroups from lse_queue0 on."""
     P, n = ph * pw, F * ph * pw + T
-    plan = pk.Plan(F, ph, pw, T, hq, hkv, d, pattern, host_only=True, n_workgroups=n_wg)
+    plan = pk.Plan(F, ph, pw, T, hq, hkv, d, pattern, host_only=True, n_workgroups=n_wg, lse_window=window)
     c = plan.counts()
+    assert c["lse_window"] == window and 0 <= c["lse_queue0"] < c["n_workgroups"]
+    if window == 0:
+        assert c["lse_queue0"] == 0
     R, gs, n_groups = c["row_blocks"], c["stacked_heads"], c["n_head_groups"]
     g = hq // hkv
     assert 1 <= gs * R <= pk.WAVES and g % gs == 0 and n_groups * gs == hq
@@ -224,6 +228,17 @@ def _check_plan_against_oracle(F, ph, pw, T, hq, hkv, d, pattern, n_wg=256):
         assert classes == sorted(classes), (q, classes)
     assert all(it[4] <= 32 for it in items)   # slices per list: what the combining wavefront's LDS table holds
     _check_steps_against_lists(plan, c, items, hq, hkv, d, n, R, gs)
+    if c["lse_queue0"] > 0:
+        for q in range(c["n_workgroups"]):
+            for i, _ in plan.queue(q):
+                holds_window_rows = (items[i][0] + 1) * bq > n - window
+                assert holds_window_rows == (q >= c["lse_queue0"]), (q, i)
+        # the set of the window's workgroups is about as large as its share of the steps (it also pays for the
+        # exact row sum, its unit switches and combinations, and must not finish last)
+        share = sum(items[i][2] for q in range(c["lse_queue0"], c["n_workgroups"]) for i, _ in plan.queue(q)) / \
+            sum(items[i][2] for q in range(c["n_workgroups"]) for i, _ in plan.queue(q))
+        assert share <= 0.25
+        assert share * c["n_workgroups"] - 1 <= c["n_workgroups"] - c["lse_queue0"] <= 2.5 * share * c["n_workgroups"] + 9
     loads = [sum(items[i][2] for i, _ in plan.queue(q)) for q in range(c["n_workgroups"])]
     if len(units) >= 4 * c["n_workgroups"]:
         assert max(loads) <= 1.5 * (sum(loads) / len(loads)) + max(it[2] for it in items)
@@ -282,6 +297,50 @@ def test_plan_lists_match_oracle_mask_benchmark_shapes(name):
     wl = WORKLOADS[name]
     _check_plan_against_oracle(wl.n_frames, wl.patch_h, wl.patch_w, wl.n_text, wl.n_q_heads, wl.n_kv_heads,
                                wl.head_dim, 3)
+
+
+@pytest.mark.parametrize("pattern", [0, 3])
+@pytest.mark.parametrize("name", ["videollama2_8f", "qwen25vl_32f", "qwen25vl_64f", "qwen25vl_128f_stack"])
+def test_window_plans_benchmark_shapes(name, pattern):
+    wl = WORKLOADS[name]
+    if name == "qwen25vl_128f_stack" and pattern == 0:
+        pytest.skip("a million steps: the 64-frame shape covers the same code in a tenth of the time")
+    _check_plan_against_oracle(wl.n_frames, wl.patch_h, wl.patch_w, wl.n_text, wl.n_q_heads, wl.n_kv_heads,
+                               wl.head_dim, pattern, window=wl.window)
+
+
+def test_window_plan_of_the_benchmark_low_layer_is_divided():
+    wl = WORKLOADS["qwen25vl_32f"]
+    plan = pk.Plan.for_workload(wl, 0, host_only=True, lse_window=wl.window)
+    c = plan.counts()
+    assert 232 <= c["lse_queue0"] <= 242      # 6 % of the steps, 8 % dearer: 16-17 of 256 workgroups and some slack
+    loads = [sum(plan.item(i)[2] for i, _ in plan.queue(q)) for q in range(256)]
+    assert max(loads[:c["lse_queue0"]]) <= 1.03 * sum(loads) / 256
+    assert 1.08 * max(loads[c["lse_queue0"]:]) <= 1.03 * max(loads[:c["lse_queue0"]])
+    plan.close()
+
+
+@pytest.mark.parametrize("window", [1, 19, 32, 200, 233])
+@pytest.mark.parametrize("pattern", [0, 3])
+@pytest.mark.parametrize("shape", [(4, 8, 8, 32), (3, 5, 7, 19), (5, 16, 16, 200), (40, 16, 16, 64)])
+def test_window_plans_small(shape, pattern, window):
+    F, ph, pw, T = shape
+    if window > F * ph * pw + T:
+        pytest.skip("window longer than the sequence")
+    _check_plan_against_oracle(F, ph, pw, T, 4, 2, 64, pattern, n_wg=16, window=window)
+
+
+def test_window_plan_argument_errors():
+    lib = pk.raw()
+    shape = pk.Shape(4, 8, 8, 32, 4, 2, 64, 3, 0.0, 0, 0, 0, 0, 0, 0)
+    h = ctypes.c_void_p()
+    for w in (0, -1, 4 * 64 + 32 + 1):
+        assert lib.purekv_plan_create_window_host(ctypes.byref(shape), w, 16, ctypes.byref(h)) == pk.EINVAL
+    assert lib.purekv_plan_create_window_host(ctypes.byref(shape), 32, 0, ctypes.byref(h)) == pk.EINVAL
+    assert lib.purekv_plan_create_window_host(ctypes.byref(shape), 4 * 64 + 32, 16, ctypes.byref(h)) == pk.OK
+    c = (ctypes.c_int64 * 16)()
+    assert lib.purekv_plan_counts(h, c) == pk.OK and c[14] == 4 * 64 + 32 and c[15] == 0   # every tile holds window rows
+    lib.purekv_plan_destroy(h)
 
 
 def test_dense_plan_benchmark_shape():
