@@ -549,7 +549,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.n_frames}f x {wl.patch_h}x{wl.patch_w} + {wl.n_text} text = {n} tokens, "
                                f"{hq}q/{hkv}kv heads, d={d}, keep ratio {args.ratio} (h={h}, w={w})",
-                   "tile": f"{pk.BLOCK}-row block x {pk.BLOCK}-key block ({pk.WAVES} wavefronts of {pk.BLOCK} rows per workgroup, {pk.BK}-key tiles)", "step": "low layer (dense prefill+LSE, importance, top-h, compaction) + "
+                   "tile": f"{pk.BLOCK}-row block x {pk.BLOCK}-key block ({pk.WAVES} wavefronts of {pk.BLOCK} rows per workgroup, {pk.BK}-key tiles)", "step": "low layer (dense prefill + log-sum-exp of the window rows, importance, top-h, compaction) + "
                    "high layer (ST-SpAttn prefill, top-h, compaction, append+decode)"},
         "prefill_ms_per_layer": round(st_call_ms, 4),
         "prefill_ms_per_layer_median": round(float(np.median(st_samples)), 4),

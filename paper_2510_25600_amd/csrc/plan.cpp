@@ -202,6 +202,9 @@ void build_plan(purekv_plan& p, int n_cu) {
   // small enough to be balanced over it: the window tiles' lists are cut into the number of slices that minimises an
   // estimate of the set's longest queue (equal units dealt evenly, a unit switch per unit, the combination charged
   // to the queue that closes a list), and the set is made large enough not to be the last to finish.
+  // KV-head groups of the XCD affinity of the dealing below: workgroup q runs on XCD q % 8, and the units of a KV
+  // head stay on the XCDs x with x % Hkv == kvh (Hkv < 8) or x == kvh % 8
+  const int32_t affinity_groups = (p.head_sel.empty() && n_cu % 8 == 0 && (g.Hkv % 8 == 0 || 8 % g.Hkv == 0)) ? std::min(g.Hkv, 8) : 1;
   auto window_tile = [&](int32_t qt) {
     return p.lse_rows > 0 && int64_t(qt + 1) * rows_per_qtile > int64_t(g.N) - p.lse_rows;
   };
@@ -242,9 +245,12 @@ void build_plan(purekv_plan& p, int n_cu) {
       auto rest_set = [&](int32_t nq) { return (cost_rest + kUnitCost * double(units_rest)) / double(n_cu - nq); };
       // smallest set, from the window tiles' share of the work on, whose longest queue ends no later than the
       // other set's average one; failing that, the size with the smallest later end of the two
+      // (a multiple of the number of KV-head groups of the XCD affinity below, so that every KV head keeps the same
+      // number of workgroups in both sets)
       const int32_t nq0 = std::max<int32_t>(1, static_cast<int32_t>(cost_w / (cost_w + cost_rest) * n_cu));
       double best_end = 0;
-      for (int32_t nq = nq0; nq <= std::min<int32_t>(n_cu - 1, 2 * nq0 + 8); ++nq) {
+      for (int32_t nq = (nq0 + affinity_groups - 1) / affinity_groups * affinity_groups;
+           nq <= std::min<int32_t>(n_cu - 1, 2 * nq0 + 8 + affinity_groups); nq += affinity_groups) {
         int32_t slices = 1;
         const double end_w = window_set(nq, slices), end_r = rest_set(nq), end = std::max(end_w, end_r);
         if (n_window_queues == 0 || end < best_end) best_end = end, n_window_queues = nq, window_slices = slices;
@@ -303,8 +309,9 @@ void build_plan(purekv_plan& p, int n_cu) {
   std::vector<std::vector<int32_t>> queues(p.n_queues);  // flat (item, group) pairs
   std::vector<double> load(p.n_queues, 0.0);
   auto deal_class = [&](int cls, int32_t q_lo, int32_t q_hi) {
-    // the affinity wants the same number of queues on every XCD
-    const bool aff = affinity && (q_hi - q_lo) % 8 == 0;
+    // the affinity needs the same number of queues for every KV head inside the range (the sets of a divided plan
+    // are sized for that)
+    const bool aff = affinity && (q_hi - q_lo) % affinity_groups == 0;
     auto allowed = [&](int32_t q, int32_t kvh) {
       if (!aff) return true;
       const int32_t x = q % 8;
