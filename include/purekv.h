@@ -141,7 +141,7 @@ PUREKV_API int purekv_plan_create_heads_host(const purekv_shape_t* shape, const 
  * query rows only (the recent window), so only those rows' log-sum-exp is needed from the prefill.  On such a plan
  * a prefill call with `lse` given writes lse[h, i] for i >= N - w only and leaves every other element of `lse`
  * untouched, and only the workgroups that own those rows carry the exact row sum through their tile loop (it costs
- * the loop about 8 %); everything else -- outputs, workspaces, every other call -- is as for purekv_plan_create.
+ * the loop 7-10 %); everything else -- outputs, workspaces, every other call -- is as for purekv_plan_create.
  * purekv_lowlayer_importance on such a plan refuses a window larger than w (PUREKV_EINVAL).  1 <= w <= N, else
  * PUREKV_EINVAL. */
 PUREKV_API int purekv_plan_create_window(const purekv_shape_t* shape, int32_t w, purekv_plan_t** out, void* stream);

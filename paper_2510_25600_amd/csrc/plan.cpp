@@ -196,7 +196,7 @@ void build_plan(purekv_plan& p, int n_cu) {
 
   // ---- window plans: the query tiles whose rows want the log-sum-exp get workgroups of their own ----
   // Only the last lse_rows rows are asked for their log-sum-exp (the recent window of Eq. 2).  Keeping the exact row
-  // sum costs the tile loop about 8 % (two more vector instructions per pair of scores), so the query tiles that
+  // sum costs the tile loop 7-10 % (two more vector instructions per pair of scores), so the query tiles that
   // hold such rows ("window tiles") are dealt to a set of workgroups of their own, sized by their share of the work,
   // and only those workgroups run the variant of the loop that keeps the sum.  A set of few workgroups needs units
   // small enough to be balanced over it: the window tiles' lists are cut into the number of slices that minimises an

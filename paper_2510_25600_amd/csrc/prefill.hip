@@ -888,7 +888,7 @@ __global__ __launch_bounds__(512, 1) void prefill_kernel(const PrefillArgs a) {
 }
 
 // Window plans with the log-sum-exp asked for: the workgroups before lse_queue0 run no unit that wants it and take
-// the loop without the exact row sum (about 8 % faster), the others the loop with it.  Two copies of the loop in one
+// the loop without the exact row sum (7-10 % faster), the others the loop with it.  Two copies of the loop in one
 // kernel; written with the early return, the first copy comes out of the compiler as it does alone (with a plain
 // if / else it ran 2.5 % slower).
 template <int D, bool ST>
