@@ -149,6 +149,31 @@ static void one_shape(int F, int ph, int pw, int T, int hq, int hkv, int d, int 
     CHECK(purekv_plan_create_host(&s, n_wg, &p) == PUREKV_OK && p != nullptr);
     inspect(p, s, n_wg, nullptr);
     CHECK(purekv_plan_destroy(p) == PUREKV_OK);
+    // window plans of the same shape: the same invariants, and the division of the queues
+    const int64_t n = (int64_t)F * ph * pw + T;
+    for (int64_t w : {(int64_t)1, (int64_t)T, n / 3, n}) {
+      if (w < 1 || w > n) continue;
+      p = nullptr;
+      CHECK(purekv_plan_create_window_host(&s, (int32_t)w, n_wg, &p) == PUREKV_OK && p != nullptr);
+      inspect(p, s, n_wg, nullptr);
+      int64_t c[16];
+      CHECK(purekv_plan_counts(p, c) == PUREKV_OK && c[14] == w && c[15] >= 0 && c[15] < c[6]);
+      if (c[15] > 0) {   // queues before c[15] hold no query tile with a window row, the others nothing else
+        const int64_t rows = c[7] * PUREKV_BLOCK;
+        std::vector<int32_t> units;
+        for (int64_t q = 0; q < c[6]; ++q) {
+          const int len = purekv_plan_queue(p, (int32_t)q, nullptr, 0);
+          units.assign(2 * (size_t)len + 2, -1);
+          CHECK(purekv_plan_queue(p, (int32_t)q, units.data(), len) == len);
+          for (int u = 0; u < len; ++u) {
+            int32_t item[6];
+            CHECK(purekv_plan_item(p, units[2 * u], item) == PUREKV_OK);
+            CHECK((((int64_t)item[0] + 1) * rows > n - w) == (q >= c[15]));
+          }
+        }
+      }
+      CHECK(purekv_plan_destroy(p) == PUREKV_OK);
+    }
   }
 }
 
@@ -222,6 +247,10 @@ int main() {
     s.pattern = 3, s.n_frames = 1 << 20, s.patch_h = 1 << 10;
     CHECK(purekv_plan_create_host(&s, 256, &p) == PUREKV_EINVAL);
     CHECK(purekv_plan_destroy(nullptr) == PUREKV_OK);
+    s = make_shape(2, 4, 4, 8, 4, 2, 64, 3);
+    CHECK(purekv_plan_create_window_host(&s, 0, 256, &p) == PUREKV_EINVAL && purekv_plan_create_window_host(&s, 41, 256, &p) == PUREKV_EINVAL);
+    CHECK(purekv_plan_create_window_host(&s, 8, 0, &p) == PUREKV_EINVAL && purekv_plan_create_window_host(&s, 8, 256, nullptr) == PUREKV_EINVAL);
+    CHECK(purekv_plan_create_window_host(nullptr, 8, 256, &p) == PUREKV_EINVAL);
     for (int st = -7; st <= 1; ++st) CHECK(purekv_strerror(st) != nullptr && purekv_strerror(st)[0] != 0);
     for (int n = 0; n < 40000; n += 997)
       for (int pct = 0; pct <= 100; pct += 5) CHECK(purekv_budget(n, 0, pct / 100.0) == (int32_t)((int64_t)pct * n / 100));
