@@ -23,7 +23,8 @@ def test_captured_step_replays_bit_exactly():
     n, w, d, hq, hkv = wl.n_tokens, 64, wl.head_dim, wl.n_q_heads, wl.n_kv_heads
     h = pk.purekv_budget(n, w, 0.5)
     n_keep, cap = h + w, h + w + 1
-    dense, st = pk.Plan.for_workload(wl, pk.PATTERN_DENSE), pk.Plan.for_workload(wl, pk.PATTERN_ST)
+    # (the low layer on a window plan, as in the benchmark: its prefill writes the window rows of lse only)
+    dense, st = pk.Plan.for_workload(wl, pk.PATTERN_DENSE, lse_window=w), pk.Plan.for_workload(wl, pk.PATTERN_ST)
     assert st.counts()["n_split_qtiles"] > 0
 
     def inputs(seed):
@@ -34,7 +35,7 @@ def test_captured_step_replays_bit_exactly():
     q0, k0, v0, q1, k1, v1, qn, kn, vn = static
     dev = q0.device
     out0, out1 = torch.empty_like(q0), torch.empty_like(q1)
-    lse = torch.empty((hq, n), dtype=torch.float32, device=dev)
+    lse = torch.zeros((hq, n), dtype=torch.float32, device=dev)
     c = torch.empty((hkv, n - w), dtype=torch.float32, device=dev)
     idx0 = torch.empty((1, hkv, n_keep), dtype=torch.int32, device=dev)
     idx1 = torch.empty_like(idx0)
