@@ -35,8 +35,10 @@ __global__ __launch_bounds__(256) void compact_kernel(const uint16_t* __restrict
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
       if (dst[u] >= 0) {
-        *reinterpret_cast<u32x4*>(kc + dst[u]) = xk[u];
-        *reinterpret_cast<u32x4*>(vc + dst[u]) = xv[u];
+        // (non-temporal: the compact cache is written once here and read by a later launch: 28.0 against 29.0 us
+        // for the 26-layer batch of the 32-frame shape; the same hint on the gathered loads costs 8 %)
+        __builtin_nontemporal_store(xk[u], reinterpret_cast<u32x4*>(kc + dst[u]));
+        __builtin_nontemporal_store(xv[u], reinterpret_cast<u32x4*>(vc + dst[u]));
       }
   }
 }
