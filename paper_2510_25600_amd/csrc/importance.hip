@@ -140,6 +140,20 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
       acc[i] += ok ? p : 0.f;
     }
   };
+  // Scores i and i + 1 together (the unmasked variant): the second score's instructions fill the latency of the
+  // first one's exponential.
+  auto exp_pair = [&](const floatx16& S, const Pending& pd, int i) {
+    if constexpr (!MASK) {
+      float p0, p1;
+      asm volatile("v_fma_f32 %0, %4, %6, %7\n\tv_fma_f32 %1, %5, %6, %7\n\tv_exp_f32 %0, %0\n\tv_exp_f32 %1, %1\n\t"
+                   "s_nop 0\n\tv_add_f32 %2, %2, %0\n\tv_add_f32 %3, %3, %1"
+                   : "=&v"(p0), "=&v"(p1), "+v"(acc[i]), "+v"(acc[i + 1])
+                   : "v"(S[i]), "v"(S[i + 1]), "v"(scale_v), "v"(pd.neg_lse2));
+    } else {
+      exp_step(S, pd, i);
+      exp_step(S, pd, i + 1);
+    }
+  };
   int rd_slot = 0, rd_g = 0, rd_qb = set, rd_b = set;   // block the next read_pending / read_frag calls fetch
   normalise(rd_g, rd_qb);
   auto read_pending = [&](Pending& pd) {
@@ -182,7 +196,7 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
       if (s == 1) issue_next(rd_slot < 2 ? rd_slot + NB - 2 : rd_slot - 2);   // the slot read a stage ago
       if (have_prev) {
 #pragma unroll
-        for (int i = s * (16 / KSTEPS); i < (s + 1) * (16 / KSTEPS); ++i) exp_step(Sp, pp, i);
+        for (int i = s * (16 / KSTEPS); i < (s + 1) * (16 / KSTEPS); i += 2) exp_pair(Sp, pp, i);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -208,10 +222,10 @@ __global__ __launch_bounds__(512) void importance_kernel(const ImportanceArgs a)
   if (it < n_iter) {
     stage(B, A, S1, S0, true);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) exp_step(S1, B.pd, i);
+    for (int i = 0; i < 16; i += 2) exp_pair(S1, B.pd, i);
   } else {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) exp_step(S0, A.pd, i);
+    for (int i = 0; i < 16; i += 2) exp_pair(S0, A.pd, i);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // the loads started past the end have landed before LDS is reused or freed
 
