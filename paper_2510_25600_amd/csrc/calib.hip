@@ -82,7 +82,9 @@ __global__ __launch_bounds__(512, 1) void calib_mfma_kernel(float* sink, unsigne
 
 
 // Skeleton of one attention tile step per compute unit (256 query rows x 64 keys, head_dim 128): only what every
-// kernel of this formulation must issue -- 32 MFMAs per 32 rows, one 1 KB LDS fragment read per fragment, the
+// kernel of this formulation must issue -- 32 MFMAs per 32 rows, one 1 KB LDS fragment read per fragment (issued
+// three MFMAs ahead of its use, as the prefill kernel does: read right before use, the same loop is 7 % slower at 32
+// rows per wavefront and 14 % at 64), the
 // softmax vector work of a score (2 multiply-adds, 2 exponentials, 1 convert per MFMA of the score product), 32 KB
 // of K/V tile loads from L2 into LDS and one barrier -- no masks, maxima, row sums, tables or output.
 // RB = 1: 8 wavefronts of 32 rows (every fragment feeds one MFMA); RB = 2: 4 wavefronts of 64 rows (every fragment
@@ -144,10 +146,21 @@ __global__ __launch_bounds__(512 / RB) void calib_step_kernel(float* sink, unsig
     }
     const uint16_t* Ks = kv[it & 1][0];
     const uint16_t* Vs = kv[it & 1][1];
+    constexpr int AH = 3;
+    auto rdk = [&](int i) { return *reinterpret_cast<const bf16x8*>(Ks + (i >> 3) * 32 * 128 + (kq0 ^ (16 * (i & 7)))); };
+    auto rdv = [&](int i) {
+      const int b = i >> 2, ks = i & 3;
+      return *reinterpret_cast<const bf16x8*>(Vs + ((ks * 16 * 128 + (kq0 ^ (16 * (2 * b + (ks & 1))))) & 8191));
+    };
+    bf16x8 fr[AH + 1];
+#pragma unroll
+    for (int i = 0; i < AH; ++i) fr[i] = rdk(i);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {   // score product of one 32-key half, softmax work on the other half's scores
       const int h = i >> 3, s = i & 7;
-      const bf16x8 f = *reinterpret_cast<const bf16x8*>(Ks + h * 32 * 128 + (kq0 ^ (16 * s)));
+      fr[(i + AH) % (AH + 1)] = (i + AH < 16) ? rdk(i + AH) : rdv(i + AH - 16);
+      const bf16x8 f = fr[i % (AH + 1)];
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         S[rb][h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[rb][s], S[rb][h], 0, 0, 0);
@@ -165,7 +178,8 @@ __global__ __launch_bounds__(512 / RB) void calib_step_kernel(float* sink, unsig
 #pragma unroll
     for (int i = 0; i < 16; ++i) {   // second product
       const int b = i >> 2, ks = i & 3;
-      const bf16x8 f = *reinterpret_cast<const bf16x8*>(Vs + ((ks * 16 * 128 + (kq0 ^ (16 * (2 * b + (ks & 1))))) & 8191));
+      if (i + AH < 16) fr[(16 + i + AH) % (AH + 1)] = rdv(i + AH);
+      const bf16x8 f = fr[(16 + i) % (AH + 1)];
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
         O[rb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, __builtin_bit_cast(bf16x8, P[rb][ks]), O[rb][b], 0, 0, 0);
