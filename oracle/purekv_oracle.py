@@ -11,7 +11,7 @@ reordered beyond blocking query rows to bound memory (rows are independent).
 Notation (paper, Sec. 3.1 and 3.2):  l = N tokens = F frames x P patches of
 video followed by T text tokens; w = recent window; h = number of non-recent
 keys kept; A = attention probabilities; C = recent-window column sums (Eq. 2);
-S = C * ||V|| (Eq. 3 / Eq. 4).
+S = C * ||V|| (Eq. 3 / Eq. 4); rank(S) and Spearman's rho between two score vectors (Sec. 3.3, Eq. 5-7).
 
 Readings of the paper where it is silent (all listed in the design notes):
   * spatial and temporal paths are combined as a union in one mask;
@@ -19,7 +19,7 @@ Readings of the paper where it is silent (all listed in the design notes):
   * text queries attend causally to every earlier token;
   * under GQA the score of a KV head is the sum over its query heads;
   * kept entries are stored in ascending original index, window last;
-  * ties in the top-h go to the lower index.
+  * ties in the top-h go to the lower index, and ranks are assigned the same way (no averaged ranks).
 """
 from __future__ import annotations
 
@@ -173,6 +173,32 @@ def topk_select(s: np.ndarray, h: int, n: int, w: int) -> np.ndarray:
         idx[kv, :h] = np.sort(order[:h])
         idx[kv, h:] = np.arange(n - w, n)
     return idx
+
+
+def score_ranks(s: np.ndarray) -> np.ndarray:
+    """rank(S) of Sec. 3.3: r[..., j] = position of s[..., j] when the scores of a row are put in descending order,
+    0 = the highest score; equal scores keep their index order (the tie rule of the top-h selection: the lower
+    index ranks first), so the ranks of a row are always a permutation of 0 .. n-1."""
+    s = np.asarray(s, dtype=np.float64)
+    order = np.argsort(-s, axis=-1, kind="stable")
+    ranks = np.empty(s.shape, dtype=np.int64)
+    np.put_along_axis(ranks, order, np.broadcast_to(np.arange(s.shape[-1], dtype=np.int64), s.shape), axis=-1)
+    return ranks
+
+
+def spearman_rank_correlation(s_hat: np.ndarray, s: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Spearman's rank correlation of Sec. 3.3 (Eq. 5-7) between the estimated scores s_hat (Eq. 4: low-layer column
+    sums, the layer's own V norms) and the scores s of the layer's own attention (Eq. 6), row by row over the last
+    axis (n = l - w non-recent keys):  rho = 1 - 6 sum_j (r_hat_j - r_j)^2 / (n (n^2 - 1)).
+    Returns (sum of squared rank differences as exact integers, rho in fp64 from exact rational arithmetic)."""
+    n = s.shape[-1]
+    if n < 2 or s_hat.shape != s.shape:
+        raise ValueError("two score arrays of the same shape with at least two scores a row")
+    d = score_ranks(s_hat) - score_ranks(s)
+    sum_d2 = np.array([sum(int(x) * int(x) for x in row) for row in d.reshape(-1, n)], dtype=object).reshape(d.shape[:-1])
+    denom = n * (n * n - 1)
+    rho = np.array([float(1 - Fraction(6 * int(x), denom)) for x in sum_d2.reshape(-1)], dtype=np.float64).reshape(d.shape[:-1])
+    return sum_d2, rho
 
 
 def stack_pattern(layer: int, st_layer: int, sparse_pattern: int = 3) -> int:

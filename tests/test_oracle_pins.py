@@ -474,3 +474,79 @@ def test_attention_and_lse_per_kv_head_against_library_softmax():
         assert np.abs(out[hq] - a @ v[kv]).max() < 1e-12
         s = torch.from_numpy(q[hq] @ k[kv].T * scale).masked_fill(~torch.from_numpy(mask), -math.inf)
         assert np.abs(lse[hq] - torch.logsumexp(s, -1).numpy()).max() < 1e-12
+
+
+# ---- Spearman's rank correlation (Sec. 3.3, Eq. 5-7) --------------------------------------------------------------
+
+def _ranks_by_definition(s):
+    """rank of s_j = number of scores that come before it in descending order, ties to the lower index: two loops."""
+    n = len(s)
+    return [sum(1 for k in range(n) if s[k] > s[j] or (s[k] == s[j] and k < j)) for j in range(n)]
+
+
+def test_score_ranks_equal_the_definition_including_ties():
+    rng = np.random.default_rng(40)
+    for n in (2, 3, 17, 64):
+        for _ in range(5):
+            s = rng.integers(0, 5, size=n).astype(np.float64)      # many ties
+            s[rng.integers(0, n)] = -0.0
+            assert orc.score_ranks(s).tolist() == _ranks_by_definition(s.tolist())
+    s = rng.standard_normal((3, 4, 50))
+    r = orc.score_ranks(s)
+    assert r.shape == s.shape
+    for a in range(3):
+        for b in range(4):
+            assert r[a, b].tolist() == _ranks_by_definition(s[a, b].tolist())
+            assert sorted(r[a, b].tolist()) == list(range(50))     # a permutation
+
+
+def test_spearman_closed_forms():
+    n = 1000
+    x = np.arange(n, dtype=np.float64)
+    d2, rho = orc.spearman_rank_correlation(x[None], x[None])
+    assert d2[0] == 0 and rho[0] == 1.0                                            # identical rankings
+    d2, rho = orc.spearman_rank_correlation(x[None], -x[None])
+    assert d2[0] == n * (n * n - 1) // 3 and rho[0] == -1.0                         # reversed: sum d^2 = n(n^2-1)/3
+    y = x.copy()
+    y[[10, 11]] = y[[11, 10]]                                                       # one adjacent transposition
+    d2, rho = orc.spearman_rank_correlation(x[None], y[None])
+    assert d2[0] == 2 and abs(rho[0] - (1 - 12 / (n * (n * n - 1)))) < 1e-18
+    # five scores, ranks differ by (1, -1, 0, 0, 0): rho = 1 - 6 * 2 / (5 * 24) = 0.9
+    d2, rho = orc.spearman_rank_correlation(np.array([[5., 4., 3., 2., 1.]]), np.array([[4., 5., 3., 2., 1.]]))
+    assert d2[0] == 2 and rho[0] == 0.9
+    with pytest.raises(ValueError):
+        orc.spearman_rank_correlation(np.zeros((1, 1)), np.zeros((1, 1)))
+
+
+def test_spearman_against_the_library_routine_and_invariances():
+    scipy_stats = pytest.importorskip("scipy.stats")
+    rng = np.random.default_rng(41)
+    for n in (2, 3, 10, 257, 4096):
+        a, b = rng.standard_normal(n), rng.standard_normal(n)
+        b = 0.6 * a + 0.8 * b                                                       # correlated, tie-free
+        _, rho = orc.spearman_rank_correlation(a[None], b[None])
+        assert abs(rho[0] - scipy_stats.spearmanr(a, b).statistic) < 1e-12
+        # symmetric; unchanged by strictly increasing maps of either argument; sign flips under a decreasing one
+        _, rho_ba = orc.spearman_rank_correlation(b[None], a[None])
+        _, rho_mono = orc.spearman_rank_correlation(np.exp(a)[None], (3 * b + 7)[None])
+        _, rho_neg = orc.spearman_rank_correlation(a[None], -b[None])
+        assert rho_ba[0] == rho[0] and rho_mono[0] == rho[0] and abs(rho_neg[0] + rho[0]) < 1e-15
+    # rows are independent
+    s_hat, s = rng.standard_normal((2, 3, 100)), rng.standard_normal((2, 3, 100))
+    d2, rho = orc.spearman_rank_correlation(s_hat, s)
+    assert d2.shape == (2, 3)
+    for i in range(2):
+        for j in range(3):
+            d2_1, rho_1 = orc.spearman_rank_correlation(s_hat[i, j][None], s[i, j][None])
+            assert d2[i, j] == d2_1[0] and rho[i, j] == rho_1[0]
+
+
+def test_spearman_of_a_planted_mistake_is_caught_by_the_pins():
+    """The pins above tell a wrong rank convention apart: ascending ranks give the same rho (so they are no mistake),
+    but ranks that break ties to the HIGHER index, or a denominator n (n^2 + 1), do not survive them."""
+    s = np.array([1.0, 1.0, 0.0])
+    assert orc.score_ranks(s).tolist() == [0, 1, 2]                    # ties: lower index first
+    wrong = np.argsort(np.argsort(-s[::-1], kind="stable"), kind="stable")[::-1]   # ties to the higher index
+    assert wrong.tolist() != [0, 1, 2]
+    n = 5
+    assert 1 - 6 * 2 / (n * (n * n + 1)) != 0.9
