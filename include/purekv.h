@@ -174,6 +174,19 @@ PUREKV_API int purekv_plan_queue(const purekv_plan_t* plan, int32_t wg, int32_t*
  * negative status. */
 PUREKV_API int purekv_plan_steps(const purekv_plan_t* plan, int32_t wg, int32_t* steps, int32_t cap);
 
+/* Spearman's rank correlation between two score arrays, row by row (Sec. 3.3, Eq. 5-7: the check that the scores
+ * estimated with a low layer's column sums, Eq. 4, rank the non-recent keys like the scores of the layer's own
+ * attention, Eq. 6).  rank(S) is a score's position in its row's descending order, equal scores in index order (the
+ * tie rule of purekv_topk_select; -0.0 equals +0.0; NaN scores are unsupported), and
+ *   rho = 1 - 6 sum_j (r_hat_j - r_j)^2 / (n (n^2 - 1)),   n = n_keys.
+ *   s_hat, s: device fp32 [n_rows, n_keys] (packed rows; e.g. the s_out of two purekv_topk_select calls);
+ *   sum_d2_out: device uint64 [n_rows], the sums of squared rank differences (exact); rho_out: device fp64 [n_rows]
+ *   or NULL.  Needs no plan and no workspace; the work is quadratic in n_keys (a diagnostic, not a step of the path).
+ *   2 <= n_keys <= 131072 (so that rho is the correctly rounded value of the exact quotient), n_rows >= 1, else
+ *   PUREKV_EINVAL. */
+PUREKV_API int purekv_spearman(const float* s_hat, const float* s, int32_t n_rows, int32_t n_keys, uint64_t* sum_d2_out,
+                               double* rho_out, void* stream);
+
 /* Device workspace bytes needed by `op` for this plan.  `n_layers`, `w` and `cap` are read by the ops
  * that take them (TOPK: n_layers, w; DECODE: cap); pass 0 otherwise.  What lives there: PREFILL, the partial
  * results of query tiles whose key list is cut into slices (the text rows of Sec. 3.2 see every key); TOPK, the

@@ -62,6 +62,7 @@ def _load() -> ctypes.CDLL:
         "purekv_plan_item": (c_int, [P, c_int32, POINTER(c_int32)]),
         "purekv_plan_queue": (c_int, [P, c_int32, POINTER(c_int32), c_int32]),
         "purekv_plan_steps": (c_int, [P, c_int32, POINTER(c_int32), c_int32]),
+        "purekv_spearman": (c_int, [P, P, c_int32, c_int32, P, P, P]),
         "purekv_workspace_bytes": (c_size_t, [P, c_int, c_int32, c_int32, c_int32]),
         "purekv_workspace_init": (c_int, [P, c_int, P, c_size_t, c_int32, c_int32, c_int32, P]),
         "purekv_stack_workspace_init": (c_int, [P, P, P, P, c_size_t, P]),
@@ -98,7 +99,7 @@ _lib = _load()
 EXPORTS = (
     "purekv_plan_create", "purekv_plan_create_host", "purekv_plan_destroy", "purekv_plan_create_heads",
     "purekv_plan_create_heads_host", "purekv_plan_create_window", "purekv_plan_create_window_host", "purekv_plan_counts",
-    "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_plan_steps", "purekv_workspace_bytes", "purekv_workspace_init",
+    "purekv_plan_qtile_list", "purekv_plan_item", "purekv_plan_queue", "purekv_plan_steps", "purekv_spearman", "purekv_workspace_bytes", "purekv_workspace_init",
     "purekv_stack_workspace_init", "purekv_st_spattn_prefill", "purekv_st_spattn_prefill_vnorm", "purekv_topk_select_vnorm",
     "purekv_lowlayer_importance", "purekv_topk_select", "purekv_topk_select_static", "purekv_kv_compact", "purekv_kv_append",
     "purekv_decode_attn", "purekv_decode_step", "purekv_stack_workspace_bytes", "purekv_stack_layer",
@@ -392,6 +393,20 @@ def purekv_topk_select_static(plan: Plan, c: torch.Tensor, v: Optional[torch.Ten
     _check(_lib.purekv_topk_select_static(plan.handle, c.data_ptr(), _ptr(v), stride, n_layers, w, h,
                                           idx_out.data_ptr(), _stream()), "purekv_topk_select_static")
     return idx_out
+
+
+def purekv_spearman(s_hat: torch.Tensor, s: torch.Tensor):
+    """s_hat, s: fp32 [..., n_keys] device tensors of one shape.  Returns (sum of squared rank differences, int64
+    [...] -- exact, below 2^63 for n_keys <= 131072 -- and rho, fp64 [...])."""
+    assert s_hat.shape == s.shape and s.dtype == torch.float32 and s_hat.dtype == torch.float32
+    assert s.is_cuda and s_hat.is_cuda and s.is_contiguous() and s_hat.is_contiguous()
+    n = s.shape[-1]
+    rows = s.numel() // n if n else 0
+    d2 = torch.empty(s.shape[:-1], dtype=torch.int64, device=s.device)
+    rho = torch.empty(s.shape[:-1], dtype=torch.float64, device=s.device)
+    _check(_lib.purekv_spearman(s_hat.data_ptr(), s.data_ptr(), rows, n, d2.data_ptr(), rho.data_ptr(), _stream()),
+           "purekv_spearman")
+    return d2, rho
 
 
 def purekv_kv_compact(plan: Plan, k: torch.Tensor, v: torch.Tensor, idx: torch.Tensor, cap: Optional[int] = None,

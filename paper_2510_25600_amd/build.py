@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libpurekv.so")
-SOURCES = ["api.hip", "plan.cpp", "prefill.hip", "importance.hip", "select.hip", "compact.hip", "decode.hip", "calib.hip"]
+SOURCES = ["api.hip", "plan.cpp", "prefill.hip", "importance.hip", "select.hip", "compact.hip", "decode.hip", "rank.hip", "calib.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -327,6 +327,13 @@ int purekv_lowlayer_importance(const purekv_plan_t* p, const void* q, const void
   return launch_importance(*p, q, k, lse, w, c_out, static_cast<hipStream_t>(stream));
 }
 
+int purekv_spearman(const float* s_hat, const float* s, int32_t n_rows, int32_t n_keys, uint64_t* sum_d2_out,
+                    double* rho_out, void* stream) {
+  if (s_hat == nullptr || s == nullptr || sum_d2_out == nullptr) return PUREKV_EINVAL;
+  if (n_rows < 1 || n_rows > 65535 || n_keys < 2 || n_keys > 131072) return PUREKV_EINVAL;
+  return launch_spearman(s_hat, s, n_rows, n_keys, sum_d2_out, rho_out, static_cast<hipStream_t>(stream));
+}
+
 int purekv_topk_select(const purekv_plan_t* p, const float* c, const void* v, int64_t v_layer_stride,
                        int32_t n_layers, int32_t w, int32_t h, int32_t* idx_out, float* s_out, void* ws,
                        size_t ws_bytes, void* stream) {

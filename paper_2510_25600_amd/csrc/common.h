@@ -123,6 +123,8 @@ double calib_step_flops(const purekv_plan& p, int32_t iters);
 size_t prefill_ws_bytes(const purekv_plan& p);
 // Arrival counters lead the prefill and decode workspaces: zero whenever no call is running on the workspace.
 size_t prefill_counter_region_bytes(const purekv_plan& p);
+int launch_spearman(const float* s_hat, const float* s, int32_t n_rows, int32_t n_keys, uint64_t* sum_d2, double* rho,
+                    hipStream_t st);
 int launch_prefill_ws_init(const purekv_plan& p, void* ws, hipStream_t st);
 int launch_decode_ws_init(const purekv_plan& p, void* ws, hipStream_t st);
 size_t topk_ws_bytes(const purekv_plan& p, int32_t n_layers, int32_t w);

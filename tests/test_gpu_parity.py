@@ -733,3 +733,74 @@ def test_prefill_vnorm_layers_and_head_subsets():
     vf = F64(x.v)
     assert torch.all(vn[0] == -7.0)
     assert np.all(np.abs(f64_of(vn[1]) - (vf[1] ** 2).sum(1)) <= 2e-6 * (vf[1] ** 2).sum(1))
+
+
+@pytest.mark.parametrize("n", [2, 3, 255, 256, 257, 1000, 8192, 20000])
+def test_spearman_matches_oracle_exactly(n):
+    """Sec. 3.3, Eq. 5-7: ranks are counts and the sum of squared rank differences an integer: bit-exact; rho is the
+    correctly rounded quotient on both sides."""
+    rng = np.random.default_rng(50 + n)
+    rows = 5
+    a = rng.standard_normal((rows, n)).astype(np.float32)
+    b = (0.5 * a + rng.standard_normal((rows, n))).astype(np.float32)
+    b[1] = a[1]                                                    # identical rankings
+    b[2] = -a[2]                                                   # reversed
+    a[3] = rng.integers(0, 4, size=n).astype(np.float32)           # heavy ties, signed zeros among them
+    b[3] = rng.integers(0, 3, size=n).astype(np.float32)
+    a[3, ::7] = -0.0
+    b[4] = np.float32(1.5)                                         # one array constant: its ranks are the indices
+    print(f"[case] spearman n={n}", flush=True)
+    d2, rho = pk.purekv_spearman(torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda())
+    torch.cuda.synchronize()
+    ref_d2, ref_rho = orc.spearman_rank_correlation(a.astype(np.float64), b.astype(np.float64))
+    assert d2.cpu().numpy().tolist() == [int(x) for x in ref_d2]
+    assert np.array_equal(rho.cpu().numpy(), ref_rho)
+    assert rho[1].item() == 1.0
+    if np.unique(a[2]).size == n:      # (two equal scores keep their index order in both arrays: not a full reversal)
+        assert rho[2].item() == -1.0
+
+
+def test_spearman_of_estimated_against_own_scores_through_the_library():
+    """The check of Sec. 3.3 end to end on one synthetic layer pair: S-hat from the low layer's column sums and the
+    high layer's V (Eq. 4), S from the high layer's own column sums (Eq. 6), both through the library, compared with
+    the oracle's scores and ranks."""
+    wl = SMALL["straddle_3f"]
+    low, high = generate(wl, seed=31), generate(wl, seed=32)
+    n, w = wl.n_tokens, wl.window
+    h = pk.purekv_budget(n, w, 0.2)
+    plan = pk.Plan.for_workload(wl, 0)
+    scores = []
+    for inp in (low, high):
+        q, k, v = to_dev(inp.q), to_dev(inp.k), to_dev(high.v)
+        _, lse = pk.purekv_st_spattn_prefill(plan, q, k, to_dev(inp.v), want_lse=True)
+        c = pk.purekv_lowlayer_importance(plan, q, k, lse, w)
+        _, s = pk.purekv_topk_select(plan, c, v, w, h, want_scores=True)
+        scores.append(s.reshape(wl.n_kv_heads, n - w).contiguous())
+    d2, rho = pk.purekv_spearman(scores[0], scores[1])
+    torch.cuda.synchronize()
+    # the oracle on the library's own fp32 scores: exact; and on its own fp64 scores: the same rho up to the few keys
+    # whose order the fp32 rounding of nearly equal scores changes
+    ref_d2, ref_rho = orc.spearman_rank_correlation(f64_of(scores[0]), f64_of(scores[1]))
+    assert d2.cpu().numpy().tolist() == [int(x) for x in ref_d2] and np.array_equal(rho.cpu().numpy(), ref_rho)
+    vf = F64(high.v)
+    s_hat = orc.vnorm_scores(orc.window_column_sums(F64(low.q), F64(low.k), wl.n_frames, wl.patches, wl.n_text, 0, w), vf)
+    s_own = orc.vnorm_scores(orc.window_column_sums(F64(high.q), F64(high.k), wl.n_frames, wl.patches, wl.n_text, 0, w), vf)
+    _, rho64 = orc.spearman_rank_correlation(s_hat, s_own)
+    assert np.abs(rho.cpu().numpy() - rho64).max() < 1e-3
+    # the two layers' Q and K are independent draws here, but both score arrays carry the same V norms: the rankings
+    # agree more than chance (n ~ 1700 keys: chance is |rho| < 0.08 at three sigma)
+    assert (rho.cpu().numpy() > 0.08).all()
+
+
+def test_spearman_argument_errors():
+    a = torch.zeros((2, 8), dtype=torch.float32, device="cuda")
+    out = torch.zeros(2, dtype=torch.int64, device="cuda")
+    lib = pk.raw()
+    assert lib.purekv_spearman(a.data_ptr(), a.data_ptr(), 2, 1, out.data_ptr(), None, None) == pk.EINVAL
+    assert lib.purekv_spearman(a.data_ptr(), a.data_ptr(), 2, 131073, out.data_ptr(), None, None) == pk.EINVAL
+    assert lib.purekv_spearman(a.data_ptr(), a.data_ptr(), 0, 8, out.data_ptr(), None, None) == pk.EINVAL
+    assert lib.purekv_spearman(None, a.data_ptr(), 2, 8, out.data_ptr(), None, None) == pk.EINVAL
+    assert lib.purekv_spearman(a.data_ptr(), a.data_ptr(), 2, 8, None, None, None) == pk.EINVAL
+    assert lib.purekv_spearman(a.data_ptr(), a.data_ptr(), 2, 8, out.data_ptr(), None, None) == pk.OK   # rho is optional
+    torch.cuda.synchronize()
+    assert out.tolist() == [0, 0]

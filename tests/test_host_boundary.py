@@ -115,6 +115,16 @@ def test_compute_calls_validate_before_touching_the_gpu():
     assert lib.purekv_plan_item(h, -1, (ctypes.c_int32 * 6)()) == pk.EINVAL
 
 
+def test_spearman_validates_before_touching_the_gpu():
+    lib = pk.raw()
+    buf = (ctypes.c_float * 8)()
+    out = (ctypes.c_uint64 * 2)()
+    for args in [(None, buf, 1, 8, out), (buf, None, 1, 8, out), (buf, buf, 1, 8, None), (buf, buf, 0, 8, out),
+                 (buf, buf, 70000, 8, out), (buf, buf, 1, 1, out), (buf, buf, 1, 131073, out)]:
+        a = [ctypes.cast(x, ctypes.c_void_p) if x is not None and not isinstance(x, int) else x for x in args]
+        assert lib.purekv_spearman(a[0], a[1], a[2], a[3], a[4], None, None) == pk.EINVAL
+
+
 def test_budget_matches_oracle_rule():
     rng = np.random.default_rng(0)
     for _ in range(2000):
