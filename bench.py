@@ -208,7 +208,7 @@ def main() -> int:
     ap.add_argument("--stack-dense", type=int, default=0, help="dense low layers of the --stack run (default: the "
                     "workload's, else 1); the last of them estimates the importance")
     ap.add_argument("--only-stage", default=None,
-                    choices=STAGES + ["copy_calib", "topk_batched", "compact_batched", "mfma_calib", "whole_path"],
+                    choices=STAGES + ["copy_calib", "topk_batched", "compact_batched", "spearman_batched", "mfma_calib", "whole_path"],
                     help="profiling aid: after one full warm-up step run only this stage --steps times and exit")
     ap.add_argument("--profile-summary", default=None, metavar="DIR",
                     help="no GPU work: turn the rocprofv3 CSV output under DIR (produced by the commands this prints with "
@@ -431,6 +431,9 @@ def main() -> int:
         if args.only_stage == "copy_calib":
             calib_src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
             calib_dst = torch.empty_like(calib_src)
+        if args.only_stage == "spearman_batched":   # 26 layers x Hkv rows of N - w scores, correlated pairs
+            sp_a = torch.randn((args.batched_layers * hkv, n - w), dtype=torch.float32, device=dev)
+            sp_b = 0.5 * sp_a + torch.randn_like(sp_a)
         stages = {
             "dense_prefill": lambda: pk.purekv_st_spattn_prefill(dense, q0, k0, v0, out=out0, lse=lse),
             "importance": lambda: pk.purekv_lowlayer_importance(dense, q0, k0, lse, w, c_out=c),
@@ -444,6 +447,7 @@ def main() -> int:
             "copy_calib": lambda: calib_dst.copy_(calib_src),
             "topk_batched": lambda: pk.purekv_topk_select(st_packed, c, v_all, w, h, idx_out=idx_all),
             "compact_batched": lambda: pk.purekv_kv_compact(st_packed, k_all, v_all, idx_all, kc=kc_all, vc=vc_all),
+            "spearman_batched": lambda: pk.purekv_spearman(sp_a, sp_b),
         }
         one = stages[args.only_stage]
         for _ in range(args.steps):

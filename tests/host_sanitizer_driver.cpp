@@ -256,6 +256,13 @@ int main() {
       for (int pct = 0; pct <= 100; pct += 5) CHECK(purekv_budget(n, 0, pct / 100.0) == (int32_t)((int64_t)pct * n / 100));
     CHECK(purekv_budget(100, 10, 0.0 / 0.0) == -1 && purekv_budget(100, 10, 2.0) == -1 && purekv_budget(-5, 0, 0.5) == -1);
     CHECK(purekv_workspace_bytes(nullptr, 0, 0, 0, 0) == 0);
+    float two[2] = {0.f, 1.f};
+    uint64_t acc = 0;
+    CHECK(purekv_spearman(nullptr, two, 1, 2, &acc, nullptr, nullptr) == PUREKV_EINVAL);
+    CHECK(purekv_spearman(two, two, 1, 2, nullptr, nullptr, nullptr) == PUREKV_EINVAL);
+    CHECK(purekv_spearman(two, two, 0, 2, &acc, nullptr, nullptr) == PUREKV_EINVAL);
+    CHECK(purekv_spearman(two, two, 1, 1, &acc, nullptr, nullptr) == PUREKV_EINVAL);
+    CHECK(purekv_spearman(two, two, 1, 131073, &acc, nullptr, nullptr) == PUREKV_EINVAL);
   }
   std::printf("host sanitizer driver: %ld plans inspected, all checks passed\n", g_plans);
   return 0;
