@@ -93,6 +93,33 @@ def test_strided_layouts_equal_packed_bit_for_bit(name, pattern, layout):
     assert np.array_equal(bits_of(kc_s), kr) and np.array_equal(bits_of(vc_s), vr)
 
 
+@pytest.mark.parametrize("pattern", [0, 3])
+def test_window_plan_on_a_token_major_layout_equals_packed(pattern):
+    """A divided window plan (more units than workgroups) on token-major views: the same bits as the packed window
+    plan, the log-sum-exp of the window rows only."""
+    wl = small_variant("manyunits_g2", n_frames=7, patch_h=15, patch_w=20, n_text=120, n_q_heads=32, n_kv_heads=16,
+                       head_dim=64)
+    inp = generate(wl, seed=23)
+    n, w = wl.n_tokens, 1
+    q, k, v = to_dev(inp.q), to_dev(inp.k), to_dev(inp.v)
+    packed_plan = pk.Plan.for_workload(wl, pattern, lse_window=w)
+    assert packed_plan.counts()["lse_queue0"] > 0
+    lse_p = torch.full((wl.n_q_heads, n), -7.0, dtype=torch.float32, device="cuda")
+    out_p, _ = pk.purekv_st_spattn_prefill(packed_plan, q, k, v, lse=lse_p)
+    qv, kv, vv, strides = token_major(wl, q, k, v)
+    plan = pk.Plan.for_workload(wl, pattern, lse_window=w, **strides)
+    assert plan.counts()["lse_queue0"] == packed_plan.counts()["lse_queue0"]
+    out_s = plan.empty_out(q.device)
+    lse_s = torch.full_like(lse_p, -7.0)
+    pk.purekv_st_spattn_prefill(plan, qv, kv, vv, out=out_s, lse=lse_s)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(out_s), bits_of(out_p)) and torch.equal(lse_s, lse_p)
+    assert (lse_s[:, :n - w] == -7.0).all() and (lse_s[:, n - w:] != -7.0).all()
+    ref, ref_lse = orc.masked_attention(F64(inp.q), F64(inp.k), F64(inp.v), wl.n_frames, wl.patches, wl.n_text, pattern)
+    check_attention(f64_of(out_p), ref, f"window token-major p{pattern}")
+    assert np.abs(f64_of(lse_s)[:, n - w:] - ref_lse[:, n - w:]).max() < 2e-3
+
+
 def test_token_major_layer_stack_equals_packed():
     """The stack entry points on token-major layers [L, N, Hkv, d] (layer stride = one layer's span)."""
     wl = small_variant("straddle_3f", n_frames=3, patch_h=24, patch_w=24, n_text=70, n_q_heads=4, n_kv_heads=1,
