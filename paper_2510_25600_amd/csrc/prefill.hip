@@ -367,12 +367,24 @@ __device__ __forceinline__ void prefill_body(const PrefillArgs& a) {
       // uniform base of the head + 32-bit lane offsets (a tensor spans at most 2^31 bytes); the row is clamped to
       // the last row of the sequence, also when the whole block lies past it (ragged last query tile)
       const char* const qhead = reinterpret_cast<const char*>(a.q) + (int64_t)((int)un[1] + hl) * a.q_head_bytes;
+      if constexpr (D == 128) {
+        // piece i of this lane: row 4 i + ln / 16, slot (ln % 16) ^ (row % 16) = (ln % 16) ^ (ln / 16) ^ (4 i % 16):
+        // one lane constant, then per piece a row (add, clamp, multiply) and one xor-add
+        const int row_l = r0 + (ln >> 4);
+        const uint32_t slot_l = (uint32_t)(((ln & 15) ^ (ln >> 4)) * 16);
 #pragma unroll
-      for (int i = 0; i < XQ; ++i) {
-        int r, u;
-        kunswz<D>(i * 64 + ln, r, u);
-        const uint32_t off = (uint32_t)min(r0 + r, a.N - 1) * a.q_row_bytes + (uint32_t)u * 16u;
-        load_to_lds_16(qhead, off, Xs + i * 512);
+        for (int i = 0; i < XQ; ++i) {
+          const uint32_t off = (uint32_t)min(row_l + 4 * i, a.N - 1) * a.q_row_bytes + (slot_l ^ (uint32_t)(((4 * i) & 15) * 16));
+          load_to_lds_16(qhead, off, Xs + i * 512);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < XQ; ++i) {
+          int r, u;
+          kunswz<D>(i * 64 + ln, r, u);
+          const uint32_t off = (uint32_t)min(r0 + r, a.N - 1) * a.q_row_bytes + (uint32_t)u * 16u;
+          load_to_lds_16(qhead, off, Xs + i * 512);
+        }
       }
     }
   };
