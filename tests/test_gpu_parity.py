@@ -573,6 +573,43 @@ def test_prefill_random_shapes_sweep():
         assert np.abs(f64_of(lse) - ref_lse).max() < 2e-3
 
 
+def test_window_plan_random_shapes_sweep():
+    """Seeded sweep of window plans with more units than workgroups (many heads on short sequences), so that most of
+    them are divided: outputs and the window's log-sum-exp against the oracle, every other element of lse untouched,
+    output bits equal to the undivided plan's where both run a row's list whole."""
+    rng = np.random.default_rng(25601)
+    divided = 0
+    for case in range(10):
+        ph, pw = int(rng.integers(4, 14)), int(rng.integers(4, 14))
+        F = max(2, int(rng.integers(900, 1600)) // (ph * pw))
+        T = int(rng.choice([0, 5, 40, 129]))
+        hkv, g = [(8, 7), (16, 4), (12, 7)][int(rng.integers(0, 3))]
+        d = int(rng.choice([64, 128]))
+        pattern = int(rng.choice([0, 1, 3, 3]))
+        wl = small_variant(f"wsweep{case}", n_frames=F, patch_h=ph, patch_w=pw, n_text=T, n_q_heads=hkv * g,
+                           n_kv_heads=hkv, head_dim=d)
+        n = wl.n_tokens
+        w = int(rng.integers(1, 48))
+        inp = generate(wl, seed=300 + case)
+        plan, whole = pk.Plan.for_workload(wl, pattern, lse_window=w), pk.Plan.for_workload(wl, pattern)
+        c = plan.counts()
+        divided += c["lse_queue0"] > 0
+        print(f"[case] window sweep {case}: F={F} P={ph}x{pw} T={T} heads {hkv * g}/{hkv} d={d} pattern={pattern} w={w} "
+              f"N={n} lse_queue0={c['lse_queue0']}", flush=True)
+        q, k, v = to_dev(inp.q), to_dev(inp.k), to_dev(inp.v)
+        lse = torch.full((wl.n_q_heads, n), 7.5, dtype=torch.float32, device="cuda")
+        out, _ = pk.purekv_st_spattn_prefill(plan, q, k, v, lse=lse)
+        out_whole = pk.purekv_st_spattn_prefill(whole, q, k, v)
+        torch.cuda.synchronize()
+        ref, ref_lse = orc.masked_attention(F64(inp.q), F64(inp.k), F64(inp.v), F, ph * pw, T, pattern)
+        check_attention(f64_of(out), ref, f"window sweep {case}")
+        got = f64_of(lse)
+        assert np.all(got[:, :n - w] == 7.5) and np.abs(got[:, n - w:] - ref_lse[:, n - w:]).max() < 2e-3
+        if c["n_split_qtiles"] == 0 and whole.counts()["n_split_qtiles"] == 0:
+            assert np.array_equal(bits_of(out), bits_of(out_whole))
+    assert divided >= 5, divided   # (a plan stays whole when the window's tiles are over a quarter of the work)
+
+
 def test_importance_random_shapes_sweep():
     """Seeded sweep of the column sums: window sizes from one row to the whole sequence (text rows only, video rows
     under a mask, windows that are not a multiple of the 32-row block), odd frame sizes, 1..7 heads per KV head."""
