@@ -208,7 +208,7 @@ def main() -> int:
     ap.add_argument("--stack-dense", type=int, default=0, help="dense low layers of the --stack run (default: the "
                     "workload's, else 1); the last of them estimates the importance")
     ap.add_argument("--only-stage", default=None,
-                    choices=STAGES + ["copy_calib", "topk_batched", "compact_batched", "spearman_batched", "mfma_calib", "whole_path"],
+                    choices=STAGES + ["copy_calib", "topk_batched", "compact_batched", "spearman_batched", "dense_prefill_all_rows_lse", "mfma_calib", "whole_path"],
                     help="profiling aid: after one full warm-up step run only this stage --steps times and exit")
     ap.add_argument("--profile-summary", default=None, metavar="DIR",
                     help="no GPU work: turn the rocprofv3 CSV output under DIR (produced by the commands this prints with "
@@ -434,7 +434,10 @@ def main() -> int:
         if args.only_stage == "spearman_batched":   # 26 layers x Hkv rows of N - w scores, correlated pairs
             sp_a = torch.randn((args.batched_layers * hkv, n - w), dtype=torch.float32, device=dev)
             sp_b = 0.5 * sp_a + torch.randn_like(sp_a)
+        if args.only_stage == "dense_prefill_all_rows_lse":   # the low layer on a plain plan: every row's log-sum-exp
+            dense_all = pk.Plan.for_workload(wl, pk.PATTERN_DENSE)
         stages = {
+            "dense_prefill_all_rows_lse": lambda: pk.purekv_st_spattn_prefill(dense_all, q0, k0, v0, out=out0, lse=lse),
             "dense_prefill": lambda: pk.purekv_st_spattn_prefill(dense, q0, k0, v0, out=out0, lse=lse),
             "importance": lambda: pk.purekv_lowlayer_importance(dense, q0, k0, lse, w, c_out=c),
             "topk_low": lambda: pk.purekv_topk_select(dense, c, v0, w, h, idx_out=idx0),
